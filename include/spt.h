@@ -1,0 +1,188 @@
+/*
+ * spt.h - C ABI of libspt: sparse tensor algebra kernels executed directly on
+ * tensors described as coordinate hierarchies, one level format per dimension
+ * (paper Section 3.1: dense, compressed, singleton, range, offset, hashed).
+ *
+ * Target: one AMD MI355X (gfx950). Every data pointer in this interface is a
+ * DEVICE pointer unless its comment says "host". The structs themselves
+ * (spt_tensor, spt_level) live in HOST memory and are read only during the
+ * call. `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *
+ * Ownership: the caller owns every buffer. The library never allocates or
+ * frees device memory and keeps no state between calls; scratch memory comes
+ * from the caller-supplied workspace `ws`, whose required size is returned by
+ * spt_workspace_bytes(). `ws` must be 256-byte aligned. Calls enqueue work on
+ * `stream` and return without synchronising.
+ *
+ * Errors: every entry point returns an spt_status. Only host-checkable
+ * conditions are diagnosed (null pointers, unknown level kinds, illegal
+ * kind/property combinations per Table 1, level compositions that are not
+ * recognised, sizes that overflow int32 positions, workspace too small).
+ * Device-side content (monotone pos, in-range crd) is NOT validated.
+ * spt_last_error() returns a thread-local human readable message for the
+ * last failing call on this thread.
+ */
+#ifndef SPT_H
+#define SPT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SPT_OK = 0,
+  SPT_ERR_INVALID_ARG = 1,
+  SPT_ERR_UNSUPPORTED = 2,
+  SPT_ERR_WORKSPACE = 3,
+  SPT_ERR_DEVICE = 4
+} spt_status;
+
+/* The six level formats of Section 3.1 / Table 2. */
+typedef enum {
+  SPT_DENSE = 0,      /* coordinates [0,N); child position p*N + i            */
+  SPT_COMPRESSED = 1, /* children of p are crd[pos[p] .. pos[p+1])            */
+  SPT_SINGLETON = 2,  /* one child per parent at the same position: crd[p]    */
+  SPT_RANGE = 3,      /* coordinates [max(0,-offset[d]), min(N, M-offset[d])) */
+  SPT_OFFSET = 4,     /* one child per parent: parent coordinate + offset[d]  */
+  SPT_HASHED = 5      /* segment of width M (=W) of an open-addressed table   */
+} spt_level_kind;
+
+typedef enum { SPT_F32 = 0, SPT_F64 = 1 } spt_dtype;
+
+/* Level properties that are configurable per level (Section 3.3, Table 1).
+ * full / branchless / compact follow from the kind. */
+enum { SPT_ORDERED = 1, SPT_UNIQUE = 2 };
+
+/* Entry order of the CSR produced by spt_coo_to_csr (the paper does not
+ * describe the conversion; both orders are total and deterministic):
+ *   ROW_COL    rows ascending, columns ascending inside a row, equal
+ *              (row,col) pairs keep their input order (sorted CSR, the
+ *              paper's default: ordered column level, Figure 4 caption).
+ *   ROW_STABLE rows ascending, input order kept inside a row.
+ * Duplicates are kept, never summed. */
+typedef enum { SPT_ORDER_ROW_COL = 0, SPT_ORDER_ROW_STABLE = 1 } spt_order;
+
+typedef enum {
+  SPT_OP_SPMV = 0,
+  SPT_OP_COO_TO_CSR = 1,
+  SPT_OP_TTV = 2,
+  SPT_OP_MTTKRP = 3
+} spt_op;
+
+/*
+ * One coordinate hierarchy level (Section 3.1).
+ *   kind   spt_level_kind
+ *   mode   tensor dimension this level encodes (0-based), or -1 for a level
+ *          that encodes no tensor dimension (DIA's diagonal index, ELL's slot)
+ *   flags  SPT_ORDERED | SPT_UNIQUE
+ *   N      dense/range: N_k of Table 2 (extent used in p*N+i);
+ *          compressed/singleton/offset/hashed: size of the tensor dimension
+ *   M      range: M_k of Table 2 (extent of the child dimension, DIA: #cols);
+ *          hashed: W_k (table width per parent);
+ *          compressed: number of parent positions (1 for a root level, #rows
+ *          for CSR's column level, #entries of the level above for CSF);
+ *          else 0
+ *   pos    compressed: M + 1 int32 entries; else NULL
+ *   crd    compressed/singleton/hashed: int32 coordinates; else NULL.
+ *          A negative singleton coordinate marks padding (ELL) and the
+ *          position is skipped, as the hashed level skips -1.
+ *   offset range/offset: int32 offsets indexed by the coordinate of the
+ *          enclosing diagonal level (DIA passes the same array to both)
+ */
+typedef struct {
+  int32_t kind;
+  int32_t mode;
+  int32_t flags;
+  int32_t reserved;
+  int64_t N;
+  int64_t M;
+  const int32_t* pos;
+  const int32_t* crd;
+  const int32_t* offset;
+} spt_level;
+
+/*
+ * A tensor = `order` tensor dimensions stored as `nlevels` levels, outermost
+ * first, plus one contiguous values array with one entry per leaf position.
+ * Recognised compositions (D dense, C compressed, S singleton, R range,
+ * O offset; ~U = not flagged unique):
+ *   CSR   (D rows, C cols)                        vals[nnz]
+ *   COO   (C~U rows with pos=[0,nnz], S cols)     vals[nnz]
+ *   DIA   (D diagonals K, R rows, O cols)         vals[K*N], cell (d,i) at d*N+i
+ *   ELL   (D slots W, D rows, S cols)             vals[W*N], cell (k,i) at k*N+i
+ *   COO3  (C~U, S~U, S)                           vals[nnz]
+ *   CSF3  (C, C, C)                               vals[nnz]
+ * Everything else returns SPT_ERR_UNSUPPORTED from the four operations.
+ */
+typedef struct {
+  int32_t order;   /* number of tensor dimensions (2 or 3) */
+  int32_t nlevels; /* number of levels (2..4) */
+  int32_t dtype;   /* spt_dtype of vals and of every dense operand */
+  int32_t reserved;
+  spt_level level[4];
+  const void* vals;
+  int64_t nvals; /* number of entries of vals */
+} spt_tensor;
+
+/*
+ * y = A x (Section 5.2, SpMV on COO/CSR/DIA/ELL). x: dense, one entry per
+ * column; y: dense, one entry per row, OVERWRITTEN (rows without entries get
+ * 0). Every stored entry counts (duplicates add up). COO flagged SPT_ORDERED
+ * on its row level runs a deterministic segmented reduction; without the flag
+ * the entries are accumulated with floating-point atomics (any order).
+ */
+spt_status spt_spmv(const spt_tensor* A, const void* x, void* y, void* ws,
+                    size_t ws_bytes, void* stream);
+
+/*
+ * COO -> CSR (the conversion of Section 5.4 / Figure 14; pos is assembled as
+ * Table 3's append_edges + append_finalize: per-row counts, then prefix sum).
+ * pos_out[N+1], crd_out[nnz], vals_out[nnz]. If both COO levels are flagged
+ * SPT_ORDERED the sort is skipped. Index outputs are exact.
+ */
+spt_status spt_coo_to_csr(const spt_tensor* A_coo, int32_t order /*spt_order*/,
+                          int32_t* pos_out, int32_t* crd_out, void* vals_out,
+                          void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * TTV, A_ij = sum_k B_ijk c_k (Section 5.3), contracting the dimension of B's
+ * last level with the dense vector c. B must be ordered.
+ *  COO3 input: output is COO sorted by (i,j) with one entry per distinct (i,j)
+ *    that has a stored entry: out_crd0/out_crd1/out_vals have capacity nnz,
+ *    *out_nnz_dev (device int64) receives the number of entries.
+ *  CSF3 input: the output shares B's two upper levels; out_vals has one entry
+ *    per position of level 1 (= B.level[2].M entries); out_crd0/out_crd1 are
+ *    ignored and may be NULL; *out_nnz_dev receives that count if non-NULL.
+ */
+spt_status spt_ttv(const spt_tensor* B, const void* c, int32_t* out_crd0,
+                   int32_t* out_crd1, void* out_vals, int64_t* out_nnz_dev,
+                   void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * MTTKRP, A_ij = sum_kl B_ikl C_kj D_lj (Section 5.3), output dimension = the
+ * dimension of B's first level. C: (dim of level 1) x J, D: (dim of level 2)
+ * x J, A_out: (dim of level 0) x J, all dense row-major, A_out OVERWRITTEN
+ * (rows without entries get 0). B is COO3 or CSF3, ordered. 1 <= J <= 1024.
+ */
+spt_status spt_mttkrp(const spt_tensor* B, const void* C, const void* D,
+                      int32_t J, void* A_out, void* ws, size_t ws_bytes,
+                      void* stream);
+
+/* Workspace size in bytes for `op` on tensor T (J only for MTTKRP).
+ * Returns 0 for invalid descriptors (spt_last_error says why). Never fails for
+ * a valid one; the result is always >= 256. */
+size_t spt_workspace_bytes(int32_t op, const spt_tensor* T, int32_t J);
+
+/* Thread-local message of the last error raised on this thread ("" if none). */
+const char* spt_last_error(void);
+
+/* Library version string, e.g. "spt 0.1 gfx950". */
+const char* spt_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPT_H */

@@ -1,0 +1,279 @@
+"""ctypes binding of the CPU oracle (oracle.c). TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg import this
+package; the GPU library never does. `build()` compiles oracle.c with gcc into
+liboracle.so next to this file; `lib()` loads it, building first only if no
+built library exists.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    if force or not os.path.exists(_SO):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _SO, os.path.join(_HERE, "oracle.c"), "-lm"]
+        subprocess.run(cmd, check=True)
+    return _SO
+
+
+class OrcLevel(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("mode", C.c_int32), ("N", C.c_int64),
+                ("M", C.c_int64), ("pos", C.c_void_p), ("crd", C.c_void_p),
+                ("offset", C.c_void_p)]
+
+
+class OrcTensor(C.Structure):
+    _fields_ = [("order", C.c_int32), ("nlevels", C.c_int32), ("is_f64", C.c_int32),
+                ("pad", C.c_int32), ("lvl", OrcLevel * 4), ("vals", C.c_void_p)]
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        L = C.CDLL(_SO)
+        vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int32
+        L.orc_level_children.restype = i64
+        L.orc_level_children.argtypes = [vp, i64, i64, i64, vp, vp, i64]
+        L.orc_hashed_locate.restype = i64
+        L.orc_hashed_locate.argtypes = [vp, i64, i64, vp]
+        L.orc_count.restype = i64
+        L.orc_count.argtypes = [vp]
+        L.orc_to_coo.restype = None
+        L.orc_to_coo.argtypes = [vp, vp, vp]
+        L.orc_spmv.restype = None
+        L.orc_spmv.argtypes = [vp, vp, i64, vp, vp]
+        L.orc_coo_to_csr.restype = None
+        L.orc_coo_to_csr.argtypes = [i64, i64, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+        L.orc_ttv.restype = i64
+        L.orc_ttv.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+        L.orc_mttkrp.restype = None
+        L.orc_mttkrp.argtypes = [vp, vp, vp, i32, i64, vp, vp]
+        L.orc_plain_spmv_csr.restype = None
+        L.orc_plain_spmv_csr.argtypes = [i64, vp, vp, vp, vp, vp, i32]
+        L.orc_plain_spmv_coo.restype = None
+        L.orc_plain_spmv_coo.argtypes = [i64, i64, vp, vp, vp, vp, vp, i32]
+        L.orc_plain_spmv_dia.restype = None
+        L.orc_plain_spmv_dia.argtypes = [i64, i64, i64, vp, vp, vp, vp, i32]
+        L.orc_plain_spmv_ell.restype = None
+        L.orc_plain_spmv_ell.argtypes = [i64, i64, vp, vp, vp, vp, i32]
+        L.orc_plain_ttv_coo.restype = i64
+        L.orc_plain_ttv_coo.argtypes = [i64, vp, vp, vp, vp, vp, vp, vp, vp, i32]
+        L.orc_plain_ttv_csf.restype = None
+        L.orc_plain_ttv_csf.argtypes = [i64, vp, vp, vp, vp, vp, i32]
+        L.orc_plain_mttkrp_coo.restype = None
+        L.orc_plain_mttkrp_coo.argtypes = [i64, i64, vp, vp, vp, vp, vp, vp, i32, vp, i32]
+        L.orc_plain_mttkrp_csf.restype = None
+        L.orc_plain_mttkrp_csf.argtypes = [i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, i32]
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data
+
+
+def _is_f64(dtype) -> int:
+    if dtype == np.float64:
+        return 1
+    if dtype == np.float32:
+        return 0
+    raise TypeError(f"oracle supports float32/float64 values, got {dtype}")
+
+
+class OTensor:
+    """Holds an OrcTensor plus the numpy arrays it points into."""
+
+    def __init__(self, spec):
+        self.spec = spec
+        self.keep = []
+        t = OrcTensor()
+        t.order = spec.order
+        t.nlevels = len(spec.levels)
+        t.is_f64 = _is_f64(spec.vals.dtype)
+        for k, lv in enumerate(spec.levels):
+            o = t.lvl[k]
+            o.kind, o.mode, o.N, o.M = lv.kind, lv.mode, lv.N, lv.M
+            for name in ("pos", "crd", "offset"):
+                a = getattr(lv, name)
+                if a is not None:
+                    a = np.ascontiguousarray(a, dtype=np.int32)
+                    self.keep.append(a)
+                    setattr(o, name, a.ctypes.data)
+        v = np.ascontiguousarray(spec.vals)
+        self.keep.append(v)
+        t.vals = v.ctypes.data
+        self.c = t
+
+    @property
+    def ref(self):
+        return C.addressof(self.c)
+
+
+def _same_dtype(spec, a):
+    a = np.ascontiguousarray(a)
+    if a.dtype != spec.vals.dtype:
+        raise TypeError("dense operand dtype must match the tensor's values")
+    return a
+
+
+def level_children(level_spec, p_parent, i_parent=0, i_grand=0):
+    """(coordinates, positions) of the children of one parent, per Table 2."""
+    t = OrcLevel()
+    keep = []
+    t.kind, t.mode, t.N, t.M = level_spec.kind, level_spec.mode, level_spec.N, level_spec.M
+    for name in ("pos", "crd", "offset"):
+        a = getattr(level_spec, name)
+        if a is not None:
+            a = np.ascontiguousarray(a, dtype=np.int32)
+            keep.append(a)
+            setattr(t, name, a.ctypes.data)
+    n = lib().orc_level_children(C.addressof(t), p_parent, i_parent, i_grand, None, None, 0)
+    oi = np.zeros(max(n, 1), np.int64)
+    op = np.zeros(max(n, 1), np.int64)
+    lib().orc_level_children(C.addressof(t), p_parent, i_parent, i_grand, _ptr(oi), _ptr(op), n)
+    return oi[:n], op[:n]
+
+
+def hashed_locate(level_spec, p_parent, i):
+    t = OrcLevel()
+    t.kind, t.mode, t.N, t.M = level_spec.kind, level_spec.mode, level_spec.N, level_spec.M
+    crd = np.ascontiguousarray(level_spec.crd, dtype=np.int32)
+    t.crd = crd.ctypes.data
+    found = C.c_int32(0)
+    p = lib().orc_hashed_locate(C.addressof(t), p_parent, i, C.addressof(found))
+    return int(p), bool(found.value)
+
+
+def to_coo(spec):
+    """All stored leaves in storage order: (coords[order, n] int64, vals[n] float64)."""
+    T = OTensor(spec)
+    n = lib().orc_count(T.ref)
+    coords = np.zeros((spec.order, max(n, 1)), np.int64)
+    vals = np.zeros(max(n, 1), np.float64)
+    if n:
+        # the C side indexes coords_out[m*count + n]
+        coords = np.zeros((spec.order, n), np.int64)
+        vals = np.zeros(n, np.float64)
+        lib().orc_to_coo(T.ref, _ptr(coords), _ptr(vals))
+    return coords[:, :n], vals[:n]
+
+
+def spmv(spec, x):
+    """Reference y = A x as float64, plus the magnitude sum per row."""
+    T = OTensor(spec)
+    x = _same_dtype(spec, x)
+    rows = spec.dims[0]
+    y = np.zeros(rows, np.float64)
+    mag = np.zeros(rows, np.float64)
+    lib().orc_spmv(T.ref, _ptr(x), rows, _ptr(y), _ptr(mag))
+    return y, mag
+
+
+def coo_to_csr(nrows, row, col, vals, order=0):
+    row = np.ascontiguousarray(row, dtype=np.int32)
+    col = np.ascontiguousarray(col, dtype=np.int32)
+    vals = np.ascontiguousarray(vals)
+    nnz = len(row)
+    pos = np.zeros(nrows + 1, np.int32)
+    crd = np.zeros(nnz, np.int32)
+    vout = np.zeros(nnz, vals.dtype)
+    perm = np.zeros(nnz, np.int64)
+    lib().orc_coo_to_csr(nnz, nrows, _ptr(row), _ptr(col), _ptr(vals), vals.dtype.itemsize,
+                         order, _ptr(pos), _ptr(crd), _ptr(vout), _ptr(perm))
+    return pos, crd, vout, perm
+
+
+def ttv(spec, c):
+    T = OTensor(spec)
+    c = _same_dtype(spec, c)
+    cap = max(lib().orc_count(T.ref), 1)
+    oi = np.zeros(cap, np.int32)
+    oj = np.zeros(cap, np.int32)
+    ov = np.zeros(cap, np.float64)
+    om = np.zeros(cap, np.float64)
+    n = lib().orc_ttv(T.ref, _ptr(c), cap, _ptr(oi), _ptr(oj), _ptr(ov), _ptr(om))
+    return oi[:n], oj[:n], ov[:n], om[:n]
+
+
+def mttkrp(spec, Cm, Dm):
+    T = OTensor(spec)
+    Cm = _same_dtype(spec, Cm)
+    Dm = _same_dtype(spec, Dm)
+    J = Cm.shape[1]
+    I = spec.dims[0]
+    A = np.zeros((I, J), np.float64)
+    mag = np.zeros((I, J), np.float64)
+    lib().orc_mttkrp(T.ref, _ptr(Cm), _ptr(Dm), J, I, _ptr(A), _ptr(mag))
+    return A, mag
+
+
+# ---- plain per-format loops (native dtype); spec must be the named format ----
+
+def plain_spmv(spec, x, fmt):
+    x = _same_dtype(spec, x)
+    f = _is_f64(spec.vals.dtype)
+    N, M = spec.dims
+    y = np.zeros(N, spec.vals.dtype)
+    lv = spec.levels
+    L = lib()
+    if fmt == "csr":
+        L.orc_plain_spmv_csr(N, _ptr(lv[1].pos), _ptr(lv[1].crd), _ptr(spec.vals), _ptr(x), _ptr(y), f)
+    elif fmt == "coo":
+        L.orc_plain_spmv_coo(N, len(spec.vals), _ptr(lv[0].crd), _ptr(lv[1].crd), _ptr(spec.vals),
+                             _ptr(x), _ptr(y), f)
+    elif fmt == "dia":
+        L.orc_plain_spmv_dia(N, M, lv[0].N, _ptr(lv[1].offset), _ptr(spec.vals), _ptr(x), _ptr(y), f)
+    elif fmt == "ell":
+        L.orc_plain_spmv_ell(N, lv[0].N, _ptr(lv[2].crd), _ptr(spec.vals), _ptr(x), _ptr(y), f)
+    else:
+        raise ValueError(fmt)
+    return y
+
+
+def plain_ttv(spec, c, fmt):
+    c = _same_dtype(spec, c)
+    f = _is_f64(spec.vals.dtype)
+    lv = spec.levels
+    L = lib()
+    if fmt == "coo":
+        nnz = len(spec.vals)
+        oi = np.zeros(max(nnz, 1), np.int32)
+        oj = np.zeros(max(nnz, 1), np.int32)
+        ov = np.zeros(max(nnz, 1), spec.vals.dtype)
+        n = L.orc_plain_ttv_coo(nnz, _ptr(lv[0].crd), _ptr(lv[1].crd), _ptr(lv[2].crd),
+                                _ptr(spec.vals), _ptr(c), _ptr(oi), _ptr(oj), _ptr(ov), f)
+        return oi[:n], oj[:n], ov[:n]
+    nfib = len(lv[1].crd)
+    ov = np.zeros(max(nfib, 1), spec.vals.dtype)
+    L.orc_plain_ttv_csf(nfib, _ptr(lv[2].pos), _ptr(lv[2].crd), _ptr(spec.vals), _ptr(c), _ptr(ov), f)
+    return ov[:nfib]
+
+
+def plain_mttkrp(spec, Cm, Dm, fmt):
+    Cm = _same_dtype(spec, Cm)
+    Dm = _same_dtype(spec, Dm)
+    f = _is_f64(spec.vals.dtype)
+    J = Cm.shape[1]
+    I = spec.dims[0]
+    A = np.zeros((I, J), spec.vals.dtype)
+    lv = spec.levels
+    L = lib()
+    if fmt == "coo":
+        L.orc_plain_mttkrp_coo(len(spec.vals), I, _ptr(lv[0].crd), _ptr(lv[1].crd), _ptr(lv[2].crd),
+                               _ptr(spec.vals), _ptr(Cm), _ptr(Dm), J, _ptr(A), f)
+    else:
+        L.orc_plain_mttkrp_csf(I, _ptr(lv[0].pos), _ptr(lv[0].crd), _ptr(lv[1].pos), _ptr(lv[1].crd),
+                               _ptr(lv[2].pos), _ptr(lv[2].crd), _ptr(spec.vals), _ptr(Cm), _ptr(Dm),
+                               J, _ptr(A), f)
+    return A

@@ -1,0 +1,544 @@
+/*
+ * oracle.c - plain CPU reference for the sparse tensor kernels (see oracle.h).
+ * TEST INFRASTRUCTURE ONLY: slow on purpose, independent of the GPU library.
+ *
+ * Part 1 interprets the six level formats exactly as Table 2 of the paper
+ * defines their level functions, and walks a tensor with the two iteration
+ * templates of Figure 5 (coordinate value iteration for dense/range levels,
+ * coordinate position iteration for the others).
+ * Part 2 states each result (SpMV, COO->CSR, TTV, MTTKRP) by its definition
+ * on top of that walk, accumulating in long double (fp64 data) or double
+ * (fp32 data) and rounding once at the end.
+ * Part 3 holds the plain per-format loop nests that the paper's generated
+ * code amounts to (Section 5.2, 5.3); they are what the CPU baseline times.
+ */
+#include "oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------ */
+/* Part 1: level functions (Table 2) and the hierarchy walk (Figure 5) */
+/* ------------------------------------------------------------------ */
+
+static int64_t imax(int64_t a, int64_t b) { return a > b ? a : b; }
+static int64_t imin(int64_t a, int64_t b) { return a < b ? a : b; }
+
+/* coord_bounds of dense and range levels. */
+static void coord_bounds(const orc_level* L, int64_t i_parent, int64_t* lo,
+                         int64_t* hi) {
+  if (L->kind == ORC_DENSE) {
+    *lo = 0;
+    *hi = L->N;
+  } else { /* range: bounds from offset[i_{k-1}] and the sizes N_k, M_k */
+    int64_t off = L->offset[i_parent];
+    *lo = imax(0, -off);
+    *hi = imin(L->N, L->M - off);
+  }
+}
+
+/* coord_access of dense and range levels: p_k = p_{k-1} * N_k + i_k. */
+static int64_t coord_access(const orc_level* L, int64_t p_parent, int64_t i) {
+  return p_parent * L->N + i;
+}
+
+/* pos_bounds of compressed / singleton / offset / hashed levels. */
+static void pos_bounds(const orc_level* L, int64_t p_parent, int64_t* lo,
+                       int64_t* hi) {
+  switch (L->kind) {
+    case ORC_COMPRESSED:
+      *lo = L->pos[p_parent];
+      *hi = L->pos[p_parent + 1];
+      break;
+    case ORC_HASHED:
+      *lo = p_parent * L->M;
+      *hi = (p_parent + 1) * L->M;
+      break;
+    default: /* singleton, offset: exactly the parent's position */
+      *lo = p_parent;
+      *hi = p_parent + 1;
+  }
+}
+
+/* pos_access: coordinate stored at position p, and whether it is a child.
+ * Singleton follows Table 2 except that a negative coordinate is read as
+ * "unlabeled node" (ELL padding stored as -1), the same test the hashed level
+ * applies to its empty buckets. */
+static int pos_access(const orc_level* L, int64_t p, int64_t i_parent,
+                      int64_t i_grand, int64_t* i_out) {
+  switch (L->kind) {
+    case ORC_COMPRESSED:
+      *i_out = L->crd[p];
+      return 1;
+    case ORC_SINGLETON:
+      *i_out = L->crd[p];
+      return L->crd[p] >= 0;
+    case ORC_OFFSET: /* i_{k-1} + offset[i_{k-2}] */
+      *i_out = i_parent + L->offset[i_grand];
+      return 1;
+    default: /* hashed */
+      *i_out = L->crd[p];
+      return L->crd[p] != -1;
+  }
+}
+
+static int uses_coord_iteration(const orc_level* L) {
+  return L->kind == ORC_DENSE || L->kind == ORC_RANGE;
+}
+
+int64_t orc_level_children(const orc_level* L, int64_t p_parent, int64_t i_parent,
+                           int64_t i_grand, int64_t* out_i, int64_t* out_p,
+                           int64_t cap) {
+  int64_t n = 0, lo, hi;
+  if (uses_coord_iteration(L)) {
+    coord_bounds(L, i_parent, &lo, &hi);
+    for (int64_t i = lo; i < hi; ++i) {
+      if (n < cap) {
+        out_i[n] = i;
+        out_p[n] = coord_access(L, p_parent, i);
+      }
+      ++n;
+    }
+  } else {
+    pos_bounds(L, p_parent, &lo, &hi);
+    for (int64_t p = lo; p < hi; ++p) {
+      int64_t i;
+      if (pos_access(L, p, i_parent, i_grand, &i)) {
+        if (n < cap) {
+          out_i[n] = i;
+          out_p[n] = p;
+        }
+        ++n;
+      }
+    }
+  }
+  return n;
+}
+
+int64_t orc_hashed_locate(const orc_level* L, int64_t p_parent, int64_t i,
+                          int32_t* found) {
+  int64_t W = L->M;
+  int64_t p = i % W + p_parent * W;
+  if (L->crd[p] != i && L->crd[p] != -1) {
+    int64_t end = p;
+    do {
+      p = (p + 1) % W + p_parent * W;
+    } while (L->crd[p] != i && L->crd[p] != -1 && p != end);
+  }
+  *found = (L->crd[p] == i);
+  return p;
+}
+
+typedef struct {
+  const orc_tensor* T;
+  orc_visit_fn visit;
+  void* ctx;
+  int64_t lvl_coord[4];
+} walk_state;
+
+static void walk(walk_state* S, int k, int64_t p_parent) {
+  const orc_tensor* T = S->T;
+  if (k == T->nlevels) {
+    int64_t coords[4] = {0, 0, 0, 0};
+    for (int l = 0; l < T->nlevels; ++l)
+      if (T->lvl[l].mode >= 0) coords[T->lvl[l].mode] = S->lvl_coord[l];
+    S->visit(S->ctx, coords, p_parent);
+    return;
+  }
+  const orc_level* L = &T->lvl[k];
+  int64_t i_parent = k >= 1 ? S->lvl_coord[k - 1] : 0;
+  int64_t i_grand = k >= 2 ? S->lvl_coord[k - 2] : 0;
+  int64_t lo, hi;
+  if (uses_coord_iteration(L)) {
+    coord_bounds(L, i_parent, &lo, &hi);
+    for (int64_t i = lo; i < hi; ++i) {
+      S->lvl_coord[k] = i;
+      walk(S, k + 1, coord_access(L, p_parent, i));
+    }
+  } else {
+    pos_bounds(L, p_parent, &lo, &hi);
+    for (int64_t p = lo; p < hi; ++p) {
+      int64_t i;
+      if (pos_access(L, p, i_parent, i_grand, &i)) {
+        S->lvl_coord[k] = i;
+        walk(S, k + 1, p);
+      }
+    }
+  }
+}
+
+void orc_enumerate(const orc_tensor* T, orc_visit_fn visit, void* ctx) {
+  walk_state S;
+  S.T = T;
+  S.visit = visit;
+  S.ctx = ctx;
+  memset(S.lvl_coord, 0, sizeof S.lvl_coord);
+  walk(&S, 0, 0); /* one root parent at position 0 */
+}
+
+static double val_at(const orc_tensor* T, int64_t p) {
+  return T->is_f64 ? ((const double*)T->vals)[p] : (double)((const float*)T->vals)[p];
+}
+static double dense_at(const void* a, int is_f64, int64_t n) {
+  return is_f64 ? ((const double*)a)[n] : (double)((const float*)a)[n];
+}
+
+static void count_visit(void* ctx, const int64_t* c, int64_t p) {
+  (void)c;
+  (void)p;
+  ++*(int64_t*)ctx;
+}
+int64_t orc_count(const orc_tensor* T) {
+  int64_t n = 0;
+  orc_enumerate(T, count_visit, &n);
+  return n;
+}
+
+typedef struct {
+  const orc_tensor* T;
+  int64_t n, total;
+  int64_t* coords;
+  double* vals;
+} dump_ctx;
+static void dump_visit(void* vctx, const int64_t* c, int64_t p) {
+  dump_ctx* D = (dump_ctx*)vctx;
+  for (int m = 0; m < D->T->order; ++m) D->coords[m * D->total + D->n] = c[m];
+  D->vals[D->n] = val_at(D->T, p);
+  ++D->n;
+}
+void orc_to_coo(const orc_tensor* T, int64_t* coords_out, double* vals_out) {
+  dump_ctx D = {T, 0, orc_count(T), coords_out, vals_out};
+  orc_enumerate(T, dump_visit, &D);
+}
+
+/* ------------------------------------------------------------------ */
+/* Part 2: results by definition                                       */
+/* ------------------------------------------------------------------ */
+
+typedef struct {
+  const orc_tensor* T;
+  const void* x;
+  long double* acc;
+  double* mag;
+} spmv_ctx;
+static void spmv_visit(void* vctx, const int64_t* c, int64_t p) {
+  spmv_ctx* S = (spmv_ctx*)vctx;
+  long double t = (long double)val_at(S->T, p) *
+                  (long double)dense_at(S->x, S->T->is_f64, c[1]);
+  S->acc[c[0]] += t;
+  S->mag[c[0]] += fabs((double)t);
+}
+void orc_spmv(const orc_tensor* T, const void* x, int64_t rows, double* y,
+              double* mag) {
+  long double* acc = (long double*)calloc((size_t)(rows > 0 ? rows : 1), sizeof(long double));
+  for (int64_t i = 0; i < rows; ++i) mag[i] = 0.0;
+  spmv_ctx S = {T, x, acc, mag};
+  orc_enumerate(T, spmv_visit, &S);
+  for (int64_t i = 0; i < rows; ++i) y[i] = (double)acc[i];
+  free(acc);
+}
+
+/* Stable bottom-up merge sort of an index permutation by one or two int32 keys. */
+static int key_less(const int32_t* k0, const int32_t* k1, int64_t a, int64_t b) {
+  if (k0[a] != k0[b]) return k0[a] < k0[b];
+  if (k1 && k1[a] != k1[b]) return k1[a] < k1[b];
+  return 0;
+}
+static void stable_sort_perm(int64_t n, int64_t* perm, const int32_t* k0,
+                             const int32_t* k1) {
+  int64_t* tmp = (int64_t*)malloc(sizeof(int64_t) * (size_t)(n > 0 ? n : 1));
+  int64_t* src = perm;
+  int64_t* dst = tmp;
+  for (int64_t w = 1; w < n; w *= 2) {
+    for (int64_t lo = 0; lo < n; lo += 2 * w) {
+      int64_t mid = imin(lo + w, n), hi = imin(lo + 2 * w, n);
+      int64_t a = lo, b = mid, o = lo;
+      while (a < mid && b < hi) {
+        /* take from the right run only if strictly smaller: stability */
+        if (key_less(k0, k1, src[b], src[a])) dst[o++] = src[b++];
+        else dst[o++] = src[a++];
+      }
+      while (a < mid) dst[o++] = src[a++];
+      while (b < hi) dst[o++] = src[b++];
+    }
+    int64_t* t = src;
+    src = dst;
+    dst = t;
+  }
+  if (src != perm) memcpy(perm, src, sizeof(int64_t) * (size_t)n);
+  free(tmp);
+}
+
+void orc_coo_to_csr(int64_t nnz, int64_t nrows, const int32_t* row,
+                    const int32_t* col, const void* vals, int32_t esize,
+                    int32_t order, int32_t* pos_out, int32_t* crd_out,
+                    void* vals_out, int64_t* perm_out) {
+  int64_t* perm = (int64_t*)malloc(sizeof(int64_t) * (size_t)(nnz > 0 ? nnz : 1));
+  for (int64_t n = 0; n < nnz; ++n) perm[n] = n;
+  stable_sort_perm(nnz, perm, row, order == 0 ? col : NULL);
+  /* Assemble the compressed column level with Table 3's append functions. */
+  for (int64_t p = 0; p <= nrows; ++p) pos_out[p] = 0; /* append_init */
+  int64_t q = 0;
+  for (int64_t i = 0; i < nrows; ++i) {
+    int64_t pbegin = q;
+    while (q < nnz && row[perm[q]] == i) {
+      crd_out[q] = col[perm[q]]; /* append_coord */
+      memcpy((char*)vals_out + q * esize, (const char*)vals + perm[q] * esize,
+             (size_t)esize);
+      ++q;
+    }
+    pos_out[i + 1] = (int32_t)(q - pbegin); /* append_edges */
+  }
+  int64_t cumsum = pos_out[0]; /* append_finalize */
+  for (int64_t p = 1; p <= nrows; ++p) {
+    cumsum += pos_out[p];
+    pos_out[p] = (int32_t)cumsum;
+  }
+  if (perm_out) memcpy(perm_out, perm, sizeof(int64_t) * (size_t)nnz);
+  free(perm);
+}
+
+typedef struct {
+  const orc_tensor* T;
+  const void* c;
+  int64_t n;
+  int32_t *ki, *kj;
+  long double* term;
+} ttv_ctx;
+static void ttv_visit(void* vctx, const int64_t* co, int64_t p) {
+  ttv_ctx* S = (ttv_ctx*)vctx;
+  S->ki[S->n] = (int32_t)co[0];
+  S->kj[S->n] = (int32_t)co[1];
+  S->term[S->n] = (long double)val_at(S->T, p) *
+                  (long double)dense_at(S->c, S->T->is_f64, co[2]);
+  ++S->n;
+}
+int64_t orc_ttv(const orc_tensor* B, const void* c, int64_t cap, int32_t* out_i,
+                int32_t* out_j, double* out_v, double* out_mag) {
+  int64_t total = orc_count(B);
+  size_t a = (size_t)(total > 0 ? total : 1);
+  ttv_ctx S = {B, c, 0, (int32_t*)malloc(4 * a), (int32_t*)malloc(4 * a),
+               (long double*)malloc(sizeof(long double) * a)};
+  orc_enumerate(B, ttv_visit, &S);
+  int64_t* perm = (int64_t*)malloc(sizeof(int64_t) * a);
+  for (int64_t n = 0; n < total; ++n) perm[n] = n;
+  stable_sort_perm(total, perm, S.ki, S.kj);
+  int64_t nout = 0;
+  int64_t n = 0;
+  while (n < total) {
+    int32_t i = S.ki[perm[n]], j = S.kj[perm[n]];
+    long double acc = 0.0L;
+    double mag = 0.0;
+    while (n < total && S.ki[perm[n]] == i && S.kj[perm[n]] == j) {
+      acc += S.term[perm[n]];
+      mag += fabs((double)S.term[perm[n]]);
+      ++n;
+    }
+    if (nout < cap) {
+      out_i[nout] = i;
+      out_j[nout] = j;
+      out_v[nout] = (double)acc;
+      out_mag[nout] = mag;
+    }
+    ++nout;
+  }
+  free(perm);
+  free(S.ki);
+  free(S.kj);
+  free(S.term);
+  return nout;
+}
+
+typedef struct {
+  const orc_tensor* T;
+  const void *C, *D;
+  int32_t J;
+  long double* acc;
+  double* mag;
+} mttkrp_ctx;
+static void mttkrp_visit(void* vctx, const int64_t* co, int64_t p) {
+  mttkrp_ctx* S = (mttkrp_ctx*)vctx;
+  int f = S->T->is_f64;
+  long double v = (long double)val_at(S->T, p);
+  for (int32_t j = 0; j < S->J; ++j) {
+    long double t = v * (long double)dense_at(S->C, f, co[1] * S->J + j) *
+                    (long double)dense_at(S->D, f, co[2] * S->J + j);
+    S->acc[co[0] * S->J + j] += t;
+    S->mag[co[0] * S->J + j] += fabs((double)t);
+  }
+}
+void orc_mttkrp(const orc_tensor* B, const void* C, const void* D, int32_t J,
+                int64_t dim0, double* A, double* mag) {
+  int64_t n = dim0 * J;
+  long double* acc = (long double*)calloc((size_t)(n > 0 ? n : 1), sizeof(long double));
+  for (int64_t q = 0; q < n; ++q) mag[q] = 0.0;
+  mttkrp_ctx S = {B, C, D, J, acc, mag};
+  orc_enumerate(B, mttkrp_visit, &S);
+  for (int64_t q = 0; q < n; ++q) A[q] = (double)acc[q];
+  free(acc);
+}
+
+/* ------------------------------------------------------------------ */
+/* Part 3: plain loop nests per format, native dtype                   */
+/* ------------------------------------------------------------------ */
+
+#define PLAIN_SPMV_CSR(TY)                                              \
+  {                                                                     \
+    const TY* v = (const TY*)vals;                                      \
+    const TY* xv = (const TY*)x;                                        \
+    TY* yv = (TY*)y;                                                    \
+    for (int64_t i = 0; i < N; ++i) {                                   \
+      TY s = 0;                                                         \
+      for (int32_t p = pos[i]; p < pos[i + 1]; ++p) s += v[p] * xv[crd[p]]; \
+      yv[i] = s;                                                        \
+    }                                                                   \
+  }
+void orc_plain_spmv_csr(int64_t N, const int32_t* pos, const int32_t* crd,
+                        const void* vals, const void* x, void* y, int32_t is_f64) {
+  if (is_f64) PLAIN_SPMV_CSR(double) else PLAIN_SPMV_CSR(float)
+}
+
+#define PLAIN_SPMV_COO(TY)                                              \
+  {                                                                     \
+    const TY* v = (const TY*)vals;                                      \
+    const TY* xv = (const TY*)x;                                        \
+    TY* yv = (TY*)y;                                                    \
+    for (int64_t i = 0; i < N; ++i) yv[i] = 0;                          \
+    for (int64_t p = 0; p < nnz; ++p) yv[row[p]] += v[p] * xv[col[p]];  \
+  }
+void orc_plain_spmv_coo(int64_t N, int64_t nnz, const int32_t* row,
+                        const int32_t* col, const void* vals, const void* x,
+                        void* y, int32_t is_f64) {
+  if (is_f64) PLAIN_SPMV_COO(double) else PLAIN_SPMV_COO(float)
+}
+
+#define PLAIN_SPMV_DIA(TY)                                              \
+  {                                                                     \
+    const TY* v = (const TY*)vals;                                      \
+    const TY* xv = (const TY*)x;                                        \
+    TY* yv = (TY*)y;                                                    \
+    for (int64_t i = 0; i < N; ++i) yv[i] = 0;                          \
+    for (int64_t d = 0; d < K; ++d) {                                   \
+      int64_t off = offset[d];                                          \
+      int64_t lo = imax(0, -off), hi = imin(N, M - off);                \
+      for (int64_t i = lo; i < hi; ++i) yv[i] += v[d * N + i] * xv[i + off]; \
+    }                                                                   \
+  }
+void orc_plain_spmv_dia(int64_t N, int64_t M, int64_t K, const int32_t* offset,
+                        const void* vals, const void* x, void* y, int32_t is_f64) {
+  if (is_f64) PLAIN_SPMV_DIA(double) else PLAIN_SPMV_DIA(float)
+}
+
+#define PLAIN_SPMV_ELL(TY)                                              \
+  {                                                                     \
+    const TY* v = (const TY*)vals;                                      \
+    const TY* xv = (const TY*)x;                                        \
+    TY* yv = (TY*)y;                                                    \
+    for (int64_t i = 0; i < N; ++i) yv[i] = 0;                          \
+    for (int64_t k = 0; k < W; ++k)                                     \
+      for (int64_t i = 0; i < N; ++i) {                                 \
+        int32_t j = crd[k * N + i];                                     \
+        if (j >= 0) yv[i] += v[k * N + i] * xv[j];                      \
+      }                                                                 \
+  }
+void orc_plain_spmv_ell(int64_t N, int64_t W, const int32_t* crd,
+                        const void* vals, const void* x, void* y, int32_t is_f64) {
+  if (is_f64) PLAIN_SPMV_ELL(double) else PLAIN_SPMV_ELL(float)
+}
+
+#define PLAIN_TTV_COO(TY)                                               \
+  {                                                                     \
+    const TY* v = (const TY*)vals;                                      \
+    const TY* cv = (const TY*)c;                                        \
+    TY* ov = (TY*)out_v;                                                \
+    int64_t p = 0;                                                      \
+    while (p < nnz) {                                                   \
+      int32_t i = ci[p], j = cj[p];                                     \
+      TY s = 0;                                                         \
+      while (p < nnz && ci[p] == i && cj[p] == j) {                     \
+        s += v[p] * cv[ck[p]];                                          \
+        ++p;                                                            \
+      }                                                                 \
+      out_i[nout] = i;                                                  \
+      out_j[nout] = j;                                                  \
+      ov[nout] = s;                                                     \
+      ++nout;                                                           \
+    }                                                                   \
+  }
+int64_t orc_plain_ttv_coo(int64_t nnz, const int32_t* ci, const int32_t* cj,
+                          const int32_t* ck, const void* vals, const void* c,
+                          int32_t* out_i, int32_t* out_j, void* out_v,
+                          int32_t is_f64) {
+  int64_t nout = 0;
+  if (is_f64) PLAIN_TTV_COO(double) else PLAIN_TTV_COO(float)
+  return nout;
+}
+
+#define PLAIN_TTV_CSF(TY)                                               \
+  {                                                                     \
+    const TY* v = (const TY*)vals;                                      \
+    const TY* cv = (const TY*)c;                                        \
+    TY* ov = (TY*)out_v;                                                \
+    for (int64_t f = 0; f < nfib; ++f) {                                \
+      TY s = 0;                                                         \
+      for (int32_t p = pos2[f]; p < pos2[f + 1]; ++p) s += v[p] * cv[crd2[p]]; \
+      ov[f] = s;                                                        \
+    }                                                                   \
+  }
+void orc_plain_ttv_csf(int64_t nfib, const int32_t* pos2, const int32_t* crd2,
+                       const void* vals, const void* c, void* out_v,
+                       int32_t is_f64) {
+  if (is_f64) PLAIN_TTV_CSF(double) else PLAIN_TTV_CSF(float)
+}
+
+#define PLAIN_MTTKRP_COO(TY)                                            \
+  {                                                                     \
+    const TY* v = (const TY*)vals;                                      \
+    const TY* Cv = (const TY*)C;                                        \
+    const TY* Dv = (const TY*)D;                                        \
+    TY* Av = (TY*)A;                                                    \
+    for (int64_t q = 0; q < dim0 * J; ++q) Av[q] = 0;                   \
+    for (int64_t p = 0; p < nnz; ++p) {                                 \
+      const TY* cr = Cv + (int64_t)ck[p] * J;                           \
+      const TY* dr = Dv + (int64_t)cl[p] * J;                           \
+      TY* ar = Av + (int64_t)ci[p] * J;                                 \
+      for (int32_t j = 0; j < J; ++j) ar[j] += v[p] * cr[j] * dr[j];    \
+    }                                                                   \
+  }
+void orc_plain_mttkrp_coo(int64_t nnz, int64_t dim0, const int32_t* ci,
+                          const int32_t* ck, const int32_t* cl, const void* vals,
+                          const void* C, const void* D, int32_t J, void* A,
+                          int32_t is_f64) {
+  if (is_f64) PLAIN_MTTKRP_COO(double) else PLAIN_MTTKRP_COO(float)
+}
+
+#define PLAIN_MTTKRP_CSF(TY)                                            \
+  {                                                                     \
+    const TY* v = (const TY*)vals;                                      \
+    const TY* Cv = (const TY*)C;                                        \
+    const TY* Dv = (const TY*)D;                                        \
+    TY* Av = (TY*)A;                                                    \
+    TY* t = (TY*)malloc(sizeof(TY) * (size_t)J);                        \
+    for (int64_t q = 0; q < dim0 * J; ++q) Av[q] = 0;                   \
+    for (int32_t p0 = pos0[0]; p0 < pos0[1]; ++p0) {                    \
+      TY* ar = Av + (int64_t)crd0[p0] * J;                              \
+      for (int32_t p1 = pos1[p0]; p1 < pos1[p0 + 1]; ++p1) {            \
+        const TY* cr = Cv + (int64_t)crd1[p1] * J;                      \
+        for (int32_t j = 0; j < J; ++j) t[j] = 0;                       \
+        for (int32_t p2 = pos2[p1]; p2 < pos2[p1 + 1]; ++p2) {          \
+          const TY* dr = Dv + (int64_t)crd2[p2] * J;                    \
+          for (int32_t j = 0; j < J; ++j) t[j] += v[p2] * dr[j];        \
+        }                                                               \
+        for (int32_t j = 0; j < J; ++j) ar[j] += cr[j] * t[j];          \
+      }                                                                 \
+    }                                                                   \
+    free(t);                                                            \
+  }
+void orc_plain_mttkrp_csf(int64_t dim0, const int32_t* pos0, const int32_t* crd0,
+                          const int32_t* pos1, const int32_t* crd1,
+                          const int32_t* pos2, const int32_t* crd2,
+                          const void* vals, const void* C, const void* D,
+                          int32_t J, void* A, int32_t is_f64) {
+  if (is_f64) PLAIN_MTTKRP_CSF(double) else PLAIN_MTTKRP_CSF(float)
+}

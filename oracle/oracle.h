@@ -1,0 +1,118 @@
+/*
+ * oracle.h - CPU reference ("oracle") for sparse tensor kernels over the
+ * coordinate-hierarchy level formats of the paper (Section 3, Table 2, Table 3).
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT PRODUCT CODE. It is deliberately plain and
+ * slow: a literal interpreter of the level functions plus the textbook
+ * definition of each result, accumulated in extended precision. It shares no
+ * code, header or table with the GPU library; only tests, the smoke check and
+ * the benchmark's CPU-baseline leg may call it.
+ *
+ * All pointers are HOST pointers. Index arrays are int32. Values are float
+ * (is_f64 = 0) or double (is_f64 = 1); reference results are always returned
+ * as double, together with the magnitude sum |term| that scales the tolerance.
+ */
+#ifndef ORACLE_H
+#define ORACLE_H
+#include <stdint.h>
+
+enum { ORC_DENSE = 0, ORC_COMPRESSED = 1, ORC_SINGLETON = 2, ORC_RANGE = 3,
+       ORC_OFFSET = 4, ORC_HASHED = 5 };
+
+typedef struct {
+  int32_t kind;   /* ORC_* */
+  int32_t mode;   /* tensor dimension encoded by this level, -1 if none */
+  int64_t N;      /* dense/range: N_k; others: dimension size */
+  int64_t M;      /* range: M_k; hashed: W_k */
+  const int32_t* pos;
+  const int32_t* crd;
+  const int32_t* offset;
+} orc_level;
+
+typedef struct {
+  int32_t order;    /* tensor dimensions */
+  int32_t nlevels;  /* levels */
+  int32_t is_f64;
+  int32_t pad;
+  orc_level lvl[4];
+  const void* vals;
+} orc_tensor;
+
+/* Visitor: coords[m] = coordinate along tensor dimension m, p = leaf position. */
+typedef void (*orc_visit_fn)(void* ctx, const int64_t* coords, int64_t p);
+
+/* Walk every stored leaf of T in storage order (Figure 5 iteration templates
+ * applied level by level with the level functions of Table 2). */
+void orc_enumerate(const orc_tensor* T, orc_visit_fn visit, void* ctx);
+
+/* Children of one parent in one level: Table 2 for that level kind.
+ * p_parent: parent position; i_parent: parent coordinate; i_grand: coordinate
+ * two levels up (the offset level reads offset[i_grand], Table 2).
+ * Writes up to cap (coordinate, position) pairs; returns the child count. */
+int64_t orc_level_children(const orc_level* L, int64_t p_parent, int64_t i_parent,
+                           int64_t i_grand, int64_t* out_i, int64_t* out_p,
+                           int64_t cap);
+
+/* Hashed level locate (Table 2): returns position, *found set to 0/1. */
+int64_t orc_hashed_locate(const orc_level* L, int64_t p_parent, int64_t i,
+                          int32_t* found);
+
+/* Number of stored leaves. */
+int64_t orc_count(const orc_tensor* T);
+/* Dump to coordinate lists: coords_out[m*count + n], vals_out[n] (as double). */
+void orc_to_coo(const orc_tensor* T, int64_t* coords_out, double* vals_out);
+
+/* y_i = sum over stored (i,j): v * x_j (Section 5.2). rows = len(y).
+ * y and mag (sum of |v*x_j|) are overwritten. x has the dtype of T. */
+void orc_spmv(const orc_tensor* T, const void* x, int64_t rows, double* y,
+              double* mag);
+
+/* COO -> CSR index assembly. order 0: by (row,col), ties keep input order;
+ * order 1: by row, input order kept inside a row. pos via Table 3's
+ * append_init / append_edges / append_finalize. perm_out[n] = input index of
+ * output entry n (may be NULL). esize = bytes per value (4 or 8). */
+void orc_coo_to_csr(int64_t nnz, int64_t nrows, const int32_t* row,
+                    const int32_t* col, const void* vals, int32_t esize,
+                    int32_t order, int32_t* pos_out, int32_t* crd_out,
+                    void* vals_out, int64_t* perm_out);
+
+/* TTV A_ij = sum_k B_ijk c_k (Section 5.3): one output entry per distinct
+ * (i,j) holding a stored entry, ascending (i,j). Returns the entry count;
+ * outputs have capacity cap (= number of leaves is always enough). */
+int64_t orc_ttv(const orc_tensor* B, const void* c, int64_t cap, int32_t* out_i,
+                int32_t* out_j, double* out_v, double* out_mag);
+
+/* MTTKRP A_ij = sum_kl B_ikl C_kj D_lj (Section 5.3), unfactored definition.
+ * C: dim1 x J, D: dim2 x J row-major in the dtype of B; A, mag: dim0 x J. */
+void orc_mttkrp(const orc_tensor* B, const void* C, const void* D, int32_t J,
+                int64_t dim0, double* A, double* mag);
+
+/* ---- plain per-format loop nests (what the paper's generated code does,
+ * Section 5.2 / 5.3), native dtype, single thread. Timed as the CPU baseline
+ * and cross-checked against the definitions above. ---- */
+void orc_plain_spmv_csr(int64_t N, const int32_t* pos, const int32_t* crd,
+                        const void* vals, const void* x, void* y, int32_t is_f64);
+void orc_plain_spmv_coo(int64_t N, int64_t nnz, const int32_t* row,
+                        const int32_t* col, const void* vals, const void* x,
+                        void* y, int32_t is_f64);
+void orc_plain_spmv_dia(int64_t N, int64_t M, int64_t K, const int32_t* offset,
+                        const void* vals, const void* x, void* y, int32_t is_f64);
+void orc_plain_spmv_ell(int64_t N, int64_t W, const int32_t* crd,
+                        const void* vals, const void* x, void* y, int32_t is_f64);
+int64_t orc_plain_ttv_coo(int64_t nnz, const int32_t* ci, const int32_t* cj,
+                          const int32_t* ck, const void* vals, const void* c,
+                          int32_t* out_i, int32_t* out_j, void* out_v,
+                          int32_t is_f64);
+void orc_plain_ttv_csf(int64_t nfib, const int32_t* pos2, const int32_t* crd2,
+                       const void* vals, const void* c, void* out_v,
+                       int32_t is_f64);
+void orc_plain_mttkrp_coo(int64_t nnz, int64_t dim0, const int32_t* ci,
+                          const int32_t* ck, const int32_t* cl, const void* vals,
+                          const void* C, const void* D, int32_t J, void* A,
+                          int32_t is_f64);
+void orc_plain_mttkrp_csf(int64_t dim0, const int32_t* pos0, const int32_t* crd0,
+                          const int32_t* pos1, const int32_t* crd1,
+                          const int32_t* pos2, const int32_t* crd2,
+                          const void* vals, const void* C, const void* D,
+                          int32_t J, void* A, int32_t is_f64);
+#endif

@@ -1,0 +1,285 @@
+"""Pins for the oracle's results: library routines (scipy.sparse, numpy dense
+algebra), closed forms, exact-integer cases and cross-format agreement.
+Each pin is chosen so that a dropped term, wrong sign/index or transposed
+operand in oracle.c fails it. CPU only."""
+import numpy as np
+import pytest
+import scipy.sparse as sp
+
+import oracle
+import workloads as wl
+
+
+def _dense(N, M, r, c, v):
+    D = np.zeros((N, M), np.float64)
+    np.add.at(D, (r, c), v.astype(np.float64))
+    return D
+
+
+# ------------------------------------------------------------------ SpMV
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("dup", [False, True])
+def test_spmv_coo_csr_vs_dense_and_scipy(dtype, dup):
+    N, M = 37, 53                                  # non-square: catches transposition
+    r, c, v = wl.random_coo_entries(N, M, 400, seed=11, dtype=dtype, duplicates=dup)
+    x = wl.dense_vector(M, 12, dtype)
+    want = _dense(N, M, r, c, v) @ x.astype(np.float64)
+    want_sp = sp.coo_matrix((v.astype(np.float64), (r, c)), shape=(N, M)).tocsr() @ x.astype(np.float64)
+    for spec in (wl.coo_spec(N, M, r, c, v), wl.csr_from_sorted_coo(N, M, r, c, v)):
+        y, mag = oracle.spmv(spec, x)
+        np.testing.assert_allclose(y, want, rtol=0, atol=1e-13 * max(1.0, mag.max()))
+        np.testing.assert_allclose(y, want_sp, rtol=0, atol=1e-13 * max(1.0, mag.max()))
+        want_mag = _dense(N, M, r, c, np.abs(v)) @ np.abs(x.astype(np.float64))
+        np.testing.assert_allclose(mag, want_mag, rtol=1e-12)
+
+
+def test_spmv_unsorted_coo_is_order_independent():
+    N, M = 20, 30
+    r, c, v = wl.random_coo_entries(N, M, 150, seed=4)
+    x = wl.dense_vector(M, 5)
+    p = np.random.default_rng(0).permutation(len(v))
+    y0, _ = oracle.spmv(wl.coo_spec(N, M, r, c, v), x)
+    y1, _ = oracle.spmv(wl.coo_spec(N, M, r[p], c[p], v[p], ordered=False), x)
+    np.testing.assert_allclose(y0, y1, rtol=0, atol=1e-15)
+
+
+def test_spmv_closed_forms():
+    N = 9
+    eye = wl.coo_spec(N, N, np.arange(N), np.arange(N), np.ones(N))
+    x = wl.dense_vector(N, 1)
+    assert np.array_equal(oracle.spmv(eye, x)[0], x)                 # A = I  =>  y = x
+    r, c, v = wl.random_coo_entries(7, 5, 20, seed=3)
+    D = _dense(7, 5, r, c, v)
+    spec = wl.csr_from_sorted_coo(7, 5, r, c, v)
+    for j in range(5):                                               # x = e_j => column j
+        e = np.zeros(5)
+        e[j] = 1
+        assert np.array_equal(oracle.spmv(spec, e)[0], D[:, j])
+    np.testing.assert_allclose(oracle.spmv(spec, np.ones(5))[0], D.sum(1), atol=1e-15)
+    y, _ = oracle.spmv(wl.csr_from_sorted_coo(4, 4, [], [], np.zeros(0)), np.ones(4))
+    assert np.array_equal(y, np.zeros(4))                            # empty rows give 0
+
+
+def test_spmv_exact_integer_case_is_bit_exact_in_every_format():
+    c2 = wl.config2(N=64, seed=2)
+    off = wl.config2_offsets(64)
+    rng = np.random.default_rng(1)
+    diag = c2["dia"].vals.reshape(len(off), 64).copy()
+    diag[~np.isnan(diag)] = 0
+    for d, o in enumerate(off):
+        lo, hi = max(0, -o), min(64, 64 - o)
+        diag[d, lo:hi] = rng.integers(-4, 5, hi - lo)
+    x = rng.integers(-4, 5, 64).astype(np.float64)
+    dia = wl.dia_spec(64, 64, off, diag)
+    want = np.zeros(64)
+    for d, o in enumerate(off):
+        for i in range(max(0, -o), min(64, 64 - o)):
+            want[i] += diag[d, i] * x[i + o]
+    assert np.array_equal(oracle.spmv(dia, x)[0], want)
+    assert np.array_equal(oracle.plain_spmv(dia, x, "dia"), want)
+
+
+def test_spmv_dia_vs_scipy_dia_and_csr_twin():
+    N = 300
+    c2 = wl.config2(N=N, seed=8, poison=True)
+    off = wl.config2_offsets(N)
+    x = c2["x"]
+    y_dia, mag = oracle.spmv(c2["dia"], x)
+    y_csr, _ = oracle.spmv(c2["csr"], x)
+    assert np.isfinite(y_dia).all()                       # poison cells never read
+    np.testing.assert_allclose(y_dia, y_csr, rtol=0, atol=1e-15 * mag.max())
+    # scipy's DIA indexes its data by COLUMN: data[d, i+off] = our cell (d,i)
+    dv = np.nan_to_num(c2["dia"].vals.reshape(len(off), N))
+    data = np.zeros((len(off), N))
+    for d, o in enumerate(off):
+        lo, hi = max(0, -o), min(N, N - o)
+        data[d, lo + o:hi + o] = dv[d, lo:hi]
+    want = sp.dia_matrix((data, off), shape=(N, N)) @ x
+    np.testing.assert_allclose(y_dia, want, rtol=0, atol=1e-14 * mag.max())
+    # a single diagonal is an element-wise product with a shifted x
+    one = wl.dia_spec(6, 9, [2], np.arange(1.0, 7.0)[None, :])
+    xx = np.arange(10.0, 19.0)
+    assert np.array_equal(oracle.spmv(one, xx)[0], np.arange(1.0, 7.0) * xx[2:8])
+
+
+def test_spmv_dia_rectangular_and_out_of_range_diagonals():
+    N, M = 5, 8
+    off = np.array([-7, -1, 0, 3, 7, 12])                 # -7 and 12 lie fully outside
+    diag = np.random.default_rng(3).uniform(-1, 1, (len(off), N))
+    x = wl.dense_vector(M, 2)
+    D = np.zeros((N, M))
+    for d, o in enumerate(off):
+        for i in range(N):
+            if 0 <= i + o < M:
+                D[i, i + o] += diag[d, i]
+    y, _ = oracle.spmv(wl.dia_spec(N, M, off, diag), x)
+    np.testing.assert_allclose(y, D @ x, atol=1e-15)
+
+
+def test_spmv_ell_vs_csr_twin_and_padding_is_ignored():
+    c3 = wl.config3(N=200, lo=0, hi=9, seed=6, dtype=np.float32)
+    x = c3["x"]
+    ell = c3["ell"]
+    y_csr, mag = oracle.spmv(c3["csr"], x)
+    y_ell, _ = oracle.spmv(ell, x)
+    np.testing.assert_allclose(y_ell, y_csr, rtol=0, atol=1e-15 * max(mag.max(), 1))
+    lv = c3["csr"].levels[1]
+    want = sp.csr_matrix((c3["csr"].vals.astype(np.float64), lv.crd, lv.pos), shape=(200, 200)) @ x.astype(np.float64)
+    np.testing.assert_allclose(y_csr, want, rtol=0, atol=1e-13 * max(mag.max(), 1))
+    v = ell.vals.copy()
+    v[ell.levels[2].crd < 0] = np.nan                     # poison the padding values
+    poisoned = wl.TensorSpec(ell.dims, ell.levels, v)
+    assert np.array_equal(oracle.spmv(poisoned, x)[0], y_ell)
+    assert np.array_equal(oracle.plain_spmv(poisoned, x, "ell").astype(np.float64),
+                          oracle.plain_spmv(ell, x, "ell").astype(np.float64))
+
+
+@pytest.mark.parametrize("dtype,tol", [(np.float64, 1e-13), (np.float32, 2e-6)])
+def test_plain_spmv_loops_agree_with_definition(dtype, tol):
+    c1 = wl.config1(N=128, nnz=900, seed=21)
+    c2 = wl.config2(N=257, seed=22, dtype=dtype)
+    c3 = wl.config3(N=130, lo=1, hi=12, seed=23, dtype=dtype)
+    cases = [(c2["dia"], c2["x"], "dia"), (c2["csr"], c2["x"], "csr"),
+             (c3["ell"], c3["x"], "ell"), (c3["csr"], c3["x"], "csr")]
+    if dtype == np.float64:
+        cases += [(c1["coo"], c1["x"], "coo"), (c1["csr"], c1["x"], "csr")]
+    for spec, x, fmt in cases:
+        y, mag = oracle.spmv(spec, x)
+        got = oracle.plain_spmv(spec, x, fmt).astype(np.float64)
+        assert np.all(np.abs(got - y) <= tol * np.maximum(mag, 1e-30) + 1e-300), fmt
+
+
+# ------------------------------------------------------------------ COO -> CSR
+
+@pytest.mark.parametrize("order", [0, 1])
+@pytest.mark.parametrize("dup", [False, True])
+def test_coo_to_csr_vs_numpy_and_scipy(order, dup):
+    N, M = 23, 17
+    r, c, v = wl.random_coo_entries(N, M, 300, seed=31, duplicates=dup, sort=False)
+    pos, crd, vout, perm = oracle.coo_to_csr(N, r, c, v, order)
+    # numpy's lexsort is a stable indirect sort: the expected permutation
+    want_perm = np.lexsort((c, r)) if order == 0 else np.argsort(r, kind="stable")
+    assert np.array_equal(perm, want_perm)
+    assert np.array_equal(crd, c[want_perm]) and np.array_equal(vout, v[want_perm])
+    want_pos = np.concatenate([[0], np.cumsum(np.bincount(r, minlength=N))])
+    assert np.array_equal(pos, want_pos)
+    assert pos[0] == 0 and pos[-1] == len(r) and np.all(np.diff(pos) >= 0)
+    if not dup and order == 0:
+        m = sp.coo_matrix((v, (r, c)), shape=(N, M)).tocsr()
+        m.sort_indices()
+        assert np.array_equal(pos, m.indptr) and np.array_equal(crd, m.indices)
+        assert np.array_equal(vout, m.data)
+    if order == 0:
+        for a, b in zip(pos[:-1], pos[1:]):
+            assert np.all(np.diff(crd[a:b]) >= 0)
+
+
+def test_coo_to_csr_fixed_point_and_edge_cases():
+    r, c, v = wl.random_coo_entries(12, 12, 50, seed=33)
+    pos, crd, vout, _ = oracle.coo_to_csr(12, r, c, v, 0)
+    rows_back = np.repeat(np.arange(12), np.diff(pos))
+    pos2, crd2, v2, perm2 = oracle.coo_to_csr(12, rows_back, crd, vout, 0)
+    assert np.array_equal(pos, pos2) and np.array_equal(crd, crd2) and np.array_equal(vout, v2)
+    assert np.array_equal(perm2, np.arange(len(v)))
+    pos, crd, vout, _ = oracle.coo_to_csr(5, [], [], np.zeros(0), 0)
+    assert np.array_equal(pos, np.zeros(6, np.int32)) and len(crd) == 0
+    pos, crd, vout, _ = oracle.coo_to_csr(5, [3], [2], np.array([1.5], np.float32), 1)
+    assert list(pos) == [0, 0, 0, 0, 1, 1] and list(crd) == [2] and vout[0] == np.float32(1.5)
+
+
+# ------------------------------------------------------------------ TTV
+
+def _dense3(dims, ci, cj, ck, v):
+    B = np.zeros(dims, np.float64)
+    np.add.at(B, (ci, cj, ck), v.astype(np.float64))
+    return B
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_ttv_vs_dense_einsum(dtype):
+    dims = (5, 4, 6)
+    ci, cj, ck, v = wl.random_coo3_entries(dims, 70, seed=41, dtype=dtype, skew=1.5)
+    c = wl.dense_vector(6, 42, dtype, "u01")
+    B = _dense3(dims, ci, cj, ck, v)
+    want = np.einsum("ijk,k->ij", B, c.astype(np.float64))
+    fib = np.unique(ci.astype(np.int64) * 4 + cj)
+    for spec in (wl.coo3_spec(dims, ci, cj, ck, v), wl.csf3_from_sorted_coo(dims, ci, cj, ck, v)):
+        oi, oj, ov, om = oracle.ttv(spec, c)
+        assert len(oi) == len(fib)                                 # one entry per stored fiber
+        assert np.array_equal(oi.astype(np.int64) * 4 + oj, fib)   # ascending (i,j)
+        np.testing.assert_allclose(ov, want[oi, oj], rtol=0, atol=1e-14 * om.max())
+    # plain loops
+    coo = wl.coo3_spec(dims, ci, cj, ck, v)
+    csf = wl.csf3_from_sorted_coo(dims, ci, cj, ck, v)
+    pi, pj, pv = oracle.plain_ttv(coo, c, "coo")
+    tol = 1e-13 if dtype == np.float64 else 2e-6
+    assert np.array_equal(pi, oi) and np.array_equal(pj, oj)
+    assert np.all(np.abs(pv - ov) <= tol * om)
+    assert np.all(np.abs(oracle.plain_ttv(csf, c, "csf") - ov) <= tol * om)
+
+
+def test_ttv_closed_forms():
+    dims = (4, 3, 5)
+    ci, cj, ck, v = wl.random_coo3_entries(dims, 30, seed=43, dtype=np.float64)
+    B = _dense3(dims, ci, cj, ck, v)
+    spec = wl.coo3_spec(dims, ci, cj, ck, v)
+    oi, oj, ov, _ = oracle.ttv(spec, np.ones(5))
+    np.testing.assert_allclose(ov, B.sum(2)[oi, oj], atol=1e-15)     # c = 1: fiber sums
+    e = np.zeros(5)
+    e[2] = 1
+    oi, oj, ov, _ = oracle.ttv(spec, e)
+    assert np.array_equal(ov, B[:, :, 2][oi, oj])                    # c = e_k: slice k
+    # a fiber whose sum is 0 is still emitted (structure comes from coordinates)
+    z = wl.coo3_spec((2, 2, 2), [0, 0], [1, 1], [0, 1], np.array([1.0, -1.0]))
+    oi, oj, ov, _ = oracle.ttv(z, np.ones(2))
+    assert list(oi) == [0] and list(oj) == [1] and ov[0] == 0.0
+    assert len(oracle.ttv(wl.coo3_spec((2, 2, 2), [], [], [], np.zeros(0)), np.ones(2))[0]) == 0
+
+
+# ------------------------------------------------------------------ MTTKRP
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("J", [1, 3, 8])
+def test_mttkrp_vs_dense_einsum_and_khatri_rao(dtype, J):
+    dims = (5, 4, 6)
+    ci, ck, cl, v = wl.random_coo3_entries(dims, 80, seed=51, dtype=dtype, skew=1.5)
+    rng = np.random.default_rng(52)
+    Cm = rng.uniform(0, 1, (4, J)).astype(dtype)
+    Dm = rng.uniform(0, 1, (6, J)).astype(dtype)
+    B = _dense3(dims, ci, ck, cl, v)
+    C64, D64 = Cm.astype(np.float64), Dm.astype(np.float64)
+    want = np.einsum("ikl,kj,lj->ij", B, C64, D64)
+    # matricised form: B_(0) (I x KL) times the Khatri-Rao product (KL x J)
+    kr = (C64[:, None, :] * D64[None, :, :]).reshape(4 * 6, J)
+    np.testing.assert_allclose(B.reshape(5, 24) @ kr, want, atol=1e-13)
+    coo = wl.coo3_spec(dims, ci, ck, cl, v)
+    csf = wl.csf3_from_sorted_coo(dims, ci, ck, cl, v)
+    tol = 1e-13 if dtype == np.float64 else 4e-6
+    for spec in (coo, csf):
+        A, mag = oracle.mttkrp(spec, Cm, Dm)
+        np.testing.assert_allclose(A, want, rtol=0, atol=1e-14 * mag.max())
+    for spec, fmt in ((coo, "coo"), (csf, "csf")):
+        P = oracle.plain_mttkrp(spec, Cm, Dm, fmt).astype(np.float64)
+        assert np.all(np.abs(P - A) <= tol * np.maximum(mag, 1e-30) + 1e-300), fmt
+
+
+def test_mttkrp_closed_forms():
+    dims = (4, 3, 5)
+    ci, ck, cl, v = wl.random_coo3_entries(dims, 30, seed=53, dtype=np.float64)
+    B = _dense3(dims, ci, ck, cl, v)
+    spec = wl.coo3_spec(dims, ci, ck, cl, v)
+    A, _ = oracle.mttkrp(spec, np.ones((3, 1)), np.ones((5, 1)))
+    np.testing.assert_allclose(A[:, 0], B.sum((1, 2)), atol=1e-15)    # slice sums
+    # D = 1 reduces MTTKRP to (TTV with ones) followed by a matrix product
+    Cm = np.random.default_rng(1).uniform(0, 1, (3, 2))
+    A, _ = oracle.mttkrp(spec, Cm, np.ones((5, 2)))
+    np.testing.assert_allclose(A, B.sum(2) @ Cm, atol=1e-14)
+    # integer data: exact regardless of summation order
+    vi = np.random.default_rng(2).integers(-3, 4, len(v)).astype(np.float64)
+    Ci = np.random.default_rng(3).integers(-3, 4, (3, 4)).astype(np.float64)
+    Di = np.random.default_rng(4).integers(-3, 4, (5, 4)).astype(np.float64)
+    si = wl.coo3_spec(dims, ci, ck, cl, vi)
+    want = np.einsum("ikl,kj,lj->ij", _dense3(dims, ci, ck, cl, vi), Ci, Di)
+    assert np.array_equal(oracle.mttkrp(si, Ci, Di)[0], want)
+    assert np.array_equal(oracle.plain_mttkrp(si, Ci, Di, "coo"), want)

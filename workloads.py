@@ -1,0 +1,340 @@
+"""Seeded synthetic inputs and plain format descriptions.
+
+This module holds DATA LAYOUT ONLY: it draws random coordinates and values and
+lays them out as the level arrays (pos / crd / offset / vals) of each storage
+format. It contains none of the arithmetic of the kernels under test; both the
+CPU oracle and the GPU library are fed from here, and neither is imported.
+
+The generated tensors stand in for the paper's evaluation inputs (Table 4:
+SuiteSparse matrices and FROSTT tensors, which are not available offline):
+uniform-random matrices, few-dense-diagonal matrices (like Lin / synth1 /
+atmosmodd with 7 diagonals), bounded-row-length mesh-like matrices for ELL,
+power-law web-like matrices, and skewed NELL-like 3rd-order tensors.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional, Tuple
+
+import numpy as np
+
+DENSE, COMPRESSED, SINGLETON, RANGE, OFFSET, HASHED = range(6)
+KIND_NAMES = ["dense", "compressed", "singleton", "range", "offset", "hashed"]
+
+
+@dataclass
+class LevelSpec:
+    """One coordinate-hierarchy level (Section 3.1): kind + arrays + sizes."""
+    kind: int
+    mode: int
+    N: int
+    M: int = 0
+    pos: Optional[np.ndarray] = None
+    crd: Optional[np.ndarray] = None
+    offset: Optional[np.ndarray] = None
+    ordered: bool = True
+    unique: bool = True
+
+
+@dataclass
+class TensorSpec:
+    """A tensor stored as a list of levels plus one values array."""
+    dims: Tuple[int, ...]
+    levels: List[LevelSpec]
+    vals: np.ndarray
+    name: str = ""
+
+    @property
+    def order(self) -> int:
+        return len(self.dims)
+
+    @property
+    def dtype(self):
+        return self.vals.dtype
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+# ---------------------------------------------------------------------------
+# format layouts
+# ---------------------------------------------------------------------------
+
+def coo_spec(N, M, row, col, vals, ordered=True, name="coo") -> TensorSpec:
+    """COO = (compressed non-unique rows with pos=[0,nnz], singleton cols)."""
+    nnz = len(vals)
+    return TensorSpec((N, M), [
+        LevelSpec(COMPRESSED, 0, N, M=1, pos=_i32([0, nnz]), crd=_i32(row),
+                  ordered=ordered, unique=False),
+        LevelSpec(SINGLETON, 1, M, crd=_i32(col), ordered=ordered),
+    ], np.ascontiguousarray(vals), name)
+
+
+def csr_spec(N, M, pos, crd, vals, ordered=True, unique=True, name="csr") -> TensorSpec:
+    """CSR = (dense rows, compressed cols)."""
+    return TensorSpec((N, M), [
+        LevelSpec(DENSE, 0, N),
+        LevelSpec(COMPRESSED, 1, M, M=N, pos=_i32(pos), crd=_i32(crd),
+                  ordered=ordered, unique=unique),
+    ], np.ascontiguousarray(vals), name)
+
+
+def dia_spec(N, M, offsets, diag_vals, name="dia") -> TensorSpec:
+    """DIA = (dense diagonals, range rows, offset cols); cell (d,i) at d*N+i,
+    column i+offset[d]; both lower levels share the offset array."""
+    off = _i32(offsets)
+    K = len(off)
+    vals = np.ascontiguousarray(diag_vals).reshape(K * N)
+    return TensorSpec((N, M), [
+        LevelSpec(DENSE, -1, K),
+        LevelSpec(RANGE, 0, N, M=M, offset=off),
+        LevelSpec(OFFSET, 1, M, offset=off),
+    ], vals, name)
+
+
+def ell_spec(N, M, crd_wn, vals_wn, name="ell") -> TensorSpec:
+    """ELL = (dense slots, dense rows, singleton cols); cell (k,i) at k*N+i,
+    padding marked by column -1."""
+    W = crd_wn.shape[0] if crd_wn.ndim == 2 else len(crd_wn) // max(N, 1)
+    return TensorSpec((N, M), [
+        LevelSpec(DENSE, -1, W),
+        LevelSpec(DENSE, 0, N),
+        LevelSpec(SINGLETON, 1, M, crd=_i32(crd_wn).reshape(W * N), ordered=False),
+    ], np.ascontiguousarray(vals_wn).reshape(W * N), name)
+
+
+def coo3_spec(dims, ci, cj, ck, vals, ordered=True, name="coo3") -> TensorSpec:
+    """3rd-order COO = (compressed ~U, singleton ~U, singleton)."""
+    nnz = len(vals)
+    return TensorSpec(tuple(dims), [
+        LevelSpec(COMPRESSED, 0, dims[0], M=1, pos=_i32([0, nnz]), crd=_i32(ci),
+                  ordered=ordered, unique=False),
+        LevelSpec(SINGLETON, 1, dims[1], crd=_i32(cj), ordered=ordered, unique=False),
+        LevelSpec(SINGLETON, 2, dims[2], crd=_i32(ck), ordered=ordered),
+    ], np.ascontiguousarray(vals), name)
+
+
+def csf3_spec(dims, pos0, crd0, pos1, crd1, pos2, crd2, vals, name="csf3") -> TensorSpec:
+    """CSF = (compressed, compressed, compressed)."""
+    return TensorSpec(tuple(dims), [
+        LevelSpec(COMPRESSED, 0, dims[0], M=1, pos=_i32(pos0), crd=_i32(crd0)),
+        LevelSpec(COMPRESSED, 1, dims[1], M=len(crd0), pos=_i32(pos1), crd=_i32(crd1)),
+        LevelSpec(COMPRESSED, 2, dims[2], M=len(crd1), pos=_i32(pos2), crd=_i32(crd2)),
+    ], np.ascontiguousarray(vals), name)
+
+
+def csr_from_sorted_coo(N, M, row, col, vals, name="csr") -> TensorSpec:
+    """Lay a row-sorted entry list out as CSR (segment bounds from a sorted search)."""
+    pos = np.searchsorted(np.asarray(row), np.arange(N + 1), side="left")
+    return csr_spec(N, M, pos, col, vals, name=name)
+
+
+def csf3_from_sorted_coo(dims, ci, cj, ck, vals, name="csf3") -> TensorSpec:
+    """Lay a lexicographically sorted, duplicate-free entry list out as CSF."""
+    ci, cj, ck = (np.asarray(a, dtype=np.int64) for a in (ci, cj, ck))
+    nnz = len(ci)
+    if nnz == 0:
+        z = np.zeros(0, np.int32)
+        return csf3_spec(dims, [0, 0], z, [0], z, [0], z, np.asarray(vals), name)
+    new_i = np.ones(nnz, bool)
+    new_i[1:] = ci[1:] != ci[:-1]
+    new_ij = new_i.copy()
+    new_ij[1:] |= cj[1:] != cj[:-1]
+    fib_start = np.flatnonzero(new_ij)            # first entry of every (i,j) fiber
+    slice_start_in_fibs = np.flatnonzero(new_i[fib_start])  # first fiber of every i
+    crd0 = ci[fib_start][slice_start_in_fibs]
+    pos0 = [0, len(crd0)]
+    pos1 = np.append(slice_start_in_fibs, len(fib_start))
+    crd1 = cj[fib_start]
+    pos2 = np.append(fib_start, nnz)
+    return csf3_spec(dims, pos0, crd0, pos1, crd1, pos2, ck, vals, name)
+
+
+# ---------------------------------------------------------------------------
+# generic small random inputs (parity sweeps)
+# ---------------------------------------------------------------------------
+
+def _values(rng, n, dtype, dist):
+    if dist == "u11":
+        v = rng.uniform(-1.0, 1.0, n)
+    elif dist == "u01":
+        v = rng.uniform(0.0, 1.0, n)
+    elif dist == "n01":
+        v = rng.standard_normal(n)
+    elif dist == "int":   # small integers: every partial sum is exact in fp32/fp64
+        v = rng.integers(-4, 5, n).astype(np.float64)
+    else:
+        raise ValueError(dist)
+    return v.astype(dtype)
+
+
+def random_coo_entries(N, M, nnz, seed, dtype=np.float64, dist="u11",
+                       duplicates=False, sort=True):
+    """(row, col, vals) at uniform-random positions; distinct unless duplicates."""
+    rng = np.random.default_rng(seed)
+    if duplicates or N * M == 0:
+        row = rng.integers(0, max(N, 1), nnz)
+        col = rng.integers(0, max(M, 1), nnz)
+    else:
+        nnz = min(nnz, N * M)
+        if N * M <= 4 * nnz + 64:
+            key = rng.permutation(N * M)[:nnz]
+        else:
+            key = np.unique(rng.integers(0, N * M, int(nnz * 1.2) + 16))
+            while len(key) < nnz:
+                key = np.unique(np.concatenate([key, rng.integers(0, N * M, nnz)]))
+            key = rng.permutation(key)[:nnz]
+        row, col = key // M, key % M
+    if sort:
+        o = np.lexsort((col, row))
+        row, col = row[o], col[o]
+    vals = _values(rng, len(row), dtype, dist)
+    return _i32(row), _i32(col), vals
+
+
+def dense_vector(n, seed, dtype=np.float64, dist="u11"):
+    return _values(np.random.default_rng(seed), n, dtype, dist)
+
+
+def random_coo3_entries(dims, nnz, seed, dtype=np.float32, dist="u01", skew=None,
+                        duplicates=False):
+    """Sorted 3rd-order entries; mode 0 optionally Zipf(skew)-distributed."""
+    rng = np.random.default_rng(seed)
+    I, J, K = dims
+    if skew:
+        w = (np.arange(I) + 1.0) ** (-skew)
+        cdf = np.cumsum(w / w.sum())
+        ci = np.minimum(np.searchsorted(cdf, rng.random(nnz)), I - 1)
+    else:
+        ci = rng.integers(0, I, nnz)
+    cj = rng.integers(0, J, nnz)
+    ck = rng.integers(0, K, nnz)
+    key = (ci.astype(np.int64) * J + cj) * K + ck
+    key = np.sort(key) if duplicates else np.unique(key)
+    ck = key % K
+    cj = (key // K) % J
+    ci = key // (K * J)
+    vals = _values(rng, len(key), dtype, dist)
+    return _i32(ci), _i32(cj), _i32(ck), vals
+
+
+# ---------------------------------------------------------------------------
+# the five benchmark configurations (full size by default, scalable)
+# ---------------------------------------------------------------------------
+
+SEED_BASE = 180410112
+
+
+def config1(N=4096, nnz=40960, seed=SEED_BASE + 1):
+    """Uniform-random fp64 matrix, distinct positions; COO sorted (row,col) + CSR."""
+    row, col, vals = random_coo_entries(N, N, nnz, seed, np.float64, "u11")
+    x = dense_vector(N, seed + 1000, np.float64, "u11")
+    return {"coo": coo_spec(N, N, row, col, vals, name="c1-coo"),
+            "csr": csr_from_sorted_coo(N, N, row, col, vals, name="c1-csr"),
+            "x": x, "entries": (row, col, vals)}
+
+
+def config2_offsets(N):
+    """Offsets {0, +-1, +-~sqrt(N), +-N/2}: (0,1,1414,1000000) at N = 2e6."""
+    a = max(2, int(np.floor(np.sqrt(N))))
+    b = max(a + 1, N // 2)
+    return np.array([-b, -a, -1, 0, 1, a, b], dtype=np.int64)
+
+
+def config2(N=2_000_000, seed=SEED_BASE + 2, poison=False, dtype=np.float64):
+    """Banded matrix with 7 densely filled diagonals, as DIA and as CSR."""
+    rng = np.random.default_rng(seed)
+    off = config2_offsets(N)
+    K = len(off)
+    i = np.arange(N, dtype=np.int64)
+    diag = np.full((K, N), np.nan if poison else 0.0, dtype=dtype)
+    valid = np.zeros((K, N), dtype=bool)
+    for d in range(K):
+        lo, hi = max(0, -off[d]), min(N, N - off[d])
+        diag[d, lo:hi] = rng.uniform(-1.0, 1.0, hi - lo).astype(dtype)
+        valid[d, lo:hi] = True
+    # CSR of the same entries: row-major walk over (row, diagonal); offsets
+    # ascend, so columns ascend inside a row.
+    vt = valid.T
+    cols = (i[:, None] + off[None, :])[vt]
+    vals = np.ascontiguousarray(diag.T)[vt]
+    pos = np.concatenate([[0], np.cumsum(vt.sum(axis=1))])
+    x = dense_vector(N, seed + 1000, dtype, "u11")
+    return {"dia": dia_spec(N, N, off, diag, name="c2-dia"),
+            "csr": csr_spec(N, N, pos, cols, vals, name="c2-csr"),
+            "x": x, "nnz": int(pos[-1])}
+
+
+def config3(N=1_000_000, lo=8, hi=32, seed=SEED_BASE + 3, dtype=np.float32):
+    """Row lengths uniform in [lo,hi], distinct uniform columns sorted inside a
+    row and left-packed; ELL (width = max length, pad col -1 / value 0) + CSR."""
+    rng = np.random.default_rng(seed)
+    M = N
+    hi = min(hi, M)
+    lo = min(lo, hi)
+    L = rng.integers(lo, hi + 1, N)
+    W = int(L.max()) if N else 0
+    slot = np.arange(W)[None, :]
+    live = slot < L[:, None]
+    cols = rng.integers(0, M, (N, W))
+    cols[~live] = M                      # sentinel sorts to the end of the row
+    cols.sort(axis=1)
+    while True:                          # redraw rows that hold a repeated column
+        dup = (cols[:, 1:] == cols[:, :-1]) & live[:, 1:]
+        bad = np.flatnonzero(dup.any(axis=1))
+        if len(bad) == 0:
+            break
+        fresh = rng.integers(0, M, (len(bad), W))
+        fresh[~live[bad]] = M
+        fresh.sort(axis=1)
+        cols[bad] = fresh
+    v = rng.standard_normal((N, W)).astype(dtype)
+    v[~live] = 0
+    crd = np.where(live, cols, -1)
+    x = dense_vector(M, seed + 1000, dtype, "n01")
+    pos = np.concatenate([[0], np.cumsum(L)])
+    return {"ell": ell_spec(N, M, np.ascontiguousarray(crd.T), np.ascontiguousarray(v.T),
+                            name="c3-ell"),
+            "csr": csr_spec(N, M, pos, crd[live], v[live], name="c3-csr"),
+            "x": x, "nnz": int(pos[-1]), "W": W}
+
+
+def config4(N=4_000_000, nnz_target=60_000_000, max_row=200_000, zipf=1.8,
+            seed=SEED_BASE + 4, dtype=np.float64):
+    """Power-law row lengths (truncated Zipf, thinned to ~nnz_target entries),
+    uniform distinct columns, entries shuffled: unsorted COO."""
+    rng = np.random.default_rng(seed)
+    M = N
+    max_row = min(max_row, M)
+    k = np.arange(1, max_row + 1, dtype=np.float64)
+    w = k ** (-zipf)
+    cdf = np.cumsum(w / w.sum())
+    L = np.minimum(np.searchsorted(cdf, rng.random(N)), max_row - 1) + 1
+    keep = min(1.0, nnz_target / float(L.sum()))
+    L = rng.binomial(L, keep)
+    row = np.repeat(np.arange(N, dtype=np.int64), L)
+    col = rng.integers(0, M, len(row))
+    key = np.unique(row * M + col)        # distinct columns inside every row
+    del row, col
+    key = rng.permutation(key)            # unsorted COO
+    row, col = _i32(key // M), _i32(key % M)
+    del key
+    vals = _values(rng, len(row), dtype, "u11")
+    x = dense_vector(M, seed + 1000, dtype, "u11")
+    return {"coo": coo_spec(N, M, row, col, vals, ordered=False, name="c4-coo"),
+            "x": x, "nnz": len(row)}
+
+
+def config5(dims=(100_000, 80_000, 50_000), nnz=50_000_000, zipf=1.5, rank=32,
+            seed=SEED_BASE + 5, dtype=np.float32):
+    """Skewed 3rd-order tensor (mode 0 Zipf), as sorted COO and as CSF, plus the
+    dense TTV vector and the two rank-`rank` factor matrices."""
+    ci, cj, ck, vals = random_coo3_entries(dims, nnz, seed, dtype, "u01", skew=zipf)
+    rng = np.random.default_rng(seed + 1000)
+    c = rng.uniform(0, 1, dims[2]).astype(dtype)
+    C = rng.uniform(0, 1, (dims[1], rank)).astype(dtype)
+    D = rng.uniform(0, 1, (dims[2], rank)).astype(dtype)
+    return {"coo": coo3_spec(dims, ci, cj, ck, vals, name="c5-coo"),
+            "csf": csf3_from_sorted_coo(dims, ci, cj, ck, vals, name="c5-csf"),
+            "c": c, "C": C, "D": D, "nnz": len(vals)}
