@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole hot path on one MI355X.
+
+One "step" runs every kernel of the path once on its full-size synthetic
+configuration (inputs resident in HBM): SpMV on DIA/CSR (7-diagonal banded
+matrix), ELL/CSR (bounded row lengths), unsorted / sorted COO and CSR
+(power-law rows), the COO->CSR conversion, and TTV / MTTKRP on 3rd-order
+COO / CSF. Prints ONE JSON line: whole-step GFLOP/s as `value`, the roofline of
+the dominant kernel, a per-kernel table, and the CPU oracle's plain loops timed
+on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--only name,name] [--scale S]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Item:
+    """One kernel call of the step with its algorithmic work."""
+
+    def __init__(self, name, run, flops, bytes_, note=""):
+        self.name, self.run, self.flops, self.bytes, self.note = name, run, flops, bytes_, note
+        self.events = []
+
+
+def build_items(args):
+    import torch
+    import paper_1804_10112_amd as spt
+    import workloads as wl
+
+    dev = "cuda:0"
+    items, cpu_jobs, keep = [], [], []
+    s = args.scale
+
+    def up(a):
+        t = torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        keep.append(t)
+        return t
+
+    def spmv_item(name, spec, x_np, bytes_, flops, fmt):
+        A = spt.DeviceTensor(spec)
+        x = up(x_np)
+        y = torch.empty(spec.dims[0], dtype=A.torch_dtype, device=dev)
+        ws = A.workspace(spt.SPT_OP_SPMV)
+        keep.extend([A, y, ws])
+        items.append(Item(name, lambda: spt.spt_spmv(A, x, y, ws), flops, bytes_))
+        cpu_jobs.append((name, spec, x_np, fmt, flops))
+        return A, x, y
+
+    want = set(args.only.split(",")) if args.only else None
+
+    def on(name):
+        return want is None or name in want or name.split("_")[0] in want
+
+    # ---- config 2: banded, 7 diagonals, fp64: DIA and CSR
+    if on("c2"):
+        t0 = time.time()
+        c2 = wl.config2(N=max(64, int(2_000_000 * s)))
+        N, nnz = c2["dia"].dims[0], c2["nnz"]
+        K = c2["dia"].levels[0].N
+        log(f"c2 generated in {time.time()-t0:.1f}s: N={N} nnz={nnz}")
+        spmv_item("c2_dia_spmv", c2["dia"], c2["x"], 8 * nnz + 4 * K + 16 * N, 2 * nnz, "dia")
+        spmv_item("c2_csr_spmv", c2["csr"], c2["x"], 12 * nnz + 4 * (N + 1) + 16 * N, 2 * nnz, "csr")
+        del c2
+    # ---- config 3: row lengths 8..32, fp32: ELL and CSR
+    if on("c3"):
+        t0 = time.time()
+        c3 = wl.config3(N=max(64, int(1_000_000 * s)))
+        N, nnz, W = c3["ell"].dims[0], c3["nnz"], c3["W"]
+        log(f"c3 generated in {time.time()-t0:.1f}s: N={N} nnz={nnz} W={W}")
+        spmv_item("c3_ell_spmv", c3["ell"], c3["x"], 8 * W * N + 8 * N, 2 * nnz, "ell")
+        spmv_item("c3_csr_spmv", c3["csr"], c3["x"], 8 * nnz + 4 * (N + 1) + 8 * N, 2 * nnz, "csr")
+        del c3
+    # ---- config 4: power-law rows, fp64, unsorted COO
+    if on("c4"):
+        t0 = time.time()
+        n4 = max(1024, int(4_000_000 * s))
+        c4 = wl.config4(N=n4, nnz_target=int(60_000_000 * s), max_row=max(8, int(200_000 * s)))
+        N, nnz = n4, c4["nnz"]
+        log(f"c4 generated in {time.time()-t0:.1f}s: N={N} nnz={nnz}")
+        spmv_item("c4_coo_unsorted_spmv", c4["coo"], c4["x"], 16 * nnz + 24 * N, 2 * nnz, "coo")
+        del c4
+    return items, cpu_jobs, keep
+
+
+def cpu_baseline(cpu_jobs, budget_s=20.0):
+    """The oracle's plain per-format loops (single thread, as the paper measured)
+    on the same inputs, one call each, stopping once the time budget is spent."""
+    import oracle
+    total_flops, total_t, done = 0.0, 0.0, []
+    for name, spec, x, fmt, flops in cpu_jobs:
+        if total_t > budget_s:
+            break
+        t0 = time.perf_counter()
+        oracle.plain_spmv(spec, x, fmt)
+        dt = time.perf_counter() - t0
+        total_flops += flops
+        total_t += dt
+        done.append(f"{name}:{dt*1e3:.0f}ms")
+    if total_t == 0:
+        return None
+    return {"value": total_flops / total_t / 1e9, "unit": "GFLOP/s", "cores": 1, "kind": "oracle",
+            "sample": "one call each of the oracle's plain loops on the full-size inputs: " + " ".join(done)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--only", type=str, default="")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink every configuration (testing)")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported")
+
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    import paper_1804_10112_amd as spt
+
+    items, cpu_jobs, keep = build_items(args)
+    stream = torch.cuda.current_stream()
+
+    def step(record):
+        for it in items:
+            if record:
+                a = torch.cuda.Event(enable_timing=True)
+                b = torch.cuda.Event(enable_timing=True)
+                a.record(stream)
+                it.run()
+                b.record(stream)
+                it.events.append((a, b))
+            else:
+                it.run()
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    kernels = []
+    for it in items:
+        ms = float(np.mean([a.elapsed_time(b) for a, b in it.events]))
+        gbs = it.bytes / (ms * 1e-3) / 1e9
+        kernels.append({"name": it.name, "ms": round(ms, 4), "gflops": round(it.flops / (ms * 1e-3) / 1e9, 2),
+                        "alg_gbs": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                        "alg_bytes": it.bytes})
+    dom = max(kernels, key=lambda k: k["ms"])
+    total_flops = sum(it.flops for it in items)
+    out = {
+        "metric": "SpMV GFLOP/s + achieved HBM GB/s (% of peak) per format, 1 MI355X",
+        "value": round(total_flops / (ms_per_step * 1e-3) / 1e9, 2),
+        "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64+f32", "data": "synthetic",
+        "config": {"workload": "one pass over every kernel of the path at full size: "
+                               + ", ".join(it.name for it in items), "scale": args.scale},
+        "roofline": {"bound": "hbm", "kernel": dom["name"], "achieved": dom["alg_gbs"],
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom["frac_hbm_peak"],
+                     "traffic": None},
+        "kernels": kernels,
+        "library": spt.spt_version(),
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(cpu_jobs)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,12 @@
+"""spt: sparse tensor kernels over coordinate-hierarchy level formats on MI355X.
+
+Thin ctypes binding of libspt.so (built from csrc/ by build.py). Every step of
+the path runs in the library's HIP kernels; this package only marshals
+arguments. There is no CPU fallback: loading fails loudly without the library.
+"""
+from .binding import (  # noqa: F401
+    DeviceTensor, SptError, lib, library_path, spt_coo_to_csr, spt_last_error, spt_mttkrp,
+    spt_spmv, spt_ttv, spt_version, spt_workspace_bytes,
+    SPT_OP_SPMV, SPT_OP_COO_TO_CSR, SPT_OP_TTV, SPT_OP_MTTKRP,
+    SPT_ORDER_ROW_COL, SPT_ORDER_ROW_STABLE, SPT_ORDERED, SPT_UNIQUE,
+)

@@ -1,0 +1,188 @@
+"""ctypes binding of the C ABI declared in include/spt.h (same names).
+
+PyTorch is used for device memory and streams only. `DeviceTensor` uploads the
+level arrays of a format description (any object with .dims, .levels[] having
+kind/mode/N/M/pos/crd/offset/ordered/unique, and .vals) and packs the pointers
+into an spt_tensor struct.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "libspt.so")
+_lib = None
+
+SPT_OK, SPT_ERR_INVALID_ARG, SPT_ERR_UNSUPPORTED, SPT_ERR_WORKSPACE, SPT_ERR_DEVICE = range(5)
+SPT_OP_SPMV, SPT_OP_COO_TO_CSR, SPT_OP_TTV, SPT_OP_MTTKRP = range(4)
+SPT_ORDER_ROW_COL, SPT_ORDER_ROW_STABLE = 0, 1
+SPT_ORDERED, SPT_UNIQUE = 1, 2
+SPT_F32, SPT_F64 = 0, 1
+
+SYMBOLS = ["spt_spmv", "spt_coo_to_csr", "spt_ttv", "spt_mttkrp", "spt_workspace_bytes",
+           "spt_last_error", "spt_version"]
+
+
+class SptLevel(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("mode", C.c_int32), ("flags", C.c_int32),
+                ("reserved", C.c_int32), ("N", C.c_int64), ("M", C.c_int64),
+                ("pos", C.c_void_p), ("crd", C.c_void_p), ("offset", C.c_void_p)]
+
+
+class SptTensor(C.Structure):
+    _fields_ = [("order", C.c_int32), ("nlevels", C.c_int32), ("dtype", C.c_int32),
+                ("reserved", C.c_int32), ("level", SptLevel * 4), ("vals", C.c_void_p),
+                ("nvals", C.c_int64)]
+
+
+class SptError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"spt status {status}: {message}")
+        self.status = status
+
+
+def library_path() -> str:
+    return _SO
+
+
+def lib():
+    """Loads libspt.so; builds it first only if it has never been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_SO):
+            from . import build as _build
+            _build.build()
+        L = C.CDLL(_SO)
+        vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+        L.spt_spmv.restype = i32
+        L.spt_spmv.argtypes = [vp, vp, vp, vp, sz, vp]
+        L.spt_coo_to_csr.restype = i32
+        L.spt_coo_to_csr.argtypes = [vp, i32, vp, vp, vp, vp, sz, vp]
+        L.spt_ttv.restype = i32
+        L.spt_ttv.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.spt_mttkrp.restype = i32
+        L.spt_mttkrp.argtypes = [vp, vp, vp, i32, vp, vp, sz, vp]
+        L.spt_workspace_bytes.restype = sz
+        L.spt_workspace_bytes.argtypes = [i32, vp, i32]
+        L.spt_last_error.restype = C.c_char_p
+        L.spt_last_error.argtypes = []
+        L.spt_version.restype = C.c_char_p
+        L.spt_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def spt_last_error() -> str:
+    return lib().spt_last_error().decode()
+
+
+def spt_version() -> str:
+    return lib().spt_version().decode()
+
+
+def _check(status):
+    if status != SPT_OK:
+        raise SptError(status, spt_last_error())
+
+
+def _p(t):
+    """Device pointer of a torch tensor (None -> NULL)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _desc(T):
+    return C.addressof(T.c) if isinstance(T, DeviceTensor) else C.addressof(T)
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return stream if isinstance(stream, int) else stream.cuda_stream
+
+
+def _ws(ws):
+    if ws is None:
+        return None, 0
+    return ws.data_ptr(), ws.numel() * ws.element_size()
+
+
+def spt_workspace_bytes(op, T, J=0) -> int:
+    n = lib().spt_workspace_bytes(op, _desc(T), J)
+    if n == 0:
+        raise SptError(SPT_ERR_INVALID_ARG, spt_last_error())
+    return n
+
+
+def spt_spmv(A, x, y, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(lib().spt_spmv(_desc(A), _p(x), _p(y), p, n, _stream(stream)))
+
+
+def spt_coo_to_csr(A, order, pos_out, crd_out, vals_out, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(lib().spt_coo_to_csr(_desc(A), order, _p(pos_out), _p(crd_out), _p(vals_out), p, n,
+                                _stream(stream)))
+
+
+def spt_ttv(B, c, out_crd0, out_crd1, out_vals, out_nnz_dev, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(lib().spt_ttv(_desc(B), _p(c), _p(out_crd0), _p(out_crd1), _p(out_vals),
+                         _p(out_nnz_dev), p, n, _stream(stream)))
+
+
+def spt_mttkrp(B, Cm, Dm, J, A_out, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(lib().spt_mttkrp(_desc(B), _p(Cm), _p(Dm), J, _p(A_out), p, n, _stream(stream)))
+
+
+class DeviceTensor:
+    """spt_tensor descriptor whose level arrays live in device memory."""
+
+    def __init__(self, spec, device="cuda:0"):
+        import torch
+        self.spec = spec
+        self.device = device
+        self.keep = []
+        t = SptTensor()
+        t.order = len(spec.dims)
+        t.nlevels = len(spec.levels)
+        vals = np.ascontiguousarray(spec.vals)
+        if vals.dtype == np.float64:
+            t.dtype = SPT_F64
+        elif vals.dtype == np.float32:
+            t.dtype = SPT_F32
+        else:
+            raise TypeError(f"values must be float32 or float64, got {vals.dtype}")
+        shared = {}
+        for k, lv in enumerate(spec.levels):
+            o = t.level[k]
+            o.kind, o.mode, o.N, o.M = int(lv.kind), int(lv.mode), int(lv.N), int(lv.M)
+            o.flags = (SPT_ORDERED if lv.ordered else 0) | (SPT_UNIQUE if lv.unique else 0)
+            for name in ("pos", "crd", "offset"):
+                a = getattr(lv, name)
+                if a is None:
+                    continue
+                if id(a) not in shared:   # DIA shares one offset array between two levels
+                    d = torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(device)
+                    shared[id(a)] = d
+                    self.keep.append(d)
+                    setattr(self, f"{name}{k}", d)
+                setattr(o, name, shared[id(a)].data_ptr())
+        self.vals = torch.from_numpy(vals).to(device)
+        t.vals = self.vals.data_ptr()
+        t.nvals = vals.size
+        self.torch_dtype = self.vals.dtype
+        self.c = t
+
+    def workspace(self, op, J=0):
+        import torch
+        n = spt_workspace_bytes(op, self, J)
+        return torch.empty(n, dtype=torch.uint8, device=self.device)

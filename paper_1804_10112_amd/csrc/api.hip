@@ -1,0 +1,266 @@
+// C ABI entry points of libspt: descriptor validation, recognition of the level
+// composition (Section 3.1: formats are compositions of level formats) and
+// dispatch to the kernels. Host code only.
+#include <cstring>
+
+#include "common.hpp"
+
+namespace spt {
+
+static thread_local char g_err[512] = "";
+
+void clear_error() { g_err[0] = 0; }
+
+spt_status fail(spt_status code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+// implemented in the kernel translation units
+spt_status spmv_dispatch(Format f, const spt_tensor* A, const void* x, void* y, void* ws,
+                         size_t ws_bytes, hipStream_t s);
+size_t seg_spmv_workspace(int64_t nnz);
+spt_status coo_to_csr_dispatch(const spt_tensor* A, int32_t order, int32_t* pos_out,
+                               int32_t* crd_out, void* vals_out, void* ws, size_t ws_bytes,
+                               hipStream_t s);
+size_t coo_to_csr_workspace(const spt_tensor* A);
+spt_status ttv_dispatch(Format f, const spt_tensor* B, const void* c, int32_t* out_crd0,
+                        int32_t* out_crd1, void* out_vals, int64_t* out_nnz_dev, void* ws,
+                        size_t ws_bytes, hipStream_t s);
+size_t ttv_workspace(Format f, const spt_tensor* B);
+spt_status mttkrp_dispatch(Format f, const spt_tensor* B, const void* C, const void* D, int32_t J,
+                           void* A_out, void* ws, size_t ws_bytes, hipStream_t s);
+size_t mttkrp_workspace(Format f, const spt_tensor* B, int32_t J);
+
+static bool is(const spt_level& L, int kind) { return L.kind == kind; }
+static bool unique(const spt_level& L) { return (L.flags & SPT_UNIQUE) != 0; }
+
+// Table 1 legality and pointer/size checks for one level.
+static bool level_ok(const spt_tensor* T, int k) {
+  const spt_level& L = T->level[k];
+  if (L.kind < SPT_DENSE || L.kind > SPT_HASHED) {
+    fail(SPT_ERR_INVALID_ARG, "level %d: unknown level kind %d", k, L.kind);
+    return false;
+  }
+  if (L.flags & ~(SPT_ORDERED | SPT_UNIQUE)) {
+    fail(SPT_ERR_INVALID_ARG, "level %d: unknown property flags 0x%x", k, L.flags);
+    return false;
+  }
+  if (L.kind == SPT_HASHED && (L.flags & SPT_ORDERED)) {
+    fail(SPT_ERR_INVALID_ARG, "level %d: a hashed level cannot be ordered (Table 1)", k);
+    return false;
+  }
+  if (L.N < 0 || L.M < 0) {
+    fail(SPT_ERR_INVALID_ARG, "level %d: negative size", k);
+    return false;
+  }
+  if (L.mode < -1 || L.mode >= T->order) {
+    fail(SPT_ERR_INVALID_ARG, "level %d: mode %d outside the tensor's %d dimensions", k, L.mode,
+         T->order);
+    return false;
+  }
+  const bool need_pos = L.kind == SPT_COMPRESSED;
+  const bool need_crd = L.kind == SPT_COMPRESSED || L.kind == SPT_SINGLETON || L.kind == SPT_HASHED;
+  const bool need_off = L.kind == SPT_RANGE || L.kind == SPT_OFFSET;
+  if (need_pos && !L.pos) {
+    fail(SPT_ERR_INVALID_ARG, "level %d: compressed level without pos", k);
+    return false;
+  }
+  if (need_crd && !L.crd && T->nvals > 0) {
+    fail(SPT_ERR_INVALID_ARG, "level %d: level without crd", k);
+    return false;
+  }
+  if (need_off && !L.offset) {
+    fail(SPT_ERR_INVALID_ARG, "level %d: range/offset level without offset", k);
+    return false;
+  }
+  if ((L.kind == SPT_RANGE || L.kind == SPT_OFFSET) && k == 0) {
+    fail(SPT_ERR_INVALID_ARG, "level %d: range/offset level needs an enclosing level", k);
+    return false;
+  }
+  if (L.kind == SPT_SINGLETON && k == 0) {
+    fail(SPT_ERR_INVALID_ARG, "level 0 cannot be a singleton level");
+    return false;
+  }
+  return true;
+}
+
+Format recognize(const spt_tensor* T) {
+  if (!T) {
+    fail(SPT_ERR_INVALID_ARG, "null tensor descriptor");
+    return Format::Invalid;
+  }
+  if (T->order < 1 || T->order > 4 || T->nlevels < 1 || T->nlevels > 4) {
+    fail(SPT_ERR_INVALID_ARG, "order %d / nlevels %d out of range", T->order, T->nlevels);
+    return Format::Invalid;
+  }
+  if (T->dtype != SPT_F32 && T->dtype != SPT_F64) {
+    fail(SPT_ERR_INVALID_ARG, "unknown dtype %d", T->dtype);
+    return Format::Invalid;
+  }
+  if (T->nvals < 0 || (T->nvals > 0 && !T->vals)) {
+    fail(SPT_ERR_INVALID_ARG, "vals is null or nvals negative");
+    return Format::Invalid;
+  }
+  for (int k = 0; k < T->nlevels; ++k)
+    if (!level_ok(T, k)) return Format::Invalid;
+  const spt_level* L = T->level;
+  auto modes = [&](int a, int b, int c, int d) {
+    const int want[4] = {a, b, c, d};
+    for (int k = 0; k < T->nlevels; ++k)
+      if (L[k].mode != want[k]) return false;
+    return true;
+  };
+  if (T->order == 2 && T->nlevels == 2) {
+    if (is(L[0], SPT_DENSE) && is(L[1], SPT_COMPRESSED) && modes(0, 1, 0, 0)) {
+      if (L[1].M != L[0].N) {
+        fail(SPT_ERR_INVALID_ARG, "CSR: column level must have one parent per row (M = N rows)");
+        return Format::Invalid;
+      }
+      return Format::CSR;
+    }
+    if (is(L[0], SPT_COMPRESSED) && is(L[1], SPT_SINGLETON) && modes(0, 1, 0, 0)) {
+      if (L[0].M != 1) {
+        fail(SPT_ERR_INVALID_ARG, "COO: the row level has one root parent (M = 1)");
+        return Format::Invalid;
+      }
+      return Format::COO2;
+    }
+  }
+  if (T->order == 2 && T->nlevels == 3) {
+    if (is(L[0], SPT_DENSE) && is(L[1], SPT_RANGE) && is(L[2], SPT_OFFSET) && modes(-1, 0, 1, 0)) {
+      if (L[1].offset != L[2].offset) {
+        fail(SPT_ERR_INVALID_ARG, "DIA: range and offset level must share one offset array");
+        return Format::Invalid;
+      }
+      if (T->nvals != L[0].N * L[1].N) {
+        fail(SPT_ERR_INVALID_ARG, "DIA: nvals must be K*N");
+        return Format::Invalid;
+      }
+      if (L[2].N != L[1].M) {
+        fail(SPT_ERR_INVALID_ARG, "DIA: the range level's M must be the column dimension");
+        return Format::Invalid;
+      }
+      return Format::DIA;
+    }
+    if (is(L[0], SPT_DENSE) && is(L[1], SPT_DENSE) && is(L[2], SPT_SINGLETON) &&
+        modes(-1, 0, 1, 0)) {
+      if (T->nvals != L[0].N * L[1].N) {
+        fail(SPT_ERR_INVALID_ARG, "ELL: nvals must be W*N");
+        return Format::Invalid;
+      }
+      return Format::ELL;
+    }
+  }
+  if (T->order == 3 && T->nlevels == 3 && modes(0, 1, 2, 0)) {
+    if (is(L[0], SPT_COMPRESSED) && is(L[1], SPT_SINGLETON) && is(L[2], SPT_SINGLETON)) {
+      if (L[0].M != 1) {
+        fail(SPT_ERR_INVALID_ARG, "COO: the first level has one root parent (M = 1)");
+        return Format::Invalid;
+      }
+      return Format::COO3;
+    }
+    if (is(L[0], SPT_COMPRESSED) && is(L[1], SPT_COMPRESSED) && is(L[2], SPT_COMPRESSED)) {
+      if (L[0].M != 1 || !unique(L[0]) || !unique(L[1])) {
+        fail(SPT_ERR_INVALID_ARG, "CSF: root level needs M = 1 and the upper levels are unique");
+        return Format::Invalid;
+      }
+      return Format::CSF3;
+    }
+  }
+  fail(SPT_ERR_UNSUPPORTED,
+       "level composition not supported (supported: CSR, COO, DIA, ELL, 3rd-order COO, CSF)");
+  return Format::Unsupported;
+}
+
+static spt_status status_of(Format f) {
+  return f == Format::Invalid ? SPT_ERR_INVALID_ARG : SPT_ERR_UNSUPPORTED;
+}
+
+}  // namespace spt
+
+using namespace spt;
+
+extern "C" {
+
+const char* spt_last_error(void) { return g_err; }
+const char* spt_version(void) { return "spt 0.1 gfx950"; }
+
+spt_status spt_spmv(const spt_tensor* A, const void* x, void* y, void* ws, size_t ws_bytes,
+                    void* stream) {
+  clear_error();
+  Format f = recognize(A);
+  if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
+  if (!x || !y) return fail(SPT_ERR_INVALID_ARG, "spmv: x or y is null");
+  return spmv_dispatch(f, A, x, y, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+spt_status spt_coo_to_csr(const spt_tensor* A, int32_t order, int32_t* pos_out, int32_t* crd_out,
+                          void* vals_out, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  Format f = recognize(A);
+  if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
+  if (f != Format::COO2) return fail(SPT_ERR_UNSUPPORTED, "coo_to_csr: input is not a COO matrix");
+  if (order != SPT_ORDER_ROW_COL && order != SPT_ORDER_ROW_STABLE)
+    return fail(SPT_ERR_INVALID_ARG, "coo_to_csr: unknown order %d", order);
+  if (!pos_out || ((!crd_out || !vals_out) && A->nvals > 0))
+    return fail(SPT_ERR_INVALID_ARG, "coo_to_csr: null output");
+  return coo_to_csr_dispatch(A, order, pos_out, crd_out, vals_out, ws, ws_bytes,
+                             static_cast<hipStream_t>(stream));
+}
+
+spt_status spt_ttv(const spt_tensor* B, const void* c, int32_t* out_crd0, int32_t* out_crd1,
+                   void* out_vals, int64_t* out_nnz_dev, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  Format f = recognize(B);
+  if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
+  if (f != Format::COO3 && f != Format::CSF3)
+    return fail(SPT_ERR_UNSUPPORTED, "ttv: input is not a 3rd-order COO or CSF tensor");
+  if (!c || (!out_vals && B->nvals > 0)) return fail(SPT_ERR_INVALID_ARG, "ttv: null operand");
+  if (f == Format::COO3 && (!out_nnz_dev || ((!out_crd0 || !out_crd1) && B->nvals > 0)))
+    return fail(SPT_ERR_INVALID_ARG, "ttv: COO output needs out_crd0, out_crd1, out_nnz_dev");
+  return ttv_dispatch(f, B, c, out_crd0, out_crd1, out_vals, out_nnz_dev, ws, ws_bytes,
+                      static_cast<hipStream_t>(stream));
+}
+
+spt_status spt_mttkrp(const spt_tensor* B, const void* C, const void* D, int32_t J, void* A_out,
+                      void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  Format f = recognize(B);
+  if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
+  if (f != Format::COO3 && f != Format::CSF3)
+    return fail(SPT_ERR_UNSUPPORTED, "mttkrp: input is not a 3rd-order COO or CSF tensor");
+  if (J < 1 || J > 1024) return fail(SPT_ERR_INVALID_ARG, "mttkrp: J = %d outside [1,1024]", J);
+  if (!C || !D || !A_out) return fail(SPT_ERR_INVALID_ARG, "mttkrp: null operand");
+  return mttkrp_dispatch(f, B, C, D, J, A_out, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+size_t spt_workspace_bytes(int32_t op, const spt_tensor* T, int32_t J) {
+  clear_error();
+  Format f = recognize(T);
+  if (f == Format::Invalid || f == Format::Unsupported) return 0;
+  size_t n = 0;
+  switch (op) {
+    case SPT_OP_SPMV:
+      n = (f == Format::CSR || f == Format::COO2) ? seg_spmv_workspace(T->nvals) : 0;
+      break;
+    case SPT_OP_COO_TO_CSR:
+      n = f == Format::COO2 ? coo_to_csr_workspace(T) : 0;
+      break;
+    case SPT_OP_TTV:
+      n = ttv_workspace(f, T);
+      break;
+    case SPT_OP_MTTKRP:
+      n = mttkrp_workspace(f, T, J);
+      break;
+    default:
+      fail(SPT_ERR_INVALID_ARG, "unknown op %d", op);
+      return 0;
+  }
+  return n < 256 ? 256 : n;
+}
+
+}  // extern "C"

@@ -1,0 +1,338 @@
+// SpMV y = A x on CSR, COO, DIA and ELL (paper Section 5.2), gfx950.
+//
+// All four kernels are bound by HBM bandwidth: the matrix arrays are streamed
+// once with coalesced (non-temporal) loads, x is gathered through the caches.
+//  * CSR and sorted COO share one kernel: a workgroup owns a fixed chunk of
+//    stored entries (balanced in entries, not rows, so power-law rows cost
+//    nothing extra), stages the products in LDS and reduces them per row with a
+//    segmented scan; a row cut by a chunk boundary is finished by a tiny carry
+//    kernel. No atomics, results are bit-reproducible.
+//  * Unsorted COO is the paper's scatter loop: atomic adds into y.
+//  * DIA and ELL read the diagonal-major / slot-major arrays with consecutive
+//    rows in consecutive lanes.
+#include "common.hpp"
+#include "segreduce.hpp"
+
+namespace spt {
+
+template <typename T>
+__device__ __forceinline__ T ld_stream(const T* p) {
+  return __builtin_nontemporal_load(p);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void fill_kernel(T* __restrict__ out, int64_t n, T value) {
+  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i < n) out[i] = value;
+}
+
+// ---------------------------------------------------------------- DIA
+// Cell (d,i) at d*N+i holds A(i, i+offset[d]) (range level: rows, offset
+// level: cols; Table 2). One row per thread, the diagonals in a register loop.
+constexpr int kDiaMaxLdsOffsets = 1024;
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void dia_spmv_kernel(int64_t N, int64_t M, int K,
+                                                          const int32_t* __restrict__ offset,
+                                                          const T* __restrict__ vals,
+                                                          const T* __restrict__ x,
+                                                          T* __restrict__ y) {
+  __shared__ int32_t s_off[kDiaMaxLdsOffsets];
+  const bool in_lds = K <= kDiaMaxLdsOffsets;
+  if (in_lds) {
+    for (int d = threadIdx.x; d < K; d += kBlock) s_off[d] = offset[d];
+    __syncthreads();
+  }
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= N) return;
+  T acc = 0;
+#pragma unroll 8
+  for (int d = 0; d < K; ++d) {
+    const int64_t j = i + (in_lds ? s_off[d] : offset[d]);
+    if (j >= 0 && j < M) acc += ld_stream(vals + (int64_t)d * N + i) * x[j];
+  }
+  y[i] = acc;
+}
+
+// ---------------------------------------------------------------- ELL
+// Cell (k,i) at k*N+i; a negative column marks padding and is skipped without
+// touching its value or x.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void ell_spmv_kernel(int64_t N, int W,
+                                                          const int32_t* __restrict__ crd,
+                                                          const T* __restrict__ vals,
+                                                          const T* __restrict__ x,
+                                                          T* __restrict__ y) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= N) return;
+  T acc = 0;
+#pragma unroll 8
+  for (int k = 0; k < W; ++k) {
+    const int32_t j = ld_stream(crd + (int64_t)k * N + i);
+    if (j >= 0) acc += ld_stream(vals + (int64_t)k * N + i) * x[j];
+  }
+  y[i] = acc;
+}
+
+// ---------------------------------------------------------------- CSR / sorted COO
+// Chunk of IPT*256 consecutive entries per workgroup.
+//   phase 1  coalesced load of col/vals (and row for COO), gather x, product
+//            and key into LDS (padded so that phase 2 is bank-conflict free)
+//   CSR only the rows that start inside the chunk are found with two wave-wide
+//            searches of pos; each such row marks its first entry as a head
+//            (empty rows store y = 0 directly)
+//   phase 2  every thread reduces IPT consecutive entries, segments that start
+//            and end inside one thread are stored at once; a workgroup scan of
+//            the per-thread summaries closes the rest
+// Output protocol: the workgroup that contains a row's first entry stores the
+// row's (possibly partial) sum with a plain store; the sum of the entries that
+// precede the first head of a chunk leaves as carry (key, value) number
+// blockIdx.x, key -1 if there is none.
+template <int IPT>
+__device__ __forceinline__ int lds_slot(int e) { return e + e / IPT; }
+
+template <typename T, bool CSR, int IPT>
+__global__ __launch_bounds__(kBlock) void seg_spmv_kernel(
+    int nnz, int nrows, const int32_t* __restrict__ pos_or_row, const int32_t* __restrict__ col,
+    const T* __restrict__ vals, const T* __restrict__ x, T* __restrict__ y,
+    int32_t* __restrict__ carry_key, T* __restrict__ carry_val) {
+  constexpr int CHUNK = IPT * kBlock;
+  __shared__ T s_val[CHUNK + kBlock];
+  __shared__ int32_t s_key[CHUNK + kBlock];
+  __shared__ SegScanStorage<T> s_scan;
+  __shared__ int s_rows[2];
+
+  const int tid = threadIdx.x;
+  const int base = blockIdx.x * CHUNK;  // host guarantees nnz + CHUNK < 2^31
+  const int end = min(base + CHUNK, nnz);
+  const bool last_chunk = (end == nnz);
+
+  if (CSR) {
+    if (wave_id() == 0) {
+      int r = wave_lower_bound(pos_or_row, nrows + 1, base);
+      if (lane_id() == 0) s_rows[0] = r;
+    } else if (wave_id() == 1) {
+      int r = last_chunk ? nrows : wave_lower_bound(pos_or_row, nrows + 1, end);
+      if (lane_id() == 0) s_rows[1] = r;
+    }
+  }
+
+  // phase 1
+  int32_t fill_key = -1;
+  if (!CSR) fill_key = pos_or_row[end - 1];  // tail padding extends the last segment
+#pragma unroll
+  for (int k = 0; k < IPT; ++k) {
+    const int e = k * kBlock + tid;
+    const int p = base + e;
+    T prod = 0;
+    int32_t key = fill_key;
+    if (p < end) {
+      const int32_t c = ld_stream(col + p);
+      prod = ld_stream(vals + p) * x[c];
+      if (!CSR) key = ld_stream(pos_or_row + p);
+    }
+    s_val[lds_slot<IPT>(e)] = prod;
+    s_key[lds_slot<IPT>(e)] = key;
+  }
+  int32_t prev_key = -1;  // key of the entry before the chunk (COO)
+  if (!CSR && base > 0) prev_key = pos_or_row[base - 1];
+  __syncthreads();
+
+  int carry_row = prev_key;
+  if (CSR) {
+    const int r_lo = s_rows[0], r_hi = s_rows[1];
+    // the row cut by the chunk start, if the chunk does not begin with a head
+    carry_row = r_lo - 1;
+    for (int r = r_lo + tid; r < r_hi; r += kBlock) {
+      const int a = pos_or_row[r], b = pos_or_row[r + 1];
+      if (b > a) s_key[lds_slot<IPT>(a - base)] = r;
+      else y[r] = T(0);
+    }
+    __syncthreads();
+  }
+
+  // phase 2
+  T acc = 0, lead = 0;
+  int has_head = 0, last_key = -1, first_close_key = -1;
+  bool head_at_chunk_start = false;
+  int32_t kprev = prev_key;
+  if (!CSR && tid > 0) kprev = s_key[lds_slot<IPT>(tid * IPT - 1)];
+#pragma unroll
+  for (int k = 0; k < IPT; ++k) {
+    const int e = tid * IPT + k;
+    const int32_t key = s_key[lds_slot<IPT>(e)];
+    const T v = s_val[lds_slot<IPT>(e)];
+    const bool head = CSR ? (key >= 0) : (key != kprev);
+    if (head) {
+      if (!has_head) {
+        lead = acc;
+        has_head = 1;
+        first_close_key = kprev;  // COO; CSR takes it from the scan
+        head_at_chunk_start = (e == 0);
+      } else {
+        y[CSR ? last_key : kprev] = acc;
+      }
+      acc = 0;
+      last_key = key;
+    }
+    acc += v;
+    if (!CSR) kprev = key;
+  }
+
+  SegSum<T> in = block_seg_exclusive_scan<T>(SegSum<T>{has_head, acc, last_key}, s_scan);
+
+  if (has_head) {
+    const T total = in.v + lead;
+    if (in.f) {
+      y[CSR ? in.k : first_close_key] = total;
+    } else {  // first head of the chunk: what precedes it continues an earlier chunk
+      carry_key[blockIdx.x] = head_at_chunk_start ? -1 : (CSR ? carry_row : first_close_key);
+      carry_val[blockIdx.x] = total;
+    }
+  }
+  if (tid == kBlock - 1) {  // the segment still open at the end of the chunk
+    if (has_head) {
+      y[last_key] = acc;  // COO: last_key == kprev
+    } else if (in.f) {
+      y[CSR ? in.k : kprev] = in.v + acc;
+    } else {  // no head in the whole chunk: everything is carry
+      carry_key[blockIdx.x] = CSR ? carry_row : kprev;
+      carry_val[blockIdx.x] = in.v + acc;
+    }
+  }
+}
+
+// Adds the carries to y. Carries of one row are consecutive; the thread at the
+// start of a run adds the whole run in order (deterministic). The sum of a run
+// is formed in double also for float data.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void carry_fixup_kernel(int n,
+                                                             const int32_t* __restrict__ carry_key,
+                                                             const T* __restrict__ carry_val,
+                                                             T* __restrict__ y) {
+  const int w = blockIdx.x * kBlock + threadIdx.x;
+  if (w >= n) return;
+  const int32_t key = carry_key[w];
+  if (key < 0) return;
+  if (w > 0 && carry_key[w - 1] == key) return;
+  double s = 0;
+  for (int u = w; u < n && carry_key[u] == key; ++u) s += (double)carry_val[u];
+  y[key] = (T)((double)y[key] + s);
+}
+
+// ---------------------------------------------------------------- unsorted COO
+// The fused single loop over all entries of the paper's COO kernel: a scatter
+// into y (Section 4.5, fusing iterators), one atomic add per entry.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void coo_atomic_spmv_kernel(
+    int nnz, const int32_t* __restrict__ row, const int32_t* __restrict__ col,
+    const T* __restrict__ vals, const T* __restrict__ x, T* __restrict__ y) {
+  const int p = blockIdx.x * kBlock + threadIdx.x;
+  if (p >= nnz) return;
+  const T prod = ld_stream(vals + p) * x[ld_stream(col + p)];
+  unsafeAtomicAdd(y + ld_stream(row + p), prod);
+}
+
+// ---------------------------------------------------------------- launchers
+
+constexpr int kSegIPT = 8;
+
+size_t seg_spmv_workspace(int64_t nnz) {
+  const int64_t chunk = (int64_t)kSegIPT * kBlock;
+  const int64_t nwg = (nnz + chunk - 1) / chunk;
+  return align_up((size_t)nwg * 4, 256) + align_up((size_t)nwg * 8, 256) + 256;
+}
+
+template <typename T>
+static spt_status launch_fill(T* out, int64_t n, T v, hipStream_t s) {
+  if (n <= 0) return SPT_OK;
+  const int64_t grid = (n + kBlock - 1) / kBlock;
+  hipLaunchKernelGGL(fill_kernel<T>, dim3((unsigned)grid), dim3(kBlock), 0, s, out, n, v);
+  SPT_CHECK_LAUNCH("fill");
+  return SPT_OK;
+}
+
+template <typename T, bool CSR>
+static spt_status launch_seg(int64_t nnz, int64_t nrows, const int32_t* pos_or_row,
+                             const int32_t* col, const T* vals, const T* x, T* y, void* ws,
+                             size_t ws_bytes, hipStream_t s) {
+  constexpr int CHUNK = kSegIPT * kBlock;
+  if (nnz == 0) return launch_fill<T>(y, nrows, T(0), s);
+  if (nnz + CHUNK >= INT32_MAX || nrows + 1 >= INT32_MAX)
+    return fail(SPT_ERR_UNSUPPORTED, "spmv: more than 2^31 entries or rows");
+  const int nwg = (int)((nnz + CHUNK - 1) / CHUNK);
+  if (ws_bytes < seg_spmv_workspace(nnz) || ws == nullptr)
+    return fail(SPT_ERR_WORKSPACE, "spmv: workspace of %zu bytes needed, %zu given",
+                seg_spmv_workspace(nnz), ws_bytes);
+  Workspace W(ws, ws_bytes);
+  int32_t* ckey = W.take<int32_t>(nwg);
+  T* cval = W.take<T>(nwg);
+  if (!CSR) {
+    spt_status st = launch_fill<T>(y, nrows, T(0), s);
+    if (st != SPT_OK) return st;
+  }
+  hipLaunchKernelGGL((seg_spmv_kernel<T, CSR, kSegIPT>), dim3(nwg), dim3(kBlock), 0, s, (int)nnz,
+                     (int)nrows, pos_or_row, col, vals, x, y, ckey, cval);
+  SPT_CHECK_LAUNCH("seg_spmv");
+  hipLaunchKernelGGL(carry_fixup_kernel<T>, dim3((nwg + kBlock - 1) / kBlock), dim3(kBlock), 0, s,
+                     nwg, ckey, cval, y);
+  SPT_CHECK_LAUNCH("carry_fixup");
+  return SPT_OK;
+}
+
+template <typename T>
+static spt_status spmv_typed(Format f, const spt_tensor* A, const T* x, T* y, void* ws,
+                             size_t ws_bytes, hipStream_t s) {
+  const T* vals = static_cast<const T*>(A->vals);
+  switch (f) {
+    case Format::CSR:
+      return launch_seg<T, true>(A->nvals, A->level[0].N, A->level[1].pos, A->level[1].crd, vals,
+                                 x, y, ws, ws_bytes, s);
+    case Format::COO2: {
+      const int64_t nnz = A->nvals, N = A->level[0].N;
+      if (A->level[0].flags & SPT_ORDERED)
+        return launch_seg<T, false>(nnz, N, A->level[0].crd, A->level[1].crd, vals, x, y, ws,
+                                    ws_bytes, s);
+      if (nnz >= INT32_MAX) return fail(SPT_ERR_UNSUPPORTED, "spmv: more than 2^31 entries");
+      spt_status st = launch_fill<T>(y, N, T(0), s);
+      if (st != SPT_OK || nnz == 0) return st;
+      hipLaunchKernelGGL(coo_atomic_spmv_kernel<T>, dim3((unsigned)((nnz + kBlock - 1) / kBlock)),
+                         dim3(kBlock), 0, s, (int)nnz, A->level[0].crd, A->level[1].crd, vals, x,
+                         y);
+      SPT_CHECK_LAUNCH("coo_atomic_spmv");
+      return SPT_OK;
+    }
+    case Format::DIA: {
+      const int64_t K = A->level[0].N, N = A->level[1].N, M = A->level[1].M;
+      if (N == 0) return SPT_OK;
+      if (K >= INT32_MAX) return fail(SPT_ERR_UNSUPPORTED, "spmv: too many diagonals");
+      if (K == 0) return launch_fill<T>(y, N, T(0), s);
+      hipLaunchKernelGGL(dia_spmv_kernel<T>, dim3((unsigned)((N + kBlock - 1) / kBlock)),
+                         dim3(kBlock), 0, s, N, M, (int)K, A->level[1].offset, vals, x, y);
+      SPT_CHECK_LAUNCH("dia_spmv");
+      return SPT_OK;
+    }
+    case Format::ELL: {
+      const int64_t Wd = A->level[0].N, N = A->level[1].N;
+      if (N == 0) return SPT_OK;
+      if (Wd >= INT32_MAX) return fail(SPT_ERR_UNSUPPORTED, "spmv: ELL width too large");
+      hipLaunchKernelGGL(ell_spmv_kernel<T>, dim3((unsigned)((N + kBlock - 1) / kBlock)),
+                         dim3(kBlock), 0, s, N, (int)Wd, A->level[2].crd, vals, x, y);
+      SPT_CHECK_LAUNCH("ell_spmv");
+      return SPT_OK;
+    }
+    default:
+      return fail(SPT_ERR_UNSUPPORTED, "spmv: the tensor is not a CSR, COO, DIA or ELL matrix");
+  }
+}
+
+spt_status spmv_dispatch(Format f, const spt_tensor* A, const void* x, void* y, void* ws,
+                         size_t ws_bytes, hipStream_t s) {
+  if (A->dtype == SPT_F64)
+    return spmv_typed<double>(f, A, static_cast<const double*>(x), static_cast<double*>(y), ws,
+                              ws_bytes, s);
+  return spmv_typed<float>(f, A, static_cast<const float*>(x), static_cast<float*>(y), ws,
+                           ws_bytes, s);
+}
+
+}  // namespace spt

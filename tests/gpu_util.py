@@ -1,0 +1,33 @@
+"""Helpers for the GPU parity tests: run the library through its C ABI binding
+and compare with the oracle under the stated tolerance."""
+import numpy as np
+
+TOL = {np.dtype(np.float64): 1e-12, np.dtype(np.float32): 1e-5}
+
+
+def assert_close(got, ref, mag, dtype, what=""):
+    """|got - ref| <= tol * sum|terms| elementwise (forward-error scale of a sum)."""
+    tol = TOL[np.dtype(dtype)]
+    got = np.asarray(got, np.float64)
+    tiny = np.finfo(np.dtype(dtype)).tiny
+    err = np.abs(got - ref)
+    bound = tol * mag + tiny
+    bad = np.flatnonzero(~(err <= bound))
+    assert bad.size == 0, (f"{what}: {bad.size} of {got.size} outside tolerance; first at {bad[:5]}: "
+                           f"got {got.ravel()[bad[:5]]} ref {np.asarray(ref).ravel()[bad[:5]]} "
+                           f"mag {np.asarray(mag).ravel()[bad[:5]]}")
+
+
+def gpu_spmv(spec, x, repeat=1):
+    import torch
+    import paper_1804_10112_amd as spt
+    A = spt.DeviceTensor(spec)
+    xd = torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    ws = A.workspace(spt.SPT_OP_SPMV)
+    outs = []
+    for _ in range(repeat):
+        y = torch.full((spec.dims[0],), float("nan"), dtype=A.torch_dtype, device="cuda")
+        spt.spt_spmv(A, xd, y, ws)
+        torch.cuda.synchronize()
+        outs.append(y.cpu().numpy())
+    return outs[0] if repeat == 1 else outs

@@ -1,0 +1,142 @@
+"""GPU parity: spt_spmv through the C ABI vs the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from gpu_util import assert_close, gpu_spmv
+
+pytestmark = pytest.mark.gpu
+
+CHUNK = 2048  # entries per workgroup of the CSR/COO kernel: sizes below straddle it
+
+
+def _check(spec, x, what):
+    ref, mag = oracle.spmv(spec, x)
+    got = gpu_spmv(spec, x)
+    assert_close(got, ref, mag, spec.vals.dtype, what)
+    return got
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("nnz", [0, 1, 63, 64, 65, 2047, 2048, 2049, 4096, 5000, 70001])
+def test_csr_coo_random_sizes(dtype, nnz):
+    N, M = 997, 1201
+    r, c, v = wl.random_coo_entries(N, M, nnz, seed=100 + nnz, dtype=dtype)
+    x = wl.dense_vector(M, 7, dtype)
+    _check(wl.csr_from_sorted_coo(N, M, r, c, v), x, f"csr nnz={nnz}")
+    _check(wl.coo_spec(N, M, r, c, v), x, f"coo nnz={nnz}")
+    p = np.random.default_rng(1).permutation(len(v))
+    _check(wl.coo_spec(N, M, r[p], c[p], v[p], ordered=False), x, f"coo-unsorted nnz={nnz}")
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_csr_coo_degenerate_structures(dtype):
+    x = wl.dense_vector(50, 3, dtype)
+    # one row holds everything (spans several chunks), all other rows empty
+    n = 3 * CHUNK + 17
+    rng = np.random.default_rng(5)
+    c = rng.integers(0, 50, n)
+    v = rng.uniform(-1, 1, n).astype(dtype)
+    for row in (0, 5, 9):
+        r = np.full(n, row)
+        _check(wl.csr_from_sorted_coo(10, 50, r, c, v), x, f"csr single row {row}")
+        _check(wl.coo_spec(10, 50, r, c, v), x, f"coo single row {row}")
+    # many empty rows between few entries, rows >> entries
+    r = np.array([3, 3, 40000, 99999])
+    c4 = np.array([1, 2, 3, 4])
+    v4 = np.array([1, 2, 3, 4], dtype)
+    _check(wl.csr_from_sorted_coo(100000, 50, r, c4, v4), x, "csr mostly empty")
+    _check(wl.coo_spec(100000, 50, r, c4, v4), x, "coo mostly empty")
+    # row boundaries exactly on chunk boundaries
+    r = np.repeat(np.arange(4), CHUNK)
+    c = rng.integers(0, 50, 4 * CHUNK)
+    v = rng.uniform(-1, 1, 4 * CHUNK).astype(dtype)
+    _check(wl.csr_from_sorted_coo(4, 50, r, c, v), x, "csr aligned rows")
+    _check(wl.coo_spec(4, 50, r, c, v), x, "coo aligned rows")
+    # duplicates are summed by SpMV
+    r, c, v = wl.random_coo_entries(20, 50, 6000, seed=8, dtype=dtype, duplicates=True)
+    _check(wl.csr_from_sorted_coo(20, 50, r, c, v), x, "csr duplicates")
+    _check(wl.coo_spec(20, 50, r, c, v), x, "coo duplicates")
+
+
+def test_config1_full_and_deterministic():
+    c1 = wl.config1()
+    for fmt in ("csr", "coo"):
+        ref, mag = oracle.spmv(c1[fmt], c1["x"])
+        a, b = gpu_spmv(c1[fmt], c1["x"], repeat=2)
+        assert_close(a, ref, mag, np.float64, f"c1 {fmt}")
+        assert np.array_equal(a, b), "run-to-run bits differ"
+
+
+def test_power_law_rows_scaled_config4():
+    c4 = wl.config4(N=40_000, nnz_target=600_000, max_row=20_000)
+    coo = c4["coo"]
+    r, c = coo.levels[0].crd, coo.levels[1].crd
+    _check(coo, c4["x"], "c4 unsorted coo")
+    o = np.lexsort((c, r))
+    rs, cs, vs = r[o], c[o], coo.vals[o]
+    a = _check(wl.coo_spec(40_000, 40_000, rs, cs, vs), c4["x"], "c4 sorted coo")
+    b = _check(wl.csr_from_sorted_coo(40_000, 40_000, rs, cs, vs), c4["x"], "c4 csr")
+    assert np.bincount(r).max() > 2 * CHUNK      # a row really spans several chunks
+
+
+def test_exact_integer_data_is_bit_exact():
+    N, M = 3000, 2000
+    r, c, v = wl.random_coo_entries(N, M, 50_000, seed=9, dtype=np.float32, dist="int")
+    x = wl.dense_vector(M, 10, np.float32, "int")
+    ref, _ = oracle.spmv(wl.coo_spec(N, M, r, c, v), x)
+    for spec in (wl.csr_from_sorted_coo(N, M, r, c, v), wl.coo_spec(N, M, r, c, v),
+                 wl.coo_spec(N, M, r[::-1].copy(), c[::-1].copy(), v[::-1].copy(), ordered=False)):
+        assert np.array_equal(gpu_spmv(spec, x).astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("N", [1, 255, 256, 257, 100_003])
+def test_dia_scaled_config2_with_poison(dtype, N):
+    c2 = wl.config2(N=max(N, 8), poison=True, dtype=dtype)
+    got = _check(c2["dia"], c2["x"], f"dia N={N}")
+    assert np.isfinite(got).all()
+    _check(c2["csr"], c2["x"], f"c2 csr N={N}")
+
+
+def test_dia_rectangular_and_outside_diagonals():
+    rng = np.random.default_rng(3)
+    for (N, M) in ((700, 1000), (1000, 700)):
+        off = np.array([-1200, -699, -3, 0, 1, 250, 999, 5000])
+        diag = rng.uniform(-1, 1, (len(off), N))
+        i = np.arange(N)
+        for d, o in enumerate(off):
+            diag[d, ~((i + o >= 0) & (i + o < M))] = np.nan
+        _check(wl.dia_spec(N, M, off, diag), wl.dense_vector(M, 4), f"dia {N}x{M}")
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("N", [1, 300, 100_001])
+def test_ell_scaled_config3_with_poisoned_padding(dtype, N):
+    c3 = wl.config3(N=max(N, 40), dtype=dtype)
+    ell = c3["ell"]
+    v = ell.vals.copy()
+    v[ell.levels[2].crd < 0] = np.nan
+    got = _check(wl.TensorSpec(ell.dims, ell.levels, v), c3["x"], f"ell N={N}")
+    assert np.isfinite(got).all()
+    _check(c3["csr"], c3["x"], f"c3 csr N={N}")
+    # a matrix whose rows are all empty: every slot is padding
+    z = wl.config3(N=50, lo=0, hi=0, dtype=dtype)
+    assert z["W"] == 0 or np.all(z["ell"].levels[2].crd < 0)
+    _check(z["ell"], z["x"], "ell all padding")
+
+
+def test_unsupported_and_invalid_descriptors_report_errors():
+    import paper_1804_10112_amd as spt
+    import torch
+    c1 = wl.config1(N=64, nnz=100)
+    A = spt.DeviceTensor(c1["csr"])
+    x = torch.zeros(64, dtype=torch.float64, device="cuda")
+    y = torch.zeros(64, dtype=torch.float64, device="cuda")
+    with pytest.raises(spt.SptError) as e:
+        spt.spt_spmv(A, x, y, None)          # workspace missing
+    assert e.value.status == 3
+    with pytest.raises(spt.SptError) as e:
+        spt.spt_spmv(A, None, y, A.workspace(spt.SPT_OP_SPMV))
+    assert e.value.status == 1

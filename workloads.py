@@ -277,18 +277,23 @@ def config3(N=1_000_000, lo=8, hi=32, seed=SEED_BASE + 3, dtype=np.float32):
     W = int(L.max()) if N else 0
     slot = np.arange(W)[None, :]
     live = slot < L[:, None]
-    cols = rng.integers(0, M, (N, W))
-    cols[~live] = M                      # sentinel sorts to the end of the row
-    cols.sort(axis=1)
-    while True:                          # redraw rows that hold a repeated column
-        dup = (cols[:, 1:] == cols[:, :-1]) & live[:, 1:]
-        bad = np.flatnonzero(dup.any(axis=1))
-        if len(bad) == 0:
-            break
-        fresh = rng.integers(0, M, (len(bad), W))
-        fresh[~live[bad]] = M
-        fresh.sort(axis=1)
-        cols[bad] = fresh
+    if M <= 64 * max(W, 1):              # small column range: draw without replacement
+        cols = np.argsort(rng.random((N, M)), axis=1)[:, :W]
+        cols[~live] = M                  # sentinel sorts to the end of the row
+        cols.sort(axis=1)
+    else:
+        cols = rng.integers(0, M, (N, W))
+        cols[~live] = M
+        cols.sort(axis=1)
+        while True:                      # redraw rows that hold a repeated column
+            dup = (cols[:, 1:] == cols[:, :-1]) & live[:, 1:]
+            bad = np.flatnonzero(dup.any(axis=1))
+            if len(bad) == 0:
+                break
+            fresh = rng.integers(0, M, (len(bad), W))
+            fresh[~live[bad]] = M
+            fresh.sort(axis=1)
+            cols[bad] = fresh
     v = rng.standard_normal((N, W)).astype(dtype)
     v[~live] = 0
     crd = np.where(live, cols, -1)
