@@ -1,8 +1,256 @@
+// COO -> CSR (paper Section 5.4, Figure 14) on gfx950.
+//
+//   1. reorder (Section 4.3 "reordering"): a stable least-significant-digit
+//      radix sort of the (row, col, value) records, 8 bits per pass, over the
+//      significant bits of the column (ROW_COL order only) and then of the row.
+//      Every pass is histogram -> exclusive scan -> stable scatter; the records
+//      themselves travel, so no gather through a permutation is needed.
+//   2. assemble pos as Table 3 prescribes for a compressed level: per-row
+//      counts (append_edges) followed by a running sum (append_finalize). On
+//      sorted rows the count of a row is (last position + 1) - first position,
+//      so each row receives exactly two integer atomics.
+// Everything is integer or bit-copy work: results are exact and deterministic.
 #include "common.hpp"
+#include "scan.hpp"
+
 namespace spt {
-size_t coo_to_csr_workspace(const spt_tensor*) { return 256; }
-spt_status coo_to_csr_dispatch(const spt_tensor*, int32_t, int32_t*, int32_t*, void*, void*, size_t,
-                               hipStream_t) {
-  return fail(SPT_ERR_UNSUPPORTED, "coo_to_csr: not built yet");
+
+constexpr int kRadixBits = 8;
+constexpr int kRadix = 1 << kRadixBits;
+constexpr int kSortIPT = 16;
+constexpr int kSortTile = kSortIPT * kBlock;  // 4096 records per workgroup
+constexpr int kWaves = kBlock / kWave;
+
+static int bits_for(int64_t dim) {
+  int b = 1;
+  while (b < 31 && ((int64_t)1 << b) < dim) ++b;
+  return b;
 }
+
+__device__ __forceinline__ int digit_of(int32_t key, int shift) {
+  return ((uint32_t)key >> shift) & (kRadix - 1);
+}
+
+// hist[d * ntiles + tile] = number of keys of this tile whose digit is d.
+__global__ __launch_bounds__(kBlock) void radix_hist_kernel(const int32_t* __restrict__ key, int n,
+                                                            int shift, int ntiles,
+                                                            int32_t* __restrict__ hist) {
+  __shared__ int s_cnt[kRadix];
+  s_cnt[threadIdx.x] = 0;
+  __syncthreads();
+  const int base = blockIdx.x * kSortTile;
+#pragma unroll
+  for (int k = 0; k < kSortIPT; ++k) {
+    const int i = base + k * kBlock + threadIdx.x;
+    if (i < n) atomicAdd(&s_cnt[digit_of(key[i], shift)], 1);
+  }
+  __syncthreads();
+  hist[(int64_t)threadIdx.x * ntiles + blockIdx.x] = s_cnt[threadIdx.x];
+}
+
+// Stable scatter of one pass. Element order inside a tile is (wave, item, lane);
+// a lane's rank among equal digits comes from a ballot-based match inside the
+// wave plus per-wave running digit counters in LDS, so equal keys keep their
+// input order. off[d * ntiles + tile] is the exclusive scan of hist.
+template <typename VT>
+__global__ __launch_bounds__(kBlock) void radix_scatter_kernel(
+    int n, int shift, int key_is_row, int ntiles, const int32_t* __restrict__ off,
+    const int32_t* __restrict__ row_in, const int32_t* __restrict__ col_in,
+    const VT* __restrict__ val_in, int32_t* __restrict__ row_out, int32_t* __restrict__ col_out,
+    VT* __restrict__ val_out) {
+  __shared__ int s_cnt[kWaves][kRadix];
+  const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
+  for (int q = tid; q < kWaves * kRadix; q += kBlock) (&s_cnt[0][0])[q] = 0;
+  __syncthreads();
+
+  const int32_t* __restrict__ key_in = key_is_row ? row_in : col_in;
+  const int wave_base = blockIdx.x * kSortTile + w * (kWave * kSortIPT);
+  const uint64_t lanes_below = ((uint64_t)1 << lane) - 1;
+  volatile int* cnt = s_cnt[w];
+
+  int32_t key[kSortIPT];
+  int rank[kSortIPT];
+#pragma unroll
+  for (int k = 0; k < kSortIPT; ++k) {
+    const int i = wave_base + k * kWave + lane;
+    const bool valid = i < n;
+    key[k] = valid ? key_in[i] : 0;
+    const int d = digit_of(key[k], shift);
+    uint64_t same = __ballot(valid);
+#pragma unroll
+    for (int b = 0; b < kRadixBits; ++b) {
+      const bool bit = (d >> b) & 1;
+      const uint64_t vote = __ballot(valid && bit);
+      same &= bit ? vote : ~vote;
+    }
+    const int before = __popcll(same & lanes_below);
+    int basecnt = 0;
+    if (valid) basecnt = cnt[d];
+    __builtin_amdgcn_wave_barrier();
+    if (valid && before == 0) cnt[d] = basecnt + __popcll(same);
+    __builtin_amdgcn_wave_barrier();
+    rank[k] = basecnt + before;
+  }
+  __syncthreads();
+  {  // thread d: turn the per-wave counts of digit d into global start offsets
+    const int d = tid;
+    int run = off[(int64_t)d * ntiles + blockIdx.x];
+#pragma unroll
+    for (int u = 0; u < kWaves; ++u) {
+      const int c = s_cnt[u][d];
+      s_cnt[u][d] = run;
+      run += c;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kSortIPT; ++k) {
+    const int i = wave_base + k * kWave + lane;
+    if (i < n) {
+      const int dst = s_cnt[w][digit_of(key[k], shift)] + rank[k];
+      if (key_is_row) {
+        row_out[dst] = key[k];
+        col_out[dst] = col_in[i];
+      } else {
+        col_out[dst] = key[k];
+        row_out[dst] = row_in[i];
+      }
+      val_out[dst] = val_in[i];
+    }
+  }
+}
+
+// Per-row counts on sorted rows, stored as Table 3's append_edges does:
+// cnt[r + 1] = number of entries of row r. cnt must be zero on entry.
+__global__ __launch_bounds__(kBlock) void row_count_kernel(const int32_t* __restrict__ row, int n,
+                                                           int32_t* __restrict__ cnt) {
+  const int p = blockIdx.x * kBlock + threadIdx.x;
+  if (p >= n) return;
+  const int32_t r = row[p];
+  if (p == 0 || row[p - 1] != r) atomicSub(&cnt[r + 1], p);
+  if (p == n - 1 || row[p + 1] != r) atomicAdd(&cnt[r + 1], p + 1);
+}
+
+template <typename VT>
+__global__ __launch_bounds__(kBlock) void copy_entries_kernel(int n, const int32_t* __restrict__ col_in,
+                                                              const VT* __restrict__ val_in,
+                                                              int32_t* __restrict__ col_out,
+                                                              VT* __restrict__ val_out) {
+  const int p = blockIdx.x * kBlock + threadIdx.x;
+  if (p < n) {
+    col_out[p] = col_in[p];
+    val_out[p] = val_in[p];
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void zero_i32_kernel(int32_t* __restrict__ out, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i < n) out[i] = 0;
+}
+
+struct SortPlan {
+  int passes_col, passes_row, ntiles;
+  size_t rec_bytes, hist_bytes, scan_bytes, total;
+};
+
+static SortPlan plan(const spt_tensor* A, int32_t order) {
+  SortPlan P;
+  const int64_t nnz = A->nvals;
+  const size_t vsz = A->dtype == SPT_F64 ? 8 : 4;
+  P.passes_col = order == SPT_ORDER_ROW_COL ? (bits_for(A->level[1].N) + kRadixBits - 1) / kRadixBits : 0;
+  P.passes_row = (bits_for(A->level[0].N) + kRadixBits - 1) / kRadixBits;
+  P.ntiles = (int)((nnz + kSortTile - 1) / kSortTile);
+  P.rec_bytes = align_up((size_t)nnz * 4, 256) * 2 + align_up((size_t)nnz * vsz, 256);
+  P.hist_bytes = align_up((size_t)kRadix * P.ntiles * 4, 256);
+  const int64_t scan_n = std::max<int64_t>((int64_t)kRadix * P.ntiles, A->level[0].N + 1);
+  P.scan_bytes = scan_workspace(scan_n);
+  P.total = 2 * P.rec_bytes + P.hist_bytes + P.scan_bytes + 256;
+  return P;
+}
+
+size_t coo_to_csr_workspace(const spt_tensor* A) {
+  return std::max(plan(A, SPT_ORDER_ROW_COL).total, plan(A, SPT_ORDER_ROW_STABLE).total);
+}
+
+template <typename VT>
+static spt_status convert_typed(const spt_tensor* A, int32_t order, int32_t* pos_out,
+                                int32_t* crd_out, VT* vals_out, void* ws, size_t ws_bytes,
+                                hipStream_t s) {
+  const int64_t nnz64 = A->nvals, N = A->level[0].N;
+  if (nnz64 + kSortTile >= INT32_MAX || N + 1 >= INT32_MAX)
+    return fail(SPT_ERR_UNSUPPORTED, "coo_to_csr: more than 2^31 entries or rows");
+  const int nnz = (int)nnz64;
+  const SortPlan P = plan(A, order);
+  if (!ws || ws_bytes < P.total)
+    return fail(SPT_ERR_WORKSPACE, "coo_to_csr: workspace of %zu bytes needed, %zu given", P.total,
+                ws_bytes);
+  const int32_t* row = A->level[0].crd;
+  const int32_t* col = A->level[1].crd;
+  const VT* vals = static_cast<const VT*>(A->vals);
+
+  hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)((N + 1 + kBlock - 1) / kBlock)), dim3(kBlock),
+                     0, s, pos_out, N + 1);
+  SPT_CHECK_LAUNCH("zero pos");
+  if (nnz == 0) return SPT_OK;
+
+  Workspace W(ws, ws_bytes);
+  int32_t* srow[2];
+  int32_t* scol[2];
+  VT* sval[2];
+  for (int b = 0; b < 2; ++b) {
+    srow[b] = W.take<int32_t>(nnz);
+    scol[b] = W.take<int32_t>(nnz);
+    sval[b] = W.take<VT>(nnz);
+  }
+  int32_t* hist = W.take<int32_t>((size_t)kRadix * P.ntiles);
+  int32_t* scan_tmp = reinterpret_cast<int32_t*>(W.take<char>(P.scan_bytes));
+
+  const bool sorted_in = (A->level[0].flags & SPT_ORDERED) &&
+                         (order == SPT_ORDER_ROW_STABLE || (A->level[1].flags & SPT_ORDERED));
+  const int32_t* sorted_rows = row;
+  const unsigned egrid = (unsigned)((nnz + kBlock - 1) / kBlock);
+  if (sorted_in) {
+    hipLaunchKernelGGL(copy_entries_kernel<VT>, dim3(egrid), dim3(kBlock), 0, s, nnz, col, vals,
+                       crd_out, vals_out);
+    SPT_CHECK_LAUNCH("copy_entries");
+  } else {
+    const int npass = P.passes_col + P.passes_row;
+    const int32_t *rin = row, *cin = col;
+    const VT* vin = vals;
+    for (int i = 0; i < npass; ++i) {
+      const bool is_row = i >= P.passes_col;
+      const int shift = kRadixBits * (is_row ? i - P.passes_col : i);
+      const bool last = i == npass - 1;
+      int32_t* rout = srow[i & 1];
+      int32_t* cout = last ? crd_out : scol[i & 1];
+      VT* vout = last ? vals_out : sval[i & 1];
+      hipLaunchKernelGGL(radix_hist_kernel, dim3(P.ntiles), dim3(kBlock), 0, s, is_row ? rin : cin,
+                         nnz, shift, P.ntiles, hist);
+      SPT_CHECK_LAUNCH("radix_hist");
+      spt_status st = device_scan_i32<false>(hist, hist, (int64_t)kRadix * P.ntiles, scan_tmp, s);
+      if (st != SPT_OK) return st;
+      hipLaunchKernelGGL(radix_scatter_kernel<VT>, dim3(P.ntiles), dim3(kBlock), 0, s, nnz, shift,
+                         (int)is_row, P.ntiles, hist, rin, cin, vin, rout, cout, vout);
+      SPT_CHECK_LAUNCH("radix_scatter");
+      rin = rout;
+      cin = cout;
+      vin = vout;
+    }
+    sorted_rows = rin;
+  }
+  hipLaunchKernelGGL(row_count_kernel, dim3(egrid), dim3(kBlock), 0, s, sorted_rows, nnz, pos_out);
+  SPT_CHECK_LAUNCH("row_count");
+  return device_scan_i32<true>(pos_out, pos_out, N + 1, scan_tmp, s);
+}
+
+spt_status coo_to_csr_dispatch(const spt_tensor* A, int32_t order, int32_t* pos_out,
+                               int32_t* crd_out, void* vals_out, void* ws, size_t ws_bytes,
+                               hipStream_t s) {
+  if (A->dtype == SPT_F64)
+    return convert_typed<uint64_t>(A, order, pos_out, crd_out, static_cast<uint64_t*>(vals_out), ws,
+                                   ws_bytes, s);
+  return convert_typed<uint32_t>(A, order, pos_out, crd_out, static_cast<uint32_t*>(vals_out), ws,
+                                 ws_bytes, s);
+}
+
 }  // namespace spt

@@ -1,0 +1,111 @@
+// Device-wide prefix sum of int32 (three plain kernels, no spin waits):
+// per-tile sums -> one workgroup scans the tile sums -> per-tile scan + offset.
+// This is the GPU form of Table 3's append_finalize (pos = running sum of the
+// per-parent counts) and of the digit offsets of every radix-sort pass.
+#pragma once
+#include "common.hpp"
+
+namespace spt {
+
+constexpr int kScanIPT = 16;
+constexpr int kScanTile = kScanIPT * kBlock;
+
+inline int64_t scan_tiles(int64_t n) { return (n + kScanTile - 1) / kScanTile; }
+inline size_t scan_workspace(int64_t n) { return align_up((size_t)(scan_tiles(n) + 1) * 4, 256); }
+
+#if defined(__HIPCC__)
+
+// Inclusive sum over the workgroup of one int per thread; returns the inclusive
+// value, *total receives the workgroup sum. One __syncthreads inside plus one
+// at entry (protects the shared array between consecutive calls).
+__device__ __forceinline__ int block_inclusive_sum(int v, int* total) {
+  __shared__ int s_w[kBlock / kWave];
+  const int lane = lane_id(), w = wave_id();
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    int u = __shfl_up(v, d);
+    if (lane >= d) v += u;
+  }
+  __syncthreads();
+  if (lane == kWave - 1) s_w[w] = v;
+  __syncthreads();
+  int pre = 0, tot = 0;
+#pragma unroll
+  for (int u = 0; u < kBlock / kWave; ++u) {
+    if (u < w) pre += s_w[u];
+    tot += s_w[u];
+  }
+  *total = tot;
+  return v + pre;
+}
+
+static __global__ __launch_bounds__(kBlock) void scan_tile_sums_kernel(const int32_t* __restrict__ in,
+                                                                int64_t n,
+                                                                int32_t* __restrict__ tile_sum) {
+  const int64_t base = (int64_t)blockIdx.x * kScanTile;
+  int s = 0;
+#pragma unroll
+  for (int k = 0; k < kScanIPT; ++k) {
+    int64_t i = base + k * kBlock + threadIdx.x;
+    if (i < n) s += in[i];
+  }
+  int total;
+  block_inclusive_sum(s, &total);
+  if (threadIdx.x == 0) tile_sum[blockIdx.x] = total;
+}
+
+// Single workgroup: exclusive scan of tile_sum[0..ntiles) in place.
+static __global__ __launch_bounds__(kBlock) void scan_spine_kernel(int32_t* __restrict__ tile_sum,
+                                                            int64_t ntiles) {
+  int carry = 0;
+  for (int64_t b = 0; b < ntiles; b += kBlock) {
+    int64_t i = b + threadIdx.x;
+    int v = i < ntiles ? tile_sum[i] : 0;
+    int total;
+    int incl = block_inclusive_sum(v, &total);
+    if (i < ntiles) tile_sum[i] = carry + incl - v;
+    carry += total;
+  }
+}
+
+// out[i] = sum of in[0..i) (+ in[i] if INCLUSIVE). in may equal out.
+template <bool INCLUSIVE>
+__global__ __launch_bounds__(kBlock) void scan_apply_kernel(const int32_t* in, int64_t n,
+                                                            const int32_t* __restrict__ tile_off,
+                                                            int32_t* out) {
+  const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanIPT;
+  int v[kScanIPT];
+  int s = 0;
+#pragma unroll
+  for (int k = 0; k < kScanIPT; ++k) {
+    v[k] = (base + k < n) ? in[base + k] : 0;
+    s += v[k];
+  }
+  int total;
+  int run = block_inclusive_sum(s, &total) - s + tile_off[blockIdx.x];
+#pragma unroll
+  for (int k = 0; k < kScanIPT; ++k) {
+    if (INCLUSIVE) run += v[k];
+    if (base + k < n) out[base + k] = run;
+    if (!INCLUSIVE) run += v[k];
+  }
+}
+
+// Enqueues the three kernels. tmp needs scan_workspace(n) bytes.
+template <bool INCLUSIVE>
+inline spt_status device_scan_i32(const int32_t* in, int32_t* out, int64_t n, int32_t* tmp,
+                                  hipStream_t s) {
+  if (n <= 0) return SPT_OK;
+  const int64_t nt = scan_tiles(n);
+  hipLaunchKernelGGL(scan_tile_sums_kernel, dim3((unsigned)nt), dim3(kBlock), 0, s, in, n, tmp);
+  SPT_CHECK_LAUNCH("scan_tile_sums");
+  hipLaunchKernelGGL(scan_spine_kernel, dim3(1), dim3(kBlock), 0, s, tmp, nt);
+  SPT_CHECK_LAUNCH("scan_spine");
+  hipLaunchKernelGGL(scan_apply_kernel<INCLUSIVE>, dim3((unsigned)nt), dim3(kBlock), 0, s, in, n,
+                     tmp, out);
+  SPT_CHECK_LAUNCH("scan_apply");
+  return SPT_OK;
+}
+
+#endif  // __HIPCC__
+}  // namespace spt

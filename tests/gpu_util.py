@@ -31,3 +31,17 @@ def gpu_spmv(spec, x, repeat=1):
         torch.cuda.synchronize()
         outs.append(y.cpu().numpy())
     return outs[0] if repeat == 1 else outs
+
+
+def gpu_coo_to_csr(spec, order):
+    import torch
+    import paper_1804_10112_amd as spt
+    A = spt.DeviceTensor(spec)
+    N, nnz = spec.dims[0], len(spec.vals)
+    pos = torch.full((N + 1,), -7, dtype=torch.int32, device="cuda")
+    crd = torch.full((max(nnz, 1),), -7, dtype=torch.int32, device="cuda")
+    vals = torch.zeros(max(nnz, 1), dtype=A.torch_dtype, device="cuda")
+    ws = A.workspace(spt.SPT_OP_COO_TO_CSR)
+    spt.spt_coo_to_csr(A, order, pos, crd, vals, ws)
+    torch.cuda.synchronize()
+    return pos.cpu().numpy(), crd.cpu().numpy()[:nnz], vals.cpu().numpy()[:nnz]

@@ -1,0 +1,83 @@
+"""GPU parity: spt_coo_to_csr vs the oracle -- every output bit-exact."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from gpu_util import gpu_coo_to_csr
+
+pytestmark = pytest.mark.gpu
+
+TILE = 4096  # records per workgroup of the radix sort: sizes below straddle it
+
+
+def _check(N, M, r, c, v, order, ordered=False, what=""):
+    spec = wl.coo_spec(N, M, r, c, v, ordered=ordered)
+    pos, crd, vout = gpu_coo_to_csr(spec, order)
+    rpos, rcrd, rv, _ = oracle.coo_to_csr(N, r, c, v, order)
+    assert np.array_equal(pos, rpos), f"{what}: pos differs"
+    assert np.array_equal(crd, rcrd), f"{what}: crd differs"
+    assert np.array_equal(vout.view(np.uint8), rv.view(np.uint8)), f"{what}: vals differ"
+    assert pos[0] == 0 and pos[-1] == len(v) and np.all(np.diff(pos) >= 0)
+
+
+@pytest.mark.parametrize("order", [0, 1])
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("nnz", [0, 1, 255, 256, 4095, 4096, 4097, 3 * 4096 + 5, 100_003])
+def test_random_unsorted(order, dtype, nnz):
+    N, M = 1500, 70_000                      # 11 row bits (2 passes), 17 col bits (3 passes)
+    r, c, v = wl.random_coo_entries(N, M, nnz, seed=200 + nnz, dtype=dtype, sort=False)
+    _check(N, M, r, c, v, order, what=f"nnz={nnz}")
+
+
+@pytest.mark.parametrize("order", [0, 1])
+def test_duplicates_keep_input_order(order):
+    N, M = 37, 19
+    r, c, v = wl.random_coo_entries(N, M, 20_000, seed=5, duplicates=True, sort=False)
+    v = np.arange(len(v), dtype=np.float64)   # values identify the input position
+    _check(N, M, r, c, v, order, what="duplicates")
+
+
+@pytest.mark.parametrize("order", [0, 1])
+def test_degenerate_shapes(order):
+    rng = np.random.default_rng(1)
+    n = 2 * TILE + 9
+    v = rng.uniform(-1, 1, n)
+    _check(1, 1, np.zeros(n, int), np.zeros(n, int), v, order, what="1x1")
+    _check(1, 300, np.zeros(n, int), rng.integers(0, 300, n), v, order, what="one row")
+    _check(300, 1, rng.integers(0, 300, n), np.zeros(n, int), v, order, what="one col")
+    _check(100_000, 3, np.array([99_999, 0, 50_000, 0]), np.array([2, 1, 0, 0]),
+           np.array([1., 2., 3., 4.]), order, what="rows >> entries")
+    big = 2**31 - 10                           # maximum dimension sizes: all 31 key bits used
+    r = np.array([big - 1, 0, big - 1, 12345, 2**30])
+    c = np.array([big - 2, 5, 0, 2**30 + 1, 7])
+    spec = wl.coo_spec(5, big, [0, 1, 2, 3, 4], c, np.arange(5.0), ordered=False)
+    pos, crd, vout = gpu_coo_to_csr(spec, order)
+    assert list(pos) == [0, 1, 2, 3, 4, 5] and np.array_equal(crd, c)
+
+
+def test_sorted_flagged_input_skips_the_sort():
+    N, M = 800, 900
+    r, c, v = wl.random_coo_entries(N, M, 30_000, seed=6)
+    _check(N, M, r, c, v, 0, ordered=True, what="flagged sorted")
+    _check(N, M, r, c, v, 1, ordered=True, what="flagged sorted, stable")
+
+
+def test_csr_to_coo_to_csr_is_a_fixed_point():
+    N, M = 500, 600
+    r, c, v = wl.random_coo_entries(N, M, 9000, seed=7, sort=False)
+    pos, crd, vout = gpu_coo_to_csr(wl.coo_spec(N, M, r, c, v, ordered=False), 0)
+    rows = np.repeat(np.arange(N), np.diff(pos))
+    pos2, crd2, v2 = gpu_coo_to_csr(wl.coo_spec(N, M, rows, crd, vout, ordered=False), 0)
+    assert np.array_equal(pos, pos2) and np.array_equal(crd, crd2) and np.array_equal(vout, v2)
+    # the multiset of (row, col, value) is preserved
+    a = np.lexsort((v, c, r))
+    b = np.lexsort((vout, crd, rows))
+    assert np.array_equal(r[a], rows[b]) and np.array_equal(c[a], crd[b]) and np.array_equal(v[a], vout[b])
+
+
+@pytest.mark.parametrize("order", [0, 1])
+def test_power_law_scaled_config4(order):
+    c4 = wl.config4(N=50_000, nnz_target=700_000, max_row=30_000)
+    coo = c4["coo"]
+    _check(50_000, 50_000, coo.levels[0].crd, coo.levels[1].crd, coo.vals, order, what="c4 scaled")
