@@ -70,4 +70,23 @@ __device__ __forceinline__ SegSum<A> block_seg_exclusive_scan(SegSum<A> me,
   return ex;
 }
 
+// Adds the carries to y. Carries of one row are consecutive; the thread at the
+// start of a run adds the whole run in order (deterministic). The sum of a run
+// is formed in double also for float data.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void carry_fixup_kernel(int n,
+                                                             const int32_t* __restrict__ carry_key,
+                                                             const T* __restrict__ carry_val,
+                                                             T* __restrict__ y) {
+  const int w = blockIdx.x * kBlock + threadIdx.x;
+  if (w >= n) return;
+  const int32_t key = carry_key[w];
+  if (key < 0) return;
+  if (w > 0 && carry_key[w - 1] == key) return;
+  double s = 0;
+  for (int u = w; u < n && carry_key[u] == key; ++u) s += (double)carry_val[u];
+  y[key] = (T)((double)y[key] + s);
+}
+
+
 }  // namespace spt

@@ -202,24 +202,6 @@ __global__ __launch_bounds__(kBlock) void seg_spmv_kernel(
   }
 }
 
-// Adds the carries to y. Carries of one row are consecutive; the thread at the
-// start of a run adds the whole run in order (deterministic). The sum of a run
-// is formed in double also for float data.
-template <typename T>
-__global__ __launch_bounds__(kBlock) void carry_fixup_kernel(int n,
-                                                             const int32_t* __restrict__ carry_key,
-                                                             const T* __restrict__ carry_val,
-                                                             T* __restrict__ y) {
-  const int w = blockIdx.x * kBlock + threadIdx.x;
-  if (w >= n) return;
-  const int32_t key = carry_key[w];
-  if (key < 0) return;
-  if (w > 0 && carry_key[w - 1] == key) return;
-  double s = 0;
-  for (int u = w; u < n && carry_key[u] == key; ++u) s += (double)carry_val[u];
-  y[key] = (T)((double)y[key] + s);
-}
-
 // ---------------------------------------------------------------- unsorted COO
 // The fused single loop over all entries of the paper's COO kernel: a scatter
 // into y (Section 4.5, fusing iterators), one atomic add per entry.
@@ -324,6 +306,20 @@ static spt_status spmv_typed(Format f, const spt_tensor* A, const T* x, T* y, vo
     default:
       return fail(SPT_ERR_UNSUPPORTED, "spmv: the tensor is not a CSR, COO, DIA or ELL matrix");
   }
+}
+
+// out[r] = sum over p in [pos[r], pos[r+1]) of vals[p] * x[crd[p]]: CSR SpMV, and
+// equally TTV on the bottom level of a CSF tensor (rows = fibers).
+spt_status csr_rows_reduce(int dtype, int64_t nnz, int64_t nrows, const int32_t* pos,
+                           const int32_t* crd, const void* vals, const void* x, void* out,
+                           void* ws, size_t ws_bytes, hipStream_t s) {
+  if (dtype == SPT_F64)
+    return launch_seg<double, true>(nnz, nrows, pos, crd, static_cast<const double*>(vals),
+                                    static_cast<const double*>(x), static_cast<double*>(out), ws,
+                                    ws_bytes, s);
+  return launch_seg<float, true>(nnz, nrows, pos, crd, static_cast<const float*>(vals),
+                                 static_cast<const float*>(x), static_cast<float*>(out), ws, ws_bytes,
+                                 s);
 }
 
 spt_status spmv_dispatch(Format f, const spt_tensor* A, const void* x, void* y, void* ws,

@@ -1,13 +1,589 @@
+// 3rd-order kernels (paper Section 5.3): TTV A_ij = sum_k B_ijk c_k and
+// MTTKRP A_ij = sum_kl B_ikl C_kj D_lj on ordered COO and on CSF, gfx950.
+//
+// Both reduce runs of consecutive stored entries that share leading
+// coordinates -- the GPU form of the paper's deduplication / iterator chaining
+// over ordered non-unique levels (Section 4.3): (i,j) fibers for TTV, i slices
+// for MTTKRP. Work is split evenly over stored entries; a run cut by a split
+// leaves a carry that a follow-up kernel adds in a fixed order (no atomics).
 #include "common.hpp"
+#include "scan.hpp"
+#include "segreduce.hpp"
+
 namespace spt {
-size_t ttv_workspace(Format, const spt_tensor*) { return 256; }
-size_t mttkrp_workspace(Format, const spt_tensor*, int32_t) { return 256; }
-spt_status ttv_dispatch(Format, const spt_tensor*, const void*, int32_t*, int32_t*, void*, int64_t*,
-                        void*, size_t, hipStream_t) {
-  return fail(SPT_ERR_UNSUPPORTED, "ttv: not built yet");
+
+spt_status csr_rows_reduce(int dtype, int64_t nnz, int64_t nrows, const int32_t* pos,
+                           const int32_t* crd, const void* vals, const void* x, void* out,
+                           void* ws, size_t ws_bytes, hipStream_t s);
+size_t seg_spmv_workspace(int64_t nnz);
+
+template <typename T>
+__device__ __forceinline__ T ldg_stream(const T* p) {
+  return __builtin_nontemporal_load(p);
 }
-spt_status mttkrp_dispatch(Format, const spt_tensor*, const void*, const void*, int32_t, void*,
-                           void*, size_t, hipStream_t) {
-  return fail(SPT_ERR_UNSUPPORTED, "mttkrp: not built yet");
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void fill_t_kernel(T* __restrict__ out, int64_t n, T value) {
+  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i < n) out[i] = value;
 }
+
+// ================================================================ TTV on COO
+
+constexpr int kTtvIPT = 8;
+constexpr int kTtvChunk = kTtvIPT * kBlock;
+
+__device__ __forceinline__ int ttv_slot(int e) { return e + e / kTtvIPT; }
+
+// heads[w] = number of (i,j) fiber starts among the entries of chunk w.
+__global__ __launch_bounds__(kBlock) void ttv_count_kernel(int nnz, const int32_t* __restrict__ ci,
+                                                           const int32_t* __restrict__ cj,
+                                                           int32_t* __restrict__ heads) {
+  const int base = blockIdx.x * kTtvChunk;
+  int cnt = 0;
+#pragma unroll
+  for (int k = 0; k < kTtvIPT; ++k) {
+    const int p = base + k * kBlock + threadIdx.x;
+    if (p < nnz) cnt += (p == 0 || ci[p] != ci[p - 1] || cj[p] != cj[p - 1]) ? 1 : 0;
+  }
+  int total;
+  block_inclusive_sum(cnt, &total);
+  if (threadIdx.x == 0) heads[blockIdx.x] = total;
+}
+
+__global__ void ttv_total_kernel(int nchunks, const int32_t* __restrict__ heads,
+                                 const int32_t* __restrict__ off, int64_t* __restrict__ out_nnz) {
+  if (threadIdx.x == 0 && blockIdx.x == 0)
+    *out_nnz = nchunks > 0 ? (int64_t)off[nchunks - 1] + heads[nchunks - 1] : 0;
+}
+
+// One output entry per fiber, at index off[chunk] + rank of the fiber's head
+// inside the chunk (append order = ascending (i,j), Section 3.4). The thread
+// holding a head appends the coordinates; the thread holding the fiber's end
+// stores the value. Carry protocol as in the SpMV kernel, keyed by output index.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void ttv_coo_kernel(
+    int nnz, const int32_t* __restrict__ ci, const int32_t* __restrict__ cj,
+    const int32_t* __restrict__ ck, const T* __restrict__ vals, const T* __restrict__ c,
+    const int32_t* __restrict__ chunk_off, int32_t* __restrict__ out_i, int32_t* __restrict__ out_j,
+    T* __restrict__ out_v, int32_t* __restrict__ carry_key, T* __restrict__ carry_val) {
+  __shared__ T s_val[kTtvChunk + kBlock];
+  __shared__ int32_t s_i[kTtvChunk + kBlock];
+  __shared__ int32_t s_j[kTtvChunk + kBlock];
+  __shared__ SegScanStorage<T> s_scan;
+
+  const int tid = threadIdx.x;
+  const int base = blockIdx.x * kTtvChunk;
+  const int end = min(base + kTtvChunk, nnz);
+  const int32_t fill_i = ci[end - 1], fill_j = cj[end - 1];
+#pragma unroll
+  for (int k = 0; k < kTtvIPT; ++k) {
+    const int e = k * kBlock + tid;
+    const int p = base + e;
+    T prod = 0;
+    int32_t i = fill_i, j = fill_j;
+    if (p < end) {
+      i = ldg_stream(ci + p);
+      j = ldg_stream(cj + p);
+      prod = ldg_stream(vals + p) * c[ldg_stream(ck + p)];
+    }
+    s_val[ttv_slot(e)] = prod;
+    s_i[ttv_slot(e)] = i;
+    s_j[ttv_slot(e)] = j;
+  }
+  int32_t pi = -1, pj = -1;  // coordinates of the entry before this thread's items
+  if (tid == 0 && base > 0) {
+    pi = ci[base - 1];
+    pj = cj[base - 1];
+  }
+  __syncthreads();
+  if (tid > 0) {
+    pi = s_i[ttv_slot(tid * kTtvIPT - 1)];
+    pj = s_j[ttv_slot(tid * kTtvIPT - 1)];
+  }
+
+  int32_t li[kTtvIPT], lj[kTtvIPT];
+  unsigned headmask = 0;
+  {
+    int32_t qi = pi, qj = pj;
+#pragma unroll
+    for (int k = 0; k < kTtvIPT; ++k) {
+      li[k] = s_i[ttv_slot(tid * kTtvIPT + k)];
+      lj[k] = s_j[ttv_slot(tid * kTtvIPT + k)];
+      if (li[k] != qi || lj[k] != qj) headmask |= 1u << k;
+      qi = li[k];
+      qj = lj[k];
+    }
+  }
+  const int cnt = __popc(headmask);
+  int wg_heads;
+  int next_idx = chunk_off[blockIdx.x] + block_inclusive_sum(cnt, &wg_heads) - cnt;
+
+  T acc = 0, lead = 0;
+  int has_head = 0, last_key = -1;
+#pragma unroll
+  for (int k = 0; k < kTtvIPT; ++k) {
+    if (headmask & (1u << k)) {
+      if (!has_head) {
+        lead = acc;
+        has_head = 1;
+      } else {
+        out_v[last_key] = acc;
+      }
+      last_key = next_idx++;
+      out_i[last_key] = li[k];
+      out_j[last_key] = lj[k];
+      acc = 0;
+    }
+    acc += s_val[ttv_slot(tid * kTtvIPT + k)];
+  }
+
+  SegSum<T> in = block_seg_exclusive_scan<T>(SegSum<T>{has_head, acc, last_key}, s_scan);
+  const int carry_idx = chunk_off[blockIdx.x] - 1;  // fiber cut by the chunk start
+  if (has_head) {
+    const T total = in.v + lead;
+    if (in.f) {
+      out_v[in.k] = total;
+    } else {
+      const bool at_start = (tid == 0) && (headmask & 1u);
+      carry_key[blockIdx.x] = at_start ? -1 : carry_idx;
+      carry_val[blockIdx.x] = total;
+    }
+  }
+  if (tid == kBlock - 1) {
+    if (has_head) {
+      out_v[last_key] = acc;
+    } else if (in.f) {
+      out_v[in.k] = in.v + acc;
+    } else {
+      carry_key[blockIdx.x] = carry_idx;
+      carry_val[blockIdx.x] = in.v + acc;
+    }
+  }
+}
+
+static size_t ttv_coo_workspace(int64_t nnz) {
+  const int64_t nch = (nnz + kTtvChunk - 1) / kTtvChunk;
+  return 3 * align_up((size_t)nch * 4, 256) + align_up((size_t)nch * 8, 256) + scan_workspace(nch) +
+         256;
+}
+
+template <typename T>
+static spt_status ttv_coo_typed(const spt_tensor* B, const T* c, int32_t* out_i, int32_t* out_j,
+                                T* out_v, int64_t* out_nnz, void* ws, size_t ws_bytes,
+                                hipStream_t s) {
+  const int64_t nnz64 = B->nvals;
+  if (nnz64 + kTtvChunk >= INT32_MAX) return fail(SPT_ERR_UNSUPPORTED, "ttv: more than 2^31 entries");
+  const int nnz = (int)nnz64;
+  const int nch = (nnz + kTtvChunk - 1) / kTtvChunk;
+  if (nnz == 0) {
+    hipLaunchKernelGGL(ttv_total_kernel, dim3(1), dim3(kWave), 0, s, 0, nullptr, nullptr, out_nnz);
+    SPT_CHECK_LAUNCH("ttv_total");
+    return SPT_OK;
+  }
+  if (!ws || ws_bytes < ttv_coo_workspace(nnz))
+    return fail(SPT_ERR_WORKSPACE, "ttv: workspace of %zu bytes needed, %zu given",
+                ttv_coo_workspace(nnz), ws_bytes);
+  Workspace W(ws, ws_bytes);
+  int32_t* heads = W.take<int32_t>(nch);
+  int32_t* off = W.take<int32_t>(nch);
+  int32_t* ckey = W.take<int32_t>(nch);
+  T* cval = W.take<T>(nch);
+  int32_t* scan_tmp = reinterpret_cast<int32_t*>(W.take<char>(scan_workspace(nch)));
+  const int32_t *ci = B->level[0].crd, *cj = B->level[1].crd, *ck = B->level[2].crd;
+  hipLaunchKernelGGL(ttv_count_kernel, dim3(nch), dim3(kBlock), 0, s, nnz, ci, cj, heads);
+  SPT_CHECK_LAUNCH("ttv_count");
+  spt_status st = device_scan_i32<false>(heads, off, nch, scan_tmp, s);
+  if (st != SPT_OK) return st;
+  hipLaunchKernelGGL(ttv_total_kernel, dim3(1), dim3(kWave), 0, s, nch, heads, off, out_nnz);
+  SPT_CHECK_LAUNCH("ttv_total");
+  hipLaunchKernelGGL(ttv_coo_kernel<T>, dim3(nch), dim3(kBlock), 0, s, nnz, ci, cj, ck,
+                     static_cast<const T*>(B->vals), c, off, out_i, out_j, out_v, ckey, cval);
+  SPT_CHECK_LAUNCH("ttv_coo");
+  hipLaunchKernelGGL(carry_fixup_kernel<T>, dim3((nch + kBlock - 1) / kBlock), dim3(kBlock), 0, s,
+                     nch, ckey, cval, out_v);
+  SPT_CHECK_LAUNCH("ttv carry_fixup");
+  return SPT_OK;
+}
+
+// ================================================================ MTTKRP
+//
+// G lanes (32 or 64) work on one stored entry at a time, lane gl owning output
+// column jt*G + gl; a workgroup has 256/G such groups, each walking kEPG
+// consecutive entries and keeping the running row sum in a register. Entry
+// coordinates are loaded G at a time (coalesced) and broadcast with shuffles;
+// the factor rows C[k,:], D[l,:] are gathered as contiguous G-wide rows.
+// LEVEL2 = the same reduction applied to the (key, vector) carries of level 1.
+// CSF    = i and k come from the upper levels (expanded into LDS per chunk) and
+//          the product with C[k,:] is applied once per fiber piece (factored
+//          form, Section 5.3 / CSF being the more efficient format).
+constexpr int kEPG = 128;
+
+template <typename T, int G>
+struct MttkrpShared {
+  T lead[kBlock / G][G];
+  T tail[kBlock / G][G];
+  int has_head[kBlock / G];
+  int first_close[kBlock / G];
+  int last_key[kBlock / G];
+  int empty[kBlock / G];
+};
+
+enum { MT_COO = 0, MT_LEVEL2 = 1, MT_CSF = 2 };
+
+template <typename T, int G, int MODE>
+__global__ __launch_bounds__(kBlock) void mttkrp_kernel(
+    int n, int J,
+    // COO: ci/ck/cl; CSF: cl only (crd of level 2) plus the upper levels below
+    const int32_t* __restrict__ ci, const int32_t* __restrict__ ck, const int32_t* __restrict__ cl,
+    const T* __restrict__ vals, const T* __restrict__ Cm, const T* __restrict__ Dm,
+    // CSF upper levels
+    const int32_t* __restrict__ crd0, const int32_t* __restrict__ pos1, const int32_t* __restrict__ crd1,
+    const int32_t* __restrict__ pos2, int nslices, int nfibers,
+    // LEVEL2 input
+    const int32_t* __restrict__ in_key, const T* __restrict__ in_vec,
+    T* __restrict__ A, int32_t* __restrict__ carry_key, T* __restrict__ carry_vec) {
+  constexpr int NG = kBlock / G;
+  constexpr int CHUNK = NG * kEPG;
+  __shared__ MttkrpShared<T, G> sh;
+  __shared__ int32_t s_i[MODE == MT_CSF ? CHUNK : 1];
+  __shared__ int32_t s_k[MODE == MT_CSF ? CHUNK : 1];
+  __shared__ int s_bounds[4];
+  __shared__ int s_mark0;
+
+  const int tid = threadIdx.x;
+  const int g = tid / G, gl = tid % G;
+  const int j = blockIdx.y * G + gl;
+  const bool jok = j < J;
+  const int chunk_base = blockIdx.x * CHUNK;
+  const int chunk_end = min(chunk_base + CHUNK, n);
+
+  if (MODE == MT_CSF) {
+    // Expand the coordinates of levels 0 and 1 for the entries of this chunk:
+    // mark the first entry of every fiber / slice that starts inside the chunk,
+    // then let every entry take the last mark at or before it.
+    const bool lastc = chunk_end == n;
+    if (wave_id() == 0) {
+      int f = wave_lower_bound(pos2, nfibers + 1, chunk_base);
+      if (lane_id() == 0) s_bounds[0] = f;
+    } else if (wave_id() == 1) {
+      int f = lastc ? nfibers : wave_lower_bound(pos2, nfibers + 1, chunk_end);
+      if (lane_id() == 0) s_bounds[1] = f;
+    }
+    for (int e = tid; e < CHUNK; e += kBlock) {
+      s_i[e] = -1;
+      s_k[e] = -1;
+    }
+    __syncthreads();
+    const int f_lo = s_bounds[0], f_hi = s_bounds[1];
+    if (wave_id() == 0) {
+      int sl = wave_lower_bound(pos1, nslices + 1, f_lo);
+      if (lane_id() == 0) s_bounds[2] = sl;
+    } else if (wave_id() == 1) {
+      int sl = (f_hi >= nfibers) ? nslices : wave_lower_bound(pos1, nslices + 1, f_hi);
+      if (lane_id() == 0) s_bounds[3] = sl;
+    }
+    for (int f = f_lo + tid; f < f_hi; f += kBlock) {
+      const int a = pos2[f];
+      if (pos2[f + 1] > a) s_k[a - chunk_base] = crd1[f];
+    }
+    __syncthreads();
+    const int s_lo = s_bounds[2], s_hi = s_bounds[3];
+    for (int sl = s_lo + tid; sl < s_hi; sl += kBlock) {
+      const int f0 = pos1[sl];
+      if (pos1[sl + 1] > f0) {
+        const int a = pos2[f0];
+        if (pos2[f0 + 1] > a) s_i[a - chunk_base] = crd0[sl];
+      }
+    }
+    __syncthreads();
+    // propagate marks forward: 256 threads, CHUNK/256 consecutive entries each
+    constexpr int PER = CHUNK / kBlock;
+    int li = -1, lk = -1;
+    if (tid == 0) s_mark0 = s_i[0] >= 0;  // the chunk starts on a slice head
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int e = tid * PER + q;
+      if (s_i[e] >= 0) li = s_i[e];
+      if (s_k[e] >= 0) lk = s_k[e];
+    }
+    // exclusive "last mark" over threads; reuse the segmented scan's key lane
+    __shared__ SegScanStorage<int> s_sc;
+    SegSum<int> a = block_seg_exclusive_scan<int>(SegSum<int>{li >= 0, 0, li}, s_sc);
+    __syncthreads();
+    SegSum<int> b = block_seg_exclusive_scan<int>(SegSum<int>{lk >= 0, 0, lk}, s_sc);
+    // carry-in coordinates of the chunk: the slice / fiber cut by its start
+    int run_i = a.f ? a.k : (s_lo > 0 ? crd0[s_lo - 1] : -1);
+    int run_k = b.f ? b.k : (f_lo > 0 ? crd1[f_lo - 1] : -1);
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int e = tid * PER + q;
+      if (s_i[e] >= 0) run_i = s_i[e];
+      else s_i[e] = run_i;
+      if (s_k[e] >= 0) run_k = s_k[e];
+      else s_k[e] = run_k;
+    }
+    __syncthreads();
+  }
+
+  // ---- group walk
+  const int g0 = chunk_base + g * kEPG;
+  const int g1 = min(g0 + kEPG, chunk_end);
+  T acc = 0, lead = 0, t = 0;
+  int has_head = 0, first_close = -1;
+  int cur = -1, cur_k = -1;
+  // cur = slice coordinate of the entry just before this group's first entry
+  // (-1: there is none; -2: unknown but different, the group starts on a head)
+  if (g0 < g1) {
+    if (MODE == MT_COO) cur = g0 > 0 ? ci[g0 - 1] : -1;
+    if (MODE == MT_LEVEL2) cur = g0 > 0 ? in_key[g0 - 1] : -1;
+    if (MODE == MT_CSF) {
+      if (g0 > chunk_base) cur = s_i[g0 - 1 - chunk_base];
+      else cur = chunk_base == 0 ? -1 : (s_mark0 ? -2 : s_i[0]);
+    }
+  }
+
+  for (int b0 = g0; b0 < g1; b0 += G) {
+    const int p_l = b0 + gl;
+    int32_t ri = 0, rk = 0, rl = 0;
+    T rv = 0;
+    if (p_l < g1) {
+      if (MODE == MT_COO) {
+        ri = ldg_stream(ci + p_l);
+        rk = ldg_stream(ck + p_l);
+        rl = ldg_stream(cl + p_l);
+        rv = ldg_stream(vals + p_l);
+      } else if (MODE == MT_CSF) {
+        ri = s_i[p_l - chunk_base];
+        rk = s_k[p_l - chunk_base];
+        rl = ldg_stream(cl + p_l);
+        rv = ldg_stream(vals + p_l);
+      } else {
+        ri = in_key[p_l];
+      }
+    }
+    const int cntb = min(G, g1 - b0);
+    for (int sidx = 0; sidx < cntb; ++sidx) {
+      const int i = __shfl(ri, sidx, G);
+      T term;
+      if (MODE == MT_LEVEL2) {
+        term = jok ? in_vec[(int64_t)(b0 + sidx) * J + j] : T(0);
+      } else {
+        const int k = __shfl(rk, sidx, G);
+        const int l = __shfl(rl, sidx, G);
+        const T v = __shfl(rv, sidx, G);
+        if (MODE == MT_COO) {
+          term = jok ? v * Cm[(int64_t)k * J + j] * Dm[(int64_t)l * J + j] : T(0);
+        } else {
+          // factored: t accumulates v * D[l,:] inside one (i,k) fiber piece
+          if (i != cur || k != cur_k) {
+            if (cur_k >= 0 && jok) acc += Cm[(int64_t)cur_k * J + j] * t;
+            t = 0;
+            cur_k = k;
+          }
+          term = jok ? v * Dm[(int64_t)l * J + j] : T(0);
+        }
+      }
+      if (i != cur) {
+        if (!has_head) {
+          lead = acc;
+          has_head = 1;
+          first_close = cur;
+        } else if (jok && cur >= 0) {
+          if (MODE == MT_LEVEL2) A[(int64_t)cur * J + j] += acc;
+          else A[(int64_t)cur * J + j] = acc;
+        }
+        acc = 0;
+        cur = i;
+      }
+      if (MODE == MT_CSF) t += term;
+      else acc += term;
+    }
+  }
+  if (MODE == MT_CSF && cur_k >= 0 && jok) acc += Cm[(int64_t)cur_k * J + j] * t;
+
+  sh.lead[g][gl] = lead;
+  sh.tail[g][gl] = acc;
+  if (gl == 0) {
+    sh.has_head[g] = has_head;
+    sh.first_close[g] = first_close;
+    sh.last_key[g] = cur;
+    sh.empty[g] = g0 >= g1;
+  }
+  __syncthreads();
+
+  // ---- resolve the NG group summaries in order (threads of group 0)
+  if (g == 0) {
+    T run = 0;
+    bool seen = false, carried = false;
+    int last = -1;
+    for (int q = 0; q < NG; ++q) {
+      if (sh.empty[q]) continue;
+      if (sh.has_head[q]) {
+        const T total = run + sh.lead[q][gl];
+        const int key = sh.first_close[q];
+        if (seen) {
+          if (jok && key >= 0) {
+            if (MODE == MT_LEVEL2) A[(int64_t)key * J + j] += total;
+            else A[(int64_t)key * J + j] = total;
+          }
+        } else {  // precedes the first head of the chunk: carry (key < 0: nothing precedes)
+          if (jok) carry_vec[(int64_t)blockIdx.x * J + j] = total;
+          if (gl == 0 && blockIdx.y == 0) carry_key[blockIdx.x] = key < 0 ? -1 : key;
+          carried = true;
+        }
+        run = sh.tail[q][gl];
+        seen = true;
+      } else {
+        run += sh.tail[q][gl];
+      }
+      last = sh.last_key[q];
+    }
+    if (seen) {
+      if (jok && last >= 0) {
+        if (MODE == MT_LEVEL2) A[(int64_t)last * J + j] += run;
+        else A[(int64_t)last * J + j] = run;
+      }
+    } else if (!carried) {
+      if (jok) carry_vec[(int64_t)blockIdx.x * J + j] = run;
+      if (gl == 0 && blockIdx.y == 0) carry_key[blockIdx.x] = last;
+    }
+  }
+}
+
+// Adds the remaining (key, vector) carries into A, one thread per (carry, j);
+// the thread at the start of a run of equal keys adds the whole run in order.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void vec_carry_fixup_kernel(int n, int J,
+                                                                 const int32_t* __restrict__ key,
+                                                                 const T* __restrict__ vec,
+                                                                 T* __restrict__ A) {
+  const int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (idx >= (int64_t)n * J) return;
+  const int w = (int)(idx / J), j = (int)(idx % J);
+  const int32_t kk = key[w];
+  if (kk < 0) return;
+  if (w > 0 && key[w - 1] == kk) return;
+  double s = 0;
+  for (int u = w; u < n && key[u] == kk; ++u) s += (double)vec[(int64_t)u * J + j];
+  A[(int64_t)kk * J + j] = (T)((double)A[(int64_t)kk * J + j] + s);
+}
+
+static int mttkrp_group(int J) { return J <= 32 ? 32 : 64; }
+static int mttkrp_chunk(int J) { return (kBlock / mttkrp_group(J)) * kEPG; }
+
+size_t mttkrp_workspace(Format, const spt_tensor* B, int32_t J) {
+  if (J < 1) J = 1;
+  const int64_t chunk = mttkrp_chunk(J);
+  const int64_t n1 = (B->nvals + chunk - 1) / chunk;
+  const int64_t n2 = (n1 + chunk - 1) / chunk;
+  return align_up((size_t)n1 * 4, 256) + align_up((size_t)n1 * J * 8, 256) +
+         align_up((size_t)n2 * 4, 256) + align_up((size_t)n2 * J * 8, 256) + 256;
+}
+
+template <typename T, int G>
+static spt_status mttkrp_launch(Format f, const spt_tensor* B, const T* Cm, const T* Dm, int J,
+                                T* A, void* ws, size_t ws_bytes, hipStream_t s) {
+  constexpr int CHUNK = (kBlock / G) * kEPG;
+  const int64_t I = B->level[0].N;
+  const int64_t nnz64 = B->nvals;
+  if (nnz64 + CHUNK >= INT32_MAX || I * J >= ((int64_t)1 << 40))
+    return fail(SPT_ERR_UNSUPPORTED, "mttkrp: tensor too large");
+  if (I * J > 0) {
+    hipLaunchKernelGGL(fill_t_kernel<T>, dim3((unsigned)((I * J + kBlock - 1) / kBlock)),
+                       dim3(kBlock), 0, s, A, I * J, T(0));
+    SPT_CHECK_LAUNCH("mttkrp fill");
+  }
+  const int nnz = (int)nnz64;
+  if (nnz == 0) return SPT_OK;
+  if (!ws || ws_bytes < mttkrp_workspace(f, B, J))
+    return fail(SPT_ERR_WORKSPACE, "mttkrp: workspace of %zu bytes needed, %zu given",
+                mttkrp_workspace(f, B, J), ws_bytes);
+  const int n1 = (nnz + CHUNK - 1) / CHUNK;
+  const int n2 = (n1 + CHUNK - 1) / CHUNK;
+  Workspace W(ws, ws_bytes);
+  int32_t* key1 = W.take<int32_t>(n1);
+  T* vec1 = W.take<T>((size_t)n1 * J);
+  int32_t* key2 = W.take<int32_t>(n2);
+  T* vec2 = W.take<T>((size_t)n2 * J);
+  const unsigned jt = (unsigned)((J + G - 1) / G);
+  const spt_level* L = B->level;
+  if (f == Format::COO3) {
+    hipLaunchKernelGGL((mttkrp_kernel<T, G, MT_COO>), dim3(n1, jt), dim3(kBlock), 0, s, nnz, J,
+                       L[0].crd, L[1].crd, L[2].crd, static_cast<const T*>(B->vals), Cm, Dm, nullptr,
+                       nullptr, nullptr, nullptr, 0, 0, nullptr, nullptr, A, key1, vec1);
+  } else {
+    const int64_t nsl = L[1].M, nfib = L[2].M;
+    if (nsl + 1 >= INT32_MAX || nfib + 1 >= INT32_MAX)
+      return fail(SPT_ERR_UNSUPPORTED, "mttkrp: tensor too large");
+    hipLaunchKernelGGL((mttkrp_kernel<T, G, MT_CSF>), dim3(n1, jt), dim3(kBlock), 0, s, nnz, J,
+                       nullptr, nullptr, L[2].crd, static_cast<const T*>(B->vals), Cm, Dm, L[0].crd,
+                       L[1].pos, L[1].crd, L[2].pos, (int)nsl, (int)nfib, nullptr, nullptr, A, key1,
+                       vec1);
+  }
+  SPT_CHECK_LAUNCH("mttkrp");
+  hipLaunchKernelGGL((mttkrp_kernel<T, G, MT_LEVEL2>), dim3(n2, jt), dim3(kBlock), 0, s, n1, J,
+                     nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                     nullptr, 0, 0, key1, vec1, A, key2, vec2);
+  SPT_CHECK_LAUNCH("mttkrp level 2");
+  const int64_t tot = (int64_t)n2 * J;
+  hipLaunchKernelGGL(vec_carry_fixup_kernel<T>, dim3((unsigned)((tot + kBlock - 1) / kBlock)),
+                     dim3(kBlock), 0, s, n2, J, key2, vec2, A);
+  SPT_CHECK_LAUNCH("mttkrp fixup");
+  return SPT_OK;
+}
+
+template <typename T>
+static spt_status mttkrp_typed(Format f, const spt_tensor* B, const void* C, const void* D, int J,
+                               void* A, void* ws, size_t ws_bytes, hipStream_t s) {
+  const T* Cm = static_cast<const T*>(C);
+  const T* Dm = static_cast<const T*>(D);
+  if (mttkrp_group(J) == 32)
+    return mttkrp_launch<T, 32>(f, B, Cm, Dm, J, static_cast<T*>(A), ws, ws_bytes, s);
+  return mttkrp_launch<T, 64>(f, B, Cm, Dm, J, static_cast<T*>(A), ws, ws_bytes, s);
+}
+
+spt_status mttkrp_dispatch(Format f, const spt_tensor* B, const void* C, const void* D, int32_t J,
+                           void* A_out, void* ws, size_t ws_bytes, hipStream_t s) {
+  for (int k = 0; k < 3; ++k)
+    if (!(B->level[k].flags & SPT_ORDERED))
+      return fail(SPT_ERR_UNSUPPORTED, "mttkrp: every level of B must be ordered");
+  if (B->dtype == SPT_F64) return mttkrp_typed<double>(f, B, C, D, J, A_out, ws, ws_bytes, s);
+  return mttkrp_typed<float>(f, B, C, D, J, A_out, ws, ws_bytes, s);
+}
+
+// ================================================================ TTV dispatch
+
+size_t ttv_workspace(Format f, const spt_tensor* B) {
+  return f == Format::COO3 ? ttv_coo_workspace(B->nvals) : seg_spmv_workspace(B->nvals);
+}
+
+__global__ void set_i64_kernel(int64_t* out, int64_t v) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *out = v;
+}
+
+spt_status ttv_dispatch(Format f, const spt_tensor* B, const void* c, int32_t* out_crd0,
+                        int32_t* out_crd1, void* out_vals, int64_t* out_nnz_dev, void* ws,
+                        size_t ws_bytes, hipStream_t s) {
+  for (int k = 0; k < 3; ++k)
+    if (!(B->level[k].flags & SPT_ORDERED))
+      return fail(SPT_ERR_UNSUPPORTED, "ttv: every level of B must be ordered");
+  if (f == Format::CSF3) {
+    // The bottom level is a compressed level over the fibers: the same row
+    // reduction as CSR SpMV with rows = fibers and x = c.
+    const int64_t nfib = B->level[2].M;
+    if (out_nnz_dev) {
+      hipLaunchKernelGGL(set_i64_kernel, dim3(1), dim3(kWave), 0, s, out_nnz_dev, nfib);
+      SPT_CHECK_LAUNCH("ttv set count");
+    }
+    return csr_rows_reduce(B->dtype, B->nvals, nfib, B->level[2].pos, B->level[2].crd, B->vals, c,
+                           out_vals, ws, ws_bytes, s);
+  }
+  if (B->dtype == SPT_F64)
+    return ttv_coo_typed<double>(B, static_cast<const double*>(c), out_crd0, out_crd1,
+                                 static_cast<double*>(out_vals), out_nnz_dev, ws, ws_bytes, s);
+  return ttv_coo_typed<float>(B, static_cast<const float*>(c), out_crd0, out_crd1,
+                              static_cast<float*>(out_vals), out_nnz_dev, ws, ws_bytes, s);
+}
+
 }  // namespace spt

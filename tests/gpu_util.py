@@ -45,3 +45,39 @@ def gpu_coo_to_csr(spec, order):
     spt.spt_coo_to_csr(A, order, pos, crd, vals, ws)
     torch.cuda.synchronize()
     return pos.cpu().numpy(), crd.cpu().numpy()[:nnz], vals.cpu().numpy()[:nnz]
+
+
+def gpu_ttv(spec, c):
+    """Returns (out_i, out_j, out_vals, count) for COO input, (None, None, out_vals, count) for CSF."""
+    import torch
+    import paper_1804_10112_amd as spt
+    B = spt.DeviceTensor(spec)
+    cd = torch.from_numpy(np.ascontiguousarray(c)).cuda()
+    nnz = len(spec.vals)
+    is_csf = spec.levels[1].kind == 1
+    cap = max(len(spec.levels[1].crd) if is_csf else nnz, 1)
+    oi = torch.full((cap,), -7, dtype=torch.int32, device="cuda")
+    oj = torch.full((cap,), -7, dtype=torch.int32, device="cuda")
+    ov = torch.full((cap,), float("nan"), dtype=B.torch_dtype, device="cuda")
+    cnt = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    ws = B.workspace(spt.SPT_OP_TTV)
+    spt.spt_ttv(B, cd, None if is_csf else oi, None if is_csf else oj, ov, cnt, ws)
+    torch.cuda.synchronize()
+    n = int(cnt.item())
+    if is_csf:
+        return None, None, ov.cpu().numpy()[:n], n
+    return oi.cpu().numpy()[:n], oj.cpu().numpy()[:n], ov.cpu().numpy()[:n], n
+
+
+def gpu_mttkrp(spec, Cm, Dm):
+    import torch
+    import paper_1804_10112_amd as spt
+    B = spt.DeviceTensor(spec)
+    Cd = torch.from_numpy(np.ascontiguousarray(Cm)).cuda()
+    Dd = torch.from_numpy(np.ascontiguousarray(Dm)).cuda()
+    J = Cm.shape[1]
+    A = torch.full((spec.dims[0], J), float("nan"), dtype=B.torch_dtype, device="cuda")
+    ws = B.workspace(spt.SPT_OP_MTTKRP, J)
+    spt.spt_mttkrp(B, Cd, Dd, J, A, ws)
+    torch.cuda.synchronize()
+    return A.cpu().numpy()

@@ -1,0 +1,121 @@
+"""GPU parity: spt_ttv and spt_mttkrp (COO and CSF) vs the oracle."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from gpu_util import assert_close, gpu_mttkrp, gpu_ttv
+
+pytestmark = pytest.mark.gpu
+
+
+def _tensor(dims, nnz, seed, dtype, skew=1.5, dist="u01"):
+    ci, cj, ck, v = wl.random_coo3_entries(dims, nnz, seed, dtype, dist, skew=skew)
+    return (wl.coo3_spec(dims, ci, cj, ck, v), wl.csf3_from_sorted_coo(dims, ci, cj, ck, v))
+
+
+def _check_ttv(coo, csf, c, what):
+    ri, rj, rv, rm = oracle.ttv(coo, c)
+    oi, oj, ov, n = gpu_ttv(coo, c)
+    assert n == len(ri), f"{what}: fiber count {n} != {len(ri)}"
+    assert np.array_equal(oi, ri) and np.array_equal(oj, rj), f"{what}: output coordinates differ"
+    assert_close(ov, rv, rm, coo.vals.dtype, what + " coo")
+    _, _, cv, n2 = gpu_ttv(csf, c)
+    assert n2 == len(ri)
+    assert_close(cv, rv, rm, coo.vals.dtype, what + " csf")
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("nnz", [1, 200, 2047, 2048, 2049, 6000, 150_000])
+def test_ttv_random(dtype, nnz):
+    dims = (300, 41, 57)
+    coo, csf = _tensor(dims, nnz, 300 + nnz, dtype)
+    c = wl.dense_vector(dims[2], 1, dtype, "u01")
+    _check_ttv(coo, csf, c, f"ttv nnz={nnz}")
+
+
+def test_ttv_degenerate():
+    # one fiber holds everything (spans chunks); single-entry fibers; empty tensor
+    n = 5000
+    k = np.arange(n)
+    v = np.random.default_rng(0).uniform(0, 1, n).astype(np.float32)
+    c = wl.dense_vector(n, 2, np.float32, "u01")
+    z = np.zeros(n, int)
+    _check_ttv(wl.coo3_spec((3, 3, n), z + 2, z + 1, k, v), wl.csf3_from_sorted_coo((3, 3, n), z + 2, z + 1, k, v),
+               c, "one fiber")
+    _check_ttv(wl.coo3_spec((n, 2, n), k, z, k, v), wl.csf3_from_sorted_coo((n, 2, n), k, z, k, v),
+               c, "singleton fibers")
+    e = np.zeros(0, int)
+    oi, oj, ov, cnt = gpu_ttv(wl.coo3_spec((3, 3, 3), e, e, e, np.zeros(0, np.float32)), c[:3])
+    assert cnt == 0
+    # a fiber whose sum cancels is still emitted
+    coo = wl.coo3_spec((2, 2, 2), [0, 0], [1, 1], [0, 1], np.array([1.0, -1.0]))
+    oi, oj, ov, cnt = gpu_ttv(coo, np.ones(2))
+    assert cnt == 1 and oi[0] == 0 and oj[0] == 1 and ov[0] == 0.0
+
+
+def test_ttv_exact_integer_is_bit_exact():
+    dims = (50, 60, 70)
+    coo, csf = _tensor(dims, 40_000, 7, np.float32, dist="int")
+    c = wl.dense_vector(70, 3, np.float32, "int")
+    ri, rj, rv, _ = oracle.ttv(coo, c)
+    oi, oj, ov, n = gpu_ttv(coo, c)
+    assert np.array_equal(ov.astype(np.float64), rv)
+    assert np.array_equal(gpu_ttv(csf, c)[2].astype(np.float64), rv)
+
+
+def _check_mttkrp(coo, csf, Cm, Dm, what):
+    ref, mag = oracle.mttkrp(coo, Cm, Dm)
+    assert_close(gpu_mttkrp(coo, Cm, Dm), ref, mag, coo.vals.dtype, what + " coo")
+    assert_close(gpu_mttkrp(csf, Cm, Dm), ref, mag, coo.vals.dtype, what + " csf")
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("J", [1, 8, 16, 32, 33, 64, 100])
+def test_mttkrp_ranks(dtype, J):
+    dims = (200, 37, 53)
+    coo, csf = _tensor(dims, 20_000, 400 + J, dtype)
+    rng = np.random.default_rng(J)
+    Cm = rng.uniform(0, 1, (dims[1], J)).astype(dtype)
+    Dm = rng.uniform(0, 1, (dims[2], J)).astype(dtype)
+    _check_mttkrp(coo, csf, Cm, Dm, f"mttkrp J={J}")
+
+
+@pytest.mark.parametrize("nnz", [1, 127, 128, 129, 1023, 1024, 1025, 5000, 300_000])
+def test_mttkrp_sizes(nnz):
+    dims = (500, 64, 81)
+    coo, csf = _tensor(dims, nnz, 500 + nnz, np.float32)
+    rng = np.random.default_rng(nnz)
+    Cm = rng.uniform(0, 1, (dims[1], 32)).astype(np.float32)
+    Dm = rng.uniform(0, 1, (dims[2], 32)).astype(np.float32)
+    _check_mttkrp(coo, csf, Cm, Dm, f"mttkrp nnz={nnz}")
+
+
+def test_mttkrp_degenerate_and_exact():
+    rng = np.random.default_rng(1)
+    # one slice holds everything (crosses many chunks and both carry levels)
+    n = 200_000
+    k = rng.integers(0, 300, n)
+    l = rng.integers(0, 400, n)
+    key = np.unique(k * 400 + l)
+    k, l = key // 400, key % 400
+    v = rng.integers(-3, 4, len(key)).astype(np.float32)
+    Cm = rng.integers(-3, 4, (300, 32)).astype(np.float32)
+    Dm = rng.integers(-3, 4, (400, 32)).astype(np.float32)
+    for row in (0, 4):
+        i = np.full(len(key), row)
+        coo = wl.coo3_spec((5, 300, 400), i, k, l, v)
+        csf = wl.csf3_from_sorted_coo((5, 300, 400), i, k, l, v)
+        ref, _ = oracle.mttkrp(coo, Cm, Dm)
+        assert np.array_equal(gpu_mttkrp(coo, Cm, Dm).astype(np.float64), ref), "coo one slice"
+        assert np.array_equal(gpu_mttkrp(csf, Cm, Dm).astype(np.float64), ref), "csf one slice"
+    # empty tensor: A is all zeros
+    e = np.zeros(0, int)
+    A = gpu_mttkrp(wl.coo3_spec((5, 300, 400), e, e, e, np.zeros(0, np.float32)), Cm, Dm)
+    assert np.array_equal(A, np.zeros((5, 32), np.float32))
+
+
+def test_scaled_config5():
+    c5 = wl.config5(dims=(2000, 1600, 1000), nnz=400_000)
+    _check_ttv(c5["coo"], c5["csf"], c5["c"], "c5 ttv")
+    _check_mttkrp(c5["coo"], c5["csf"], c5["C"], c5["D"], "c5 mttkrp")
