@@ -59,7 +59,7 @@ def build_items(args):
         ws = A.workspace(spt.SPT_OP_SPMV)
         keep.extend([A, y, ws])
         items.append(Item(name, lambda: spt.spt_spmv(A, x, y, ws), flops, bytes_))
-        cpu_jobs.append((name, spec, x_np, fmt, flops))
+        cpu_jobs.append((name, lambda o, t=spec, v=x_np, f=fmt: o.plain_spmv(t, v, f), flops))
         return A, x, y
 
     want = set(args.only.split(",")) if args.only else None
@@ -86,15 +86,80 @@ def build_items(args):
         spmv_item("c3_ell_spmv", c3["ell"], c3["x"], 8 * W * N + 8 * N, 2 * nnz, "ell")
         spmv_item("c3_csr_spmv", c3["csr"], c3["x"], 8 * nnz + 4 * (N + 1) + 8 * N, 2 * nnz, "csr")
         del c3
-    # ---- config 4: power-law rows, fp64, unsorted COO
+    # ---- config 4: power-law rows, fp64, unsorted COO: the three pipelines of Section 5.4
     if on("c4"):
         t0 = time.time()
         n4 = max(1024, int(4_000_000 * s))
         c4 = wl.config4(N=n4, nnz_target=int(60_000_000 * s), max_row=max(8, int(200_000 * s)))
         N, nnz = n4, c4["nnz"]
         log(f"c4 generated in {time.time()-t0:.1f}s: N={N} nnz={nnz}")
-        spmv_item("c4_coo_unsorted_spmv", c4["coo"], c4["x"], 16 * nnz + 24 * N, 2 * nnz, "coo")
+        A, x, _ = spmv_item("c4_coo_unsorted_spmv", c4["coo"], c4["x"], 16 * nnz + 24 * N, 2 * nnz, "coo")
+        # COO -> CSR (sort by (row,col) + pos assembly); its outputs feed the next two items
+        pos = torch.empty(N + 1, dtype=torch.int32, device=dev)
+        crd = torch.empty(nnz, dtype=torch.int32, device=dev)
+        vout = torch.empty(nnz, dtype=A.torch_dtype, device=dev)
+        wsc = A.workspace(spt.SPT_OP_COO_TO_CSR)
+        keep.extend([pos, crd, vout, wsc])
+        bits = lambda d: max(1, int(np.ceil(np.log2(max(d, 2)))))
+        passes = 2 * ((bits(N) + 7) // 8)
+        conv_bytes = passes * (4 + 32) * nnz + 4 * nnz + 12 * (N + 1)
+        items.append(Item("c4_coo_to_csr", lambda: spt.spt_coo_to_csr(A, spt.SPT_ORDER_ROW_COL, pos, crd, vout, wsc),
+                          0, conv_bytes, f"{passes} radix passes"))
+        items[-1].run()
+        torch.cuda.synchronize()
+        rows_sorted = torch.repeat_interleave(torch.arange(N, dtype=torch.int32, device=dev),
+                                              (pos[1:] - pos[:-1]).long())
+        sorted_coo = wl.coo_spec(N, N, np.zeros(0, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float64))
+        As = spt.DeviceTensor(sorted_coo)      # descriptor shell; point it at the device arrays
+        As.c.level[0].crd = rows_sorted.data_ptr()
+        As.c.level[1].crd = crd.data_ptr()
+        As.c.vals = vout.data_ptr()
+        As.c.nvals = nnz
+        csr_shell = wl.csr_spec(N, N, np.zeros(N + 1, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float64))
+        Ac = spt.DeviceTensor(csr_shell)
+        Ac.c.level[1].pos = pos.data_ptr()
+        Ac.c.level[1].crd = crd.data_ptr()
+        Ac.c.vals = vout.data_ptr()
+        Ac.c.nvals = nnz
+        y2 = torch.empty(N, dtype=A.torch_dtype, device=dev)
+        ws2 = torch.empty(spt.spt_workspace_bytes(spt.SPT_OP_SPMV, As), dtype=torch.uint8, device=dev)
+        keep.extend([rows_sorted, As, Ac, y2, ws2])
+        items.append(Item("c4_coo_sorted_spmv", lambda: spt.spt_spmv(As, x, y2, ws2), 2 * nnz, 16 * nnz + 16 * N))
+        items.append(Item("c4_csr_spmv", lambda: spt.spt_spmv(Ac, x, y2, ws2), 2 * nnz,
+                          12 * nnz + 4 * (N + 1) + 16 * N))
         del c4
+    # ---- config 5: skewed 3rd-order tensor, fp32: TTV and MTTKRP on COO and CSF
+    if on("c5"):
+        t0 = time.time()
+        dims = tuple(max(16, int(d * s)) for d in (100_000, 80_000, 50_000))
+        c5 = wl.config5(dims=dims, nnz=max(1000, int(50_000_000 * s)))
+        nnz, J = c5["nnz"], c5["C"].shape[1]
+        nfib = len(c5["csf"].levels[1].crd)
+        log(f"c5 generated in {time.time()-t0:.1f}s: nnz={nnz} fibers={nfib}")
+        Bc, Bf = spt.DeviceTensor(c5["coo"]), spt.DeviceTensor(c5["csf"])
+        cv, Cm, Dm = up(c5["c"]), up(c5["C"]), up(c5["D"])
+        oi = torch.empty(nnz, dtype=torch.int32, device=dev)
+        oj = torch.empty(nnz, dtype=torch.int32, device=dev)
+        ov = torch.empty(nnz, dtype=torch.float32, device=dev)
+        cnt = torch.zeros(1, dtype=torch.int64, device=dev)
+        Aout = torch.empty(dims[0], J, dtype=torch.float32, device=dev)
+        w_tc, w_tf = Bc.workspace(spt.SPT_OP_TTV), Bf.workspace(spt.SPT_OP_TTV)
+        w_mc, w_mf = Bc.workspace(spt.SPT_OP_MTTKRP, J), Bf.workspace(spt.SPT_OP_MTTKRP, J)
+        keep.extend([Bc, Bf, oi, oj, ov, cnt, Aout, w_tc, w_tf, w_mc, w_mf])
+        dense = 4 * (dims[1] + dims[2] + dims[0]) * J
+        items.append(Item("c5_ttv_coo", lambda: spt.spt_ttv(Bc, cv, oi, oj, ov, cnt, w_tc), 2 * nnz,
+                          16 * nnz + 12 * nfib + 4 * dims[2]))
+        items.append(Item("c5_ttv_csf", lambda: spt.spt_ttv(Bf, cv, None, None, ov, cnt, w_tf), 2 * nnz,
+                          8 * nnz + 4 * (nfib + 1) + 4 * nfib + 4 * dims[2]))
+        items.append(Item("c5_mttkrp_coo", lambda: spt.spt_mttkrp(Bc, Cm, Dm, J, Aout, w_mc), 3 * J * nnz,
+                          16 * nnz + dense, "compulsory HBM bytes; factor rows are gathered from cache"))
+        items.append(Item("c5_mttkrp_csf", lambda: spt.spt_mttkrp(Bf, Cm, Dm, J, Aout, w_mf),
+                          2 * J * nnz + 2 * J * nfib, 8 * nnz + 8 * nfib + dense,
+                          "compulsory HBM bytes; factor rows are gathered from cache"))
+        cpu_jobs.append(("c5_ttv_coo", lambda o, t=c5["coo"], c=c5["c"]: o.plain_ttv(t, c, "coo"), 2 * nnz))
+        cpu_jobs.append(("c5_mttkrp_coo", lambda o, t=c5["coo"], C=c5["C"], D=c5["D"]: o.plain_mttkrp(t, C, D, "coo"),
+                         3 * J * nnz))
+        del c5
     return items, cpu_jobs, keep
 
 
@@ -103,11 +168,11 @@ def cpu_baseline(cpu_jobs, budget_s=20.0):
     on the same inputs, one call each, stopping once the time budget is spent."""
     import oracle
     total_flops, total_t, done = 0.0, 0.0, []
-    for name, spec, x, fmt, flops in cpu_jobs:
+    for name, job, flops in cpu_jobs:
         if total_t > budget_s:
             break
         t0 = time.perf_counter()
-        oracle.plain_spmv(spec, x, fmt)
+        job(oracle)
         dt = time.perf_counter() - t0
         total_flops += flops
         total_t += dt
