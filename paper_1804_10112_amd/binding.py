@@ -102,14 +102,17 @@ def _desc(T):
 
 
 def _stream(stream):
+    """hipStream_t as an integer; None = torch's current stream (null stream without a GPU)."""
     if stream is None:
         import torch
+        if not torch.cuda.is_available():
+            return None
         return torch.cuda.current_stream().cuda_stream
     return stream if isinstance(stream, int) else stream.cuda_stream
 
 
 def _ws(ws):
-    if ws is None:
+    if ws is None or isinstance(ws, int):
         return None, 0
     return ws.data_ptr(), ws.numel() * ws.element_size()
 

@@ -1,0 +1,109 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol that
+include/spt.h declares, and the host-side validation / recognition logic
+returns the documented statuses without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1804_10112_amd as spt
+from paper_1804_10112_amd import binding as B
+import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _host_desc(spec):
+    """An spt_tensor whose pointers are fake but non-null: host validation only."""
+    t = B.SptTensor()
+    t.order, t.nlevels = len(spec.dims), len(spec.levels)
+    t.dtype = B.SPT_F64 if spec.vals.dtype == np.float64 else B.SPT_F32
+    for k, lv in enumerate(spec.levels):
+        o = t.level[k]
+        o.kind, o.mode, o.N, o.M = lv.kind, lv.mode, lv.N, lv.M
+        o.flags = (B.SPT_ORDERED if lv.ordered else 0) | (B.SPT_UNIQUE if lv.unique else 0)
+        for name in ("pos", "crd", "offset"):
+            if getattr(lv, name) is not None:
+                setattr(o, name, 0x1000)
+    t.vals = 0x1000
+    t.nvals = spec.vals.size
+    return t
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "spt.h")).read()
+    declared = set(re.findall(r"\b(spt_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(B.SYMBOLS), declared ^ set(B.SYMBOLS)
+    lib = spt.lib()
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert "gfx950" in spt.spt_version()
+
+
+def test_struct_layout_matches_header():
+    assert C.sizeof(B.SptLevel) == 4 * 4 + 2 * 8 + 3 * 8
+    assert C.sizeof(B.SptTensor) == 16 + 4 * C.sizeof(B.SptLevel) + 16
+
+
+def test_recognised_compositions_have_workspace_sizes():
+    c1 = wl.config1(N=64, nnz=200)
+    c2 = wl.config2(N=64)
+    c3 = wl.config3(N=64)
+    c5 = wl.config5(dims=(20, 16, 12), nnz=300, rank=4)
+    for spec, op in ((c1["csr"], B.SPT_OP_SPMV), (c1["coo"], B.SPT_OP_SPMV), (c2["dia"], B.SPT_OP_SPMV),
+                     (c3["ell"], B.SPT_OP_SPMV), (c1["coo"], B.SPT_OP_COO_TO_CSR),
+                     (c5["coo"], B.SPT_OP_TTV), (c5["csf"], B.SPT_OP_TTV),
+                     (c5["coo"], B.SPT_OP_MTTKRP), (c5["csf"], B.SPT_OP_MTTKRP)):
+        assert spt.spt_workspace_bytes(op, _host_desc(spec), 4) >= 256, spec.name
+
+
+def _status(fn, *args):
+    try:
+        fn(*args)
+    except spt.SptError as e:
+        return e.status, str(e)
+    return 0, ""
+
+
+def test_invalid_and_unsupported_descriptors():
+    c1 = wl.config1(N=64, nnz=200)
+    # unknown level kind
+    t = _host_desc(c1["csr"])
+    t.level[1].kind = 9
+    assert _status(spt.spt_workspace_bytes, B.SPT_OP_SPMV, t)[0] == B.SPT_ERR_INVALID_ARG
+    # Table 1: a hashed level cannot be ordered
+    t = _host_desc(c1["csr"])
+    t.level[1].kind = wl.HASHED
+    st, msg = _status(spt.spt_workspace_bytes, B.SPT_OP_SPMV, t)
+    assert st == B.SPT_ERR_INVALID_ARG and "hashed" in msg
+    # hashed, legally flagged: a valid level but no kernel for the composition
+    t.level[1].flags = B.SPT_UNIQUE
+    st, msg = _status(spt.spt_spmv, t, 0x1000, 0x1000, None, 0)
+    assert st == B.SPT_ERR_UNSUPPORTED
+    # compressed level without pos; CSR whose column level has the wrong parent count
+    t = _host_desc(c1["csr"])
+    t.level[1].pos = None
+    assert _status(spt.spt_spmv, t, 0x1000, 0x1000, None, 0)[0] == B.SPT_ERR_INVALID_ARG
+    t = _host_desc(c1["csr"])
+    t.level[1].M = 7
+    assert _status(spt.spt_spmv, t, 0x1000, 0x1000, None, 0)[0] == B.SPT_ERR_INVALID_ARG
+    # (compressed, compressed) = DCSR: valid levels, unsupported composition
+    t = _host_desc(c1["coo"])
+    t.level[1].kind = wl.COMPRESSED
+    t.level[1].pos = 0x1000
+    assert _status(spt.spt_spmv, t, 0x1000, 0x1000, None, 0)[0] == B.SPT_ERR_UNSUPPORTED
+    # null operands, bad order, bad rank, wrong operation for the format
+    t = _host_desc(c1["coo"])
+    assert _status(spt.spt_spmv, t, None, 0x1000, None, 0)[0] == B.SPT_ERR_INVALID_ARG
+    assert _status(spt.spt_coo_to_csr, t, 5, 0x1000, 0x1000, 0x1000, None, 0)[0] == B.SPT_ERR_INVALID_ARG
+    assert _status(spt.spt_coo_to_csr, _host_desc(c1["csr"]), 0, 0x1000, 0x1000, 0x1000, None, 0)[0] == B.SPT_ERR_UNSUPPORTED
+    c5 = wl.config5(dims=(20, 16, 12), nnz=300, rank=4)
+    t5 = _host_desc(c5["coo"])
+    assert _status(spt.spt_mttkrp, t5, 0x1000, 0x1000, 0, 0x1000, None, 0)[0] == B.SPT_ERR_INVALID_ARG
+    assert _status(spt.spt_mttkrp, _host_desc(c1["coo"]), 0x1000, 0x1000, 4, 0x1000, None, 0)[0] == B.SPT_ERR_UNSUPPORTED
+    assert _status(spt.spt_ttv, t5, 0x1000, None, None, 0x1000, None, None, 0)[0] == B.SPT_ERR_INVALID_ARG
+    # workspace too small is diagnosed before anything is launched
+    st, msg = _status(spt.spt_spmv, _host_desc(c1["csr"]), 0x1000, 0x1000, None, 0)
+    assert st == B.SPT_ERR_WORKSPACE and "workspace" in msg

@@ -306,7 +306,7 @@ def config3(N=1_000_000, lo=8, hi=32, seed=SEED_BASE + 3, dtype=np.float32):
 
 
 def config4(N=4_000_000, nnz_target=60_000_000, max_row=200_000, zipf=1.8,
-            seed=SEED_BASE + 4, dtype=np.float64):
+            seed=SEED_BASE + 4, dtype=np.float64, with_sorted=False):
     """Power-law row lengths (truncated Zipf, thinned to ~nnz_target entries),
     uniform distinct columns, entries shuffled: unsorted COO."""
     rng = np.random.default_rng(seed)
@@ -320,15 +320,19 @@ def config4(N=4_000_000, nnz_target=60_000_000, max_row=200_000, zipf=1.8,
     L = rng.binomial(L, keep)
     row = np.repeat(np.arange(N, dtype=np.int64), L)
     col = rng.integers(0, M, len(row))
-    key = np.unique(row * M + col)        # distinct columns inside every row
+    key = np.unique(row * M + col)        # distinct columns inside every row (sorted)
     del row, col
-    key = rng.permutation(key)            # unsorted COO
-    row, col = _i32(key // M), _i32(key % M)
-    del key
+    perm = rng.permutation(len(key))      # unsorted COO: entry p is sorted entry perm[p]
+    row, col = _i32(key[perm] // M), _i32(key[perm] % M)
     vals = _values(rng, len(row), dtype, "u11")
     x = dense_vector(M, seed + 1000, dtype, "u11")
-    return {"coo": coo_spec(N, M, row, col, vals, ordered=False, name="c4-coo"),
-            "x": x, "nnz": len(row)}
+    out = {"coo": coo_spec(N, M, row, col, vals, ordered=False, name="c4-coo"),
+           "x": x, "nnz": len(row)}
+    if with_sorted:                       # the same entries in (row, col) order
+        vs = np.empty_like(vals)
+        vs[perm] = vals
+        out["sorted"] = (_i32(key // M), _i32(key % M), vs)
+    return out
 
 
 def config5(dims=(100_000, 80_000, 50_000), nnz=50_000_000, zipf=1.5, rank=32,
