@@ -51,7 +51,11 @@ __global__ __launch_bounds__(kBlock) void radix_hist_kernel(const int32_t* __res
 // Stable scatter of one pass. Element order inside a tile is (wave, item, lane);
 // a lane's rank among equal digits comes from a ballot-based match inside the
 // wave plus per-wave running digit counters in LDS, so equal keys keep their
-// input order. off[d * ntiles + tile] is the exclusive scan of hist.
+// input order. The tile is then sorted by digit inside LDS (one array at a time
+// through the same buffer) so that consecutive lanes store to consecutive
+// addresses of each digit's run: scattered single-lane stores cost one memory
+// transaction each, exactly like random gathers. off[d * ntiles + tile] is the
+// exclusive scan of hist.
 template <typename VT>
 __global__ __launch_bounds__(kBlock) void radix_scatter_kernel(
     int n, int shift, int key_is_row, int ntiles, const int32_t* __restrict__ off,
@@ -59,22 +63,37 @@ __global__ __launch_bounds__(kBlock) void radix_scatter_kernel(
     const VT* __restrict__ val_in, int32_t* __restrict__ row_out, int32_t* __restrict__ col_out,
     VT* __restrict__ val_out) {
   __shared__ int s_cnt[kWaves][kRadix];
+  __shared__ int s_gdelta[kRadix];
+  __shared__ VT s_buf[kSortTile];
+  int32_t* s_buf32 = reinterpret_cast<int32_t*>(s_buf);
   const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
   for (int q = tid; q < kWaves * kRadix; q += kBlock) (&s_cnt[0][0])[q] = 0;
   __syncthreads();
 
   const int32_t* __restrict__ key_in = key_is_row ? row_in : col_in;
-  const int wave_base = blockIdx.x * kSortTile + w * (kWave * kSortIPT);
+  const int32_t* __restrict__ oth_in = key_is_row ? col_in : row_in;
+  int32_t* __restrict__ key_out = key_is_row ? row_out : col_out;
+  int32_t* __restrict__ oth_out = key_is_row ? col_out : row_out;
+  const int tile_base = blockIdx.x * kSortTile;
+  const int tile_n = min(kSortTile, n - tile_base);
+  const int wave_base = tile_base + w * (kWave * kSortIPT);
   const uint64_t lanes_below = ((uint64_t)1 << lane) - 1;
   volatile int* cnt = s_cnt[w];
 
-  int32_t key[kSortIPT];
-  int rank[kSortIPT];
+  int32_t key[kSortIPT], oth[kSortIPT];
+  VT val[kSortIPT];
 #pragma unroll
-  for (int k = 0; k < kSortIPT; ++k) {
+  for (int k = 0; k < kSortIPT; ++k) {  // all loads of the tile are issued up front
     const int i = wave_base + k * kWave + lane;
     const bool valid = i < n;
     key[k] = valid ? key_in[i] : 0;
+    oth[k] = valid ? oth_in[i] : 0;
+    val[k] = valid ? val_in[i] : VT(0);
+  }
+  int lpos[kSortIPT];  // first the rank inside (wave, digit), later the slot in the sorted tile
+#pragma unroll
+  for (int k = 0; k < kSortIPT; ++k) {
+    const bool valid = wave_base + k * kWave + lane < n;
     const int d = digit_of(key[k], shift);
     uint64_t same = __ballot(valid);
 #pragma unroll
@@ -89,34 +108,64 @@ __global__ __launch_bounds__(kBlock) void radix_scatter_kernel(
     __builtin_amdgcn_wave_barrier();
     if (valid && before == 0) cnt[d] = basecnt + __popcll(same);
     __builtin_amdgcn_wave_barrier();
-    rank[k] = basecnt + before;
+    lpos[k] = basecnt + before;
   }
   __syncthreads();
-  {  // thread d: turn the per-wave counts of digit d into global start offsets
+  {  // thread d: where digit d starts inside the sorted tile and in global memory
     const int d = tid;
-    int run = off[(int64_t)d * ntiles + blockIdx.x];
+    int c[kWaves], tot = 0;
 #pragma unroll
     for (int u = 0; u < kWaves; ++u) {
-      const int c = s_cnt[u][d];
-      s_cnt[u][d] = run;
-      run += c;
+      c[u] = s_cnt[u][d];
+      tot += c[u];
+    }
+    int all;
+    int start = block_inclusive_sum(tot, &all) - tot;
+    s_gdelta[d] = off[(int64_t)d * ntiles + blockIdx.x] - start;
+#pragma unroll
+    for (int u = 0; u < kWaves; ++u) {
+      s_cnt[u][d] = start;
+      start += c[u];
     }
   }
   __syncthreads();
 #pragma unroll
   for (int k = 0; k < kSortIPT; ++k) {
-    const int i = wave_base + k * kWave + lane;
-    if (i < n) {
-      const int dst = s_cnt[w][digit_of(key[k], shift)] + rank[k];
-      if (key_is_row) {
-        row_out[dst] = key[k];
-        col_out[dst] = col_in[i];
-      } else {
-        col_out[dst] = key[k];
-        row_out[dst] = row_in[i];
-      }
-      val_out[dst] = val_in[i];
+    if (wave_base + k * kWave + lane < n) {
+      lpos[k] += s_cnt[w][digit_of(key[k], shift)];
+      s_buf32[lpos[k]] = key[k];
     }
+  }
+  __syncthreads();
+  int dst[kSortIPT];
+#pragma unroll
+  for (int k = 0; k < kSortIPT; ++k) {
+    const int j = k * kBlock + tid;
+    if (j < tile_n) {
+      const int32_t kk = s_buf32[j];
+      dst[k] = j + s_gdelta[digit_of(kk, shift)];
+      key_out[dst[k]] = kk;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kSortIPT; ++k)
+    if (wave_base + k * kWave + lane < n) s_buf32[lpos[k]] = oth[k];
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kSortIPT; ++k) {
+    const int j = k * kBlock + tid;
+    if (j < tile_n) oth_out[dst[k]] = s_buf32[j];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kSortIPT; ++k)
+    if (wave_base + k * kWave + lane < n) s_buf[lpos[k]] = val[k];
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kSortIPT; ++k) {
+    const int j = k * kBlock + tid;
+    if (j < tile_n) val_out[dst[k]] = s_buf[j];
   }
 }
 
