@@ -191,6 +191,9 @@ def main():
     ap.add_argument("--only", type=str, default="")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink every configuration (testing)")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy per step (known traffic, for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE); it is excluded from every figure")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported")
@@ -201,6 +204,11 @@ def main():
 
     items, cpu_jobs, keep = build_items(args)
     stream = torch.cuda.current_stream()
+    calib = None
+    if args.calib_copy:
+        ca = torch.zeros(1 << 28, dtype=torch.float32, device="cuda:0")
+        cb = torch.empty_like(ca)
+        calib = lambda: cb.copy_(ca)
 
     def step(record):
         for it in items:
@@ -213,6 +221,8 @@ def main():
                 it.events.append((a, b))
             else:
                 it.run()
+        if calib is not None:
+            calib()
 
     for _ in range(args.warmup):
         step(False)

@@ -149,7 +149,9 @@ def spt_mttkrp(B, Cm, Dm, J, A_out, ws=None, stream=None):
 class DeviceTensor:
     """spt_tensor descriptor whose level arrays live in device memory."""
 
-    def __init__(self, spec, device="cuda:0"):
+    def __init__(self, spec, device="cuda:0", misalign=False):
+        """misalign=True places every array one element past a 256-byte boundary
+        (exercises the kernels' paths for buffers that are not 16-byte aligned)."""
         import torch
         self.spec = spec
         self.device = device
@@ -174,16 +176,25 @@ class DeviceTensor:
                 if a is None:
                     continue
                 if id(a) not in shared:   # DIA shares one offset array between two levels
-                    d = torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(device)
+                    d = self._upload(np.ascontiguousarray(a, dtype=np.int32), device, misalign)
                     shared[id(a)] = d
                     self.keep.append(d)
                     setattr(self, f"{name}{k}", d)
                 setattr(o, name, shared[id(a)].data_ptr())
-        self.vals = torch.from_numpy(vals).to(device)
+        self.vals = self._upload(vals, device, misalign)
         t.vals = self.vals.data_ptr()
         t.nvals = vals.size
         self.torch_dtype = self.vals.dtype
         self.c = t
+
+    @staticmethod
+    def _upload(a, device, misalign):
+        import torch
+        if not misalign:
+            return torch.from_numpy(a).to(device)
+        buf = torch.empty(a.size + 1, dtype=torch.from_numpy(a).dtype, device=device)
+        buf[1:].copy_(torch.from_numpy(a))
+        return buf[1:]
 
     def workspace(self, op, J=0):
         import torch

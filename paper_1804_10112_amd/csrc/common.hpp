@@ -54,6 +54,17 @@ struct Workspace {
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 __device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
 
+// Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its
+// own L2. This maps blockIdx.x to a logical block id such that every XCD works
+// on one contiguous range of logical blocks, so neighbouring blocks (which
+// re-read each other's part of x) share an L2.
+constexpr int kXcds = 8;
+__device__ __forceinline__ int xcd_contiguous_block_id() {
+  const int nb = gridDim.x, q = nb / kXcds, rem = nb % kXcds;
+  const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+  return xcd * q + (xcd < rem ? xcd : rem) + slot;
+}
+
 // Accumulator used when partial sums of many workgroups are combined.
 template <typename T> struct Wide { using type = double; };
 

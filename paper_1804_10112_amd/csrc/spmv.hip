@@ -92,18 +92,12 @@ __global__ __launch_bounds__(kBlock) void dia_spmv_vec_kernel(int64_t N, int64_t
                                                               T* __restrict__ y) {
   constexpr int R = VecOf<T>::R;
   using V = typename VecOf<T>::type;
-  __shared__ int32_t s_off[kDiaMaxLdsOffsets];
-  const bool in_lds = K <= kDiaMaxLdsOffsets;
-  if (in_lds) {
-    for (int d = threadIdx.x; d < K; d += kBlock) s_off[d] = offset[d];
-    __syncthreads();
-  }
-  const int64_t i0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * R;
+  const int64_t i0 = ((int64_t)xcd_contiguous_block_id() * kBlock + threadIdx.x) * R;
   if (i0 >= N) return;
   V acc = 0;
 #pragma unroll 8
   for (int d = 0; d < K; ++d) {
-    const int64_t j0 = i0 + (in_lds ? s_off[d] : offset[d]);
+    const int64_t j0 = i0 + offset[d];  // uniform address: a scalar load
     if (j0 + R <= 0 || j0 >= M) continue;  // no row of this lane meets the diagonal
     const V v = ld_stream(reinterpret_cast<const V*>(vals + (int64_t)d * N + i0));
 #pragma unroll
@@ -153,11 +147,11 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // Output protocol: the workgroup that contains a row's first entry stores the
 // row's (possibly partial) sum with a plain store; the sum of the entries that
 // precede the first head of a chunk leaves as carry (key, value) number
-// blockIdx.x, key -1 if there is none.
+// `chunk`, key -1 if there is none.
 template <int IPT>
 __device__ __forceinline__ int lds_slot(int e) { return e + e / IPT; }
 
-template <typename T, bool CSR, int IPT>
+template <typename T, bool CSR, int IPT, bool VEC>
 __global__ __launch_bounds__(kBlock) void seg_spmv_kernel(
     int nnz, int nrows, const int32_t* __restrict__ pos_or_row, const int32_t* __restrict__ col,
     const T* __restrict__ vals, const T* __restrict__ x, T* __restrict__ y,
@@ -169,7 +163,8 @@ __global__ __launch_bounds__(kBlock) void seg_spmv_kernel(
   __shared__ int s_rows[2];
 
   const int tid = threadIdx.x;
-  const int base = blockIdx.x * CHUNK;  // host guarantees nnz + CHUNK < 2^31
+  const int chunk = xcd_contiguous_block_id();
+  const int base = chunk * CHUNK;  // host guarantees nnz + CHUNK < 2^31
   const int end = min(base + CHUNK, nnz);
   const bool last_chunk = (end == nnz);
 
@@ -183,22 +178,46 @@ __global__ __launch_bounds__(kBlock) void seg_spmv_kernel(
     }
   }
 
-  // phase 1
+  // phase 1: a lane loads R consecutive entries per step with 16-byte (fp32) or
+  // 8+16-byte (fp64) vector loads when the arrays allow it
+  constexpr int R = VecOf<T>::R;
+  using V = typename VecOf<T>::type;
+  using IV = typename VecOf<T>::itype;
   int32_t fill_key = -1;
   if (!CSR) fill_key = pos_or_row[end - 1];  // tail padding extends the last segment
 #pragma unroll
-  for (int k = 0; k < IPT; ++k) {
-    const int e = k * kBlock + tid;
-    const int p = base + e;
-    T prod = 0;
-    int32_t key = fill_key;
-    if (p < end) {
-      const int32_t c = ld_stream(col + p);
-      prod = ld_stream(vals + p) * x[c];
-      if (!CSR) key = ld_stream(pos_or_row + p);
+  for (int q = 0; q < IPT / R; ++q) {
+    const int e0 = (q * kBlock + tid) * R;
+    const int p0 = base + e0;
+    int32_t c[R], key[R];
+    T v[R];
+    bool ok[R];
+    if (VEC && p0 + R <= end) {
+      const IV cv = ld_stream(reinterpret_cast<const IV*>(col + p0));
+      const V vv = ld_stream(reinterpret_cast<const V*>(vals + p0));
+      IV kv = fill_key;
+      if (!CSR) kv = ld_stream(reinterpret_cast<const IV*>(pos_or_row + p0));
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        c[r] = cv[r];
+        v[r] = vv[r];
+        key[r] = kv[r];
+        ok[r] = true;
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        ok[r] = p0 + r < end;
+        c[r] = ok[r] ? ld_stream(col + p0 + r) : 0;
+        v[r] = ok[r] ? ld_stream(vals + p0 + r) : T(0);
+        key[r] = (!CSR && ok[r]) ? ld_stream(pos_or_row + p0 + r) : fill_key;
+      }
     }
-    s_val[lds_slot<IPT>(e)] = prod;
-    s_key[lds_slot<IPT>(e)] = key;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      s_val[lds_slot<IPT>(e0 + r)] = ok[r] ? v[r] * x[c[r]] : T(0);
+      s_key[lds_slot<IPT>(e0 + r)] = key[r];
+    }
   }
   int32_t prev_key = -1;  // key of the entry before the chunk (COO)
   if (!CSR && base > 0) prev_key = pos_or_row[base - 1];
@@ -252,8 +271,8 @@ __global__ __launch_bounds__(kBlock) void seg_spmv_kernel(
     if (in.f) {
       y[CSR ? in.k : first_close_key] = total;
     } else {  // first head of the chunk: what precedes it continues an earlier chunk
-      carry_key[blockIdx.x] = head_at_chunk_start ? -1 : (CSR ? carry_row : first_close_key);
-      carry_val[blockIdx.x] = total;
+      carry_key[chunk] = head_at_chunk_start ? -1 : (CSR ? carry_row : first_close_key);
+      carry_val[chunk] = total;
     }
   }
   if (tid == kBlock - 1) {  // the segment still open at the end of the chunk
@@ -262,8 +281,8 @@ __global__ __launch_bounds__(kBlock) void seg_spmv_kernel(
     } else if (in.f) {
       y[CSR ? in.k : kprev] = in.v + acc;
     } else {  // no head in the whole chunk: everything is carry
-      carry_key[blockIdx.x] = CSR ? carry_row : kprev;
-      carry_val[blockIdx.x] = in.v + acc;
+      carry_key[chunk] = CSR ? carry_row : kprev;
+      carry_val[chunk] = in.v + acc;
     }
   }
 }
@@ -319,8 +338,13 @@ static spt_status launch_seg(int64_t nnz, int64_t nrows, const int32_t* pos_or_r
     spt_status st = launch_fill<T>(y, nrows, T(0), s);
     if (st != SPT_OK) return st;
   }
-  hipLaunchKernelGGL((seg_spmv_kernel<T, CSR, kSegIPT>), dim3(nwg), dim3(kBlock), 0, s, (int)nnz,
-                     (int)nrows, pos_or_row, col, vals, x, y, ckey, cval);
+  const bool vec = aligned16(col) && aligned16(vals) && (CSR || aligned16(pos_or_row));
+  if (vec)
+    hipLaunchKernelGGL((seg_spmv_kernel<T, CSR, kSegIPT, true>), dim3(nwg), dim3(kBlock), 0, s,
+                       (int)nnz, (int)nrows, pos_or_row, col, vals, x, y, ckey, cval);
+  else
+    hipLaunchKernelGGL((seg_spmv_kernel<T, CSR, kSegIPT, false>), dim3(nwg), dim3(kBlock), 0, s,
+                       (int)nnz, (int)nrows, pos_or_row, col, vals, x, y, ckey, cval);
   SPT_CHECK_LAUNCH("seg_spmv");
   hipLaunchKernelGGL(carry_fixup_kernel<T>, dim3((nwg + kBlock - 1) / kBlock), dim3(kBlock), 0, s,
                      nwg, ckey, cval, y);

@@ -217,7 +217,11 @@ static spt_status ttv_coo_typed(const spt_tensor* B, const T* c, int32_t* out_i,
 // CSF    = i and k come from the upper levels (expanded into LDS per chunk) and
 //          the product with C[k,:] is applied once per fiber piece (factored
 //          form, Section 5.3 / CSF being the more efficient format).
-constexpr int kEPG = 128;
+// entries walked by one group of lanes, per mode: the CSF pre-phase is amortised over a
+// longer walk; the carry level is small and wants parallelism instead
+enum { MT_COO = 0, MT_LEVEL2 = 1, MT_CSF = 2 };
+template <int MODE> struct Epg { static constexpr int value = MODE == 2 ? 256 : (MODE == 1 ? 32 : 128); };
+constexpr int kU = 8;  // entries whose factor rows are in flight together
 
 template <typename T, int G>
 struct MttkrpShared {
@@ -229,7 +233,6 @@ struct MttkrpShared {
   int empty[kBlock / G];
 };
 
-enum { MT_COO = 0, MT_LEVEL2 = 1, MT_CSF = 2 };
 
 template <typename T, int G, int MODE>
 __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
@@ -244,6 +247,7 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
     const int32_t* __restrict__ in_key, const T* __restrict__ in_vec,
     T* __restrict__ A, int32_t* __restrict__ carry_key, T* __restrict__ carry_vec) {
   constexpr int NG = kBlock / G;
+  constexpr int kEPG = Epg<MODE>::value;
   constexpr int CHUNK = NG * kEPG;
   __shared__ MttkrpShared<T, G> sh;
   __shared__ int32_t s_i[MODE == MT_CSF ? CHUNK : 1];
@@ -329,7 +333,7 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
   // ---- group walk
   const int g0 = chunk_base + g * kEPG;
   const int g1 = min(g0 + kEPG, chunk_end);
-  T acc = 0, lead = 0, t = 0;
+  T acc = 0, lead = 0, t = 0, c_cur = 0;
   int has_head = 0, first_close = -1;
   int cur = -1, cur_k = -1;
   // cur = slice coordinate of the entry just before this group's first entry
@@ -363,44 +367,71 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
       }
     }
     const int cntb = min(G, g1 - b0);
-    for (int sidx = 0; sidx < cntb; ++sidx) {
-      const int i = __shfl(ri, sidx, G);
-      T term;
-      if (MODE == MT_LEVEL2) {
-        term = jok ? in_vec[(int64_t)(b0 + sidx) * J + j] : T(0);
-      } else {
-        const int k = __shfl(rk, sidx, G);
-        const int l = __shfl(rl, sidx, G);
-        const T v = __shfl(rv, sidx, G);
-        if (MODE == MT_COO) {
-          term = jok ? v * Cm[(int64_t)k * J + j] * Dm[(int64_t)l * J + j] : T(0);
+    // kU entries at a time: first issue all their factor-row loads (they are
+    // independent, so the cache latency is paid once per batch, not per entry),
+    // then run the segment logic over the batch in order.
+    for (int s0 = 0; s0 < cntb; s0 += kU) {
+      int ii[kU];
+      T fa[kU], fb[kU], vv[kU];
+      bool fh[kU];
+      int pi = cur, pk = cur_k;
+#pragma unroll
+      for (int u = 0; u < kU; ++u) {
+        const int sidx = s0 + u;  // < G because kU divides G
+        const bool live = sidx < cntb;
+        ii[u] = __shfl(ri, sidx, G);
+        fh[u] = false;
+        vv[u] = T(1);
+        fb[u] = T(1);
+        if (MODE == MT_LEVEL2) {
+          fa[u] = (live && jok) ? in_vec[(int64_t)(b0 + sidx) * J + j] : T(0);
         } else {
-          // factored: t accumulates v * D[l,:] inside one (i,k) fiber piece
-          if (i != cur || k != cur_k) {
-            if (cur_k >= 0 && jok) acc += Cm[(int64_t)cur_k * J + j] * t;
-            t = 0;
-            cur_k = k;
+          const int k = __shfl(rk, sidx, G);
+          const int l = __shfl(rl, sidx, G);
+          vv[u] = __shfl(rv, sidx, G);
+          fb[u] = (live && jok) ? Dm[(int64_t)l * J + j] : T(0);
+          if (MODE == MT_COO) {
+            fa[u] = (live && jok) ? Cm[(int64_t)k * J + j] : T(0);
+          } else {  // CSF: C[k,:] only where a new (i,k) fiber piece starts
+            fh[u] = live && (ii[u] != pi || k != pk);
+            fa[u] = (fh[u] && jok) ? Cm[(int64_t)k * J + j] : T(0);
+            if (live) {
+              pi = ii[u];
+              pk = k;
+            }
           }
-          term = jok ? v * Dm[(int64_t)l * J + j] : T(0);
         }
       }
-      if (i != cur) {
-        if (!has_head) {
-          lead = acc;
-          has_head = 1;
-          first_close = cur;
-        } else if (jok && cur >= 0) {
-          if (MODE == MT_LEVEL2) A[(int64_t)cur * J + j] += acc;
-          else A[(int64_t)cur * J + j] = acc;
+      cur_k = pk;
+#pragma unroll
+      for (int u = 0; u < kU; ++u) {
+        if (s0 + u < cntb) {
+          const int i = ii[u];
+          if (MODE == MT_CSF && fh[u]) {  // factored form: close the previous fiber piece
+            acc += c_cur * t;
+            t = 0;
+            c_cur = fa[u];
+          }
+          if (i != cur) {
+            if (!has_head) {
+              lead = acc;
+              has_head = 1;
+              first_close = cur;
+            } else if (jok && cur >= 0) {
+              if (MODE == MT_LEVEL2) A[(int64_t)cur * J + j] += acc;
+              else A[(int64_t)cur * J + j] = acc;
+            }
+            acc = 0;
+            cur = i;
+          }
+          if (MODE == MT_CSF) t += vv[u] * fb[u];
+          else if (MODE == MT_COO) acc += vv[u] * fa[u] * fb[u];
+          else acc += fa[u];
         }
-        acc = 0;
-        cur = i;
       }
-      if (MODE == MT_CSF) t += term;
-      else acc += term;
     }
   }
-  if (MODE == MT_CSF && cur_k >= 0 && jok) acc += Cm[(int64_t)cur_k * J + j] * t;
+  if (MODE == MT_CSF) acc += c_cur * t;
 
   sh.lead[g][gl] = lead;
   sh.tail[g][gl] = acc;
@@ -470,13 +501,17 @@ __global__ __launch_bounds__(kBlock) void vec_carry_fixup_kernel(int n, int J,
 }
 
 static int mttkrp_group(int J) { return J <= 32 ? 32 : 64; }
-static int mttkrp_chunk(int J) { return (kBlock / mttkrp_group(J)) * kEPG; }
+static int mttkrp_chunk(int J, int mode) {
+  const int epg = mode == MT_CSF ? Epg<MT_CSF>::value : (mode == MT_LEVEL2 ? Epg<MT_LEVEL2>::value : Epg<MT_COO>::value);
+  return (kBlock / mttkrp_group(J)) * epg;
+}
 
 size_t mttkrp_workspace(Format, const spt_tensor* B, int32_t J) {
   if (J < 1) J = 1;
-  const int64_t chunk = mttkrp_chunk(J);
+  const int64_t chunk = mttkrp_chunk(J, MT_COO);  // the smaller level-1 chunk of the two formats
+  const int64_t chunk2 = mttkrp_chunk(J, MT_LEVEL2);
   const int64_t n1 = (B->nvals + chunk - 1) / chunk;
-  const int64_t n2 = (n1 + chunk - 1) / chunk;
+  const int64_t n2 = (n1 + chunk2 - 1) / chunk2;
   return align_up((size_t)n1 * 4, 256) + align_up((size_t)n1 * J * 8, 256) +
          align_up((size_t)n2 * 4, 256) + align_up((size_t)n2 * J * 8, 256) + 256;
 }
@@ -484,7 +519,8 @@ size_t mttkrp_workspace(Format, const spt_tensor* B, int32_t J) {
 template <typename T, int G>
 static spt_status mttkrp_launch(Format f, const spt_tensor* B, const T* Cm, const T* Dm, int J,
                                 T* A, void* ws, size_t ws_bytes, hipStream_t s) {
-  constexpr int CHUNK = (kBlock / G) * kEPG;
+  const int CHUNK = mttkrp_chunk(J, f == Format::CSF3 ? MT_CSF : MT_COO);
+  const int CHUNK2 = mttkrp_chunk(J, MT_LEVEL2);
   const int64_t I = B->level[0].N;
   const int64_t nnz64 = B->nvals;
   if (nnz64 + CHUNK >= INT32_MAX || I * J >= ((int64_t)1 << 40))
@@ -500,7 +536,7 @@ static spt_status mttkrp_launch(Format f, const spt_tensor* B, const T* Cm, cons
     return fail(SPT_ERR_WORKSPACE, "mttkrp: workspace of %zu bytes needed, %zu given",
                 mttkrp_workspace(f, B, J), ws_bytes);
   const int n1 = (nnz + CHUNK - 1) / CHUNK;
-  const int n2 = (n1 + CHUNK - 1) / CHUNK;
+  const int n2 = (n1 + CHUNK2 - 1) / CHUNK2;
   Workspace W(ws, ws_bytes);
   int32_t* key1 = W.take<int32_t>(n1);
   T* vec1 = W.take<T>((size_t)n1 * J);

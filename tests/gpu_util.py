@@ -18,10 +18,10 @@ def assert_close(got, ref, mag, dtype, what=""):
                            f"mag {np.asarray(mag).ravel()[bad[:5]]}")
 
 
-def gpu_spmv(spec, x, repeat=1):
+def gpu_spmv(spec, x, repeat=1, misalign=False):
     import torch
     import paper_1804_10112_amd as spt
-    A = spt.DeviceTensor(spec)
+    A = spt.DeviceTensor(spec, misalign=misalign)
     xd = torch.from_numpy(np.ascontiguousarray(x)).cuda()
     ws = A.workspace(spt.SPT_OP_SPMV)
     outs = []

@@ -60,6 +60,20 @@ def test_csr_coo_degenerate_structures(dtype):
     _check(wl.coo_spec(20, 50, r, c, v), x, "coo duplicates")
 
 
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_buffers_that_are_not_16_byte_aligned(dtype):
+    """Arrays one element past an aligned address take the scalar-load paths."""
+    N, M = 1000, 1200
+    r, c, v = wl.random_coo_entries(N, M, 9000, seed=77, dtype=dtype)
+    x = wl.dense_vector(M, 7, dtype)
+    c2 = wl.config2(N=1000, dtype=dtype)
+    c3 = wl.config3(N=1000, dtype=dtype)
+    for spec, xx in ((wl.csr_from_sorted_coo(N, M, r, c, v), x), (wl.coo_spec(N, M, r, c, v), x),
+                     (c2["dia"], c2["x"]), (c3["ell"], c3["x"])):
+        ref, mag = oracle.spmv(spec, xx)
+        assert_close(gpu_spmv(spec, xx, misalign=True), ref, mag, dtype, spec.name + " misaligned")
+
+
 def test_config1_full_and_deterministic():
     c1 = wl.config1()
     for fmt in ("csr", "coo"):
