@@ -84,31 +84,56 @@ template <typename T> struct VecOf;
 template <> struct VecOf<double> { static constexpr int R = 2; typedef double type __attribute__((ext_vector_type(2))); typedef int32_t itype __attribute__((ext_vector_type(2))); };
 template <> struct VecOf<float> { static constexpr int R = 4; typedef float type __attribute__((ext_vector_type(4))); typedef int32_t itype __attribute__((ext_vector_type(4))); };
 
-template <typename T>
+// KT > 0: the number of diagonals is the compile-time constant KT, so all KT
+// diagonal loads and their x loads are issued before the first use (one memory
+// round trip per lane). KT == 0: any K, in batches of 8 (the tail batch re-reads
+// the last diagonal and masks it out). No load sits behind a branch: cells
+// outside the diagonal's row range are loaded (they are inside the array) but
+// never used, and x is read at a clamped index.
+template <typename T, int KT>
 __global__ __launch_bounds__(kBlock) void dia_spmv_vec_kernel(int64_t N, int64_t M, int K,
                                                               const int32_t* __restrict__ offset,
                                                               const T* __restrict__ vals,
                                                               const T* __restrict__ x,
                                                               T* __restrict__ y) {
   constexpr int R = VecOf<T>::R;
+  constexpr int B = KT > 0 ? KT : 8;
   using V = typename VecOf<T>::type;
   const int64_t i0 = ((int64_t)xcd_contiguous_block_id() * kBlock + threadIdx.x) * R;
   if (i0 >= N) return;
   V acc = 0;
-#pragma unroll 8
-  for (int d = 0; d < K; ++d) {
-    const int64_t j0 = i0 + offset[d];  // uniform address: a scalar load
-    if (j0 + R <= 0 || j0 >= M) continue;  // no row of this lane meets the diagonal
-    const V v = ld_stream(reinterpret_cast<const V*>(vals + (int64_t)d * N + i0));
+  const int kend = KT > 0 ? KT : K;
+  for (int d0 = 0; d0 < kend; d0 += B) {
+    V v[B];
+    T xv[B][R];
+    int64_t j0[B];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const int64_t j = j0 + r;
-      if (j >= 0 && j < M) acc[r] += v[r] * x[j];
+    for (int u = 0; u < B; ++u) {
+      const int d = min(d0 + u, kend - 1);
+      j0[u] = i0 + offset[d];  // uniform address: a scalar load
+      v[u] = ld_stream(reinterpret_cast<const V*>(vals + (int64_t)d * N + i0));
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const int64_t j = j0[u] + r;
+        xv[u][r] = x[j < 0 ? 0 : (j >= M ? M - 1 : j)];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < B; ++u) {
+      if (d0 + u < kend) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          const int64_t j = j0[u] + r;
+          acc[r] += (j >= 0 && j < M) ? v[u][r] * xv[u][r] : T(0);
+        }
+      }
     }
   }
   *reinterpret_cast<V*>(y + i0) = acc;
 }
 
+// Bound by the gathers of x (one cache line per stored entry), so the loop is
+// kept simple: padding neither gathers nor multiplies.
 template <typename T>
 __global__ __launch_bounds__(kBlock) void ell_spmv_vec_kernel(int64_t N, int W,
                                                               const int32_t* __restrict__ crd,
@@ -380,10 +405,26 @@ static spt_status spmv_typed(Format f, const spt_tensor* A, const T* x, T* y, vo
       if (K >= INT32_MAX) return fail(SPT_ERR_UNSUPPORTED, "spmv: too many diagonals");
       if (K == 0) return launch_fill<T>(y, N, T(0), s);
       constexpr int R = VecOf<T>::R;
+      if (M == 0) return launch_fill<T>(y, N, T(0), s);
       if (N % R == 0 && aligned16(vals) && aligned16(y)) {
         const int64_t lanes = N / R;
-        hipLaunchKernelGGL(dia_spmv_vec_kernel<T>, dim3((unsigned)((lanes + kBlock - 1) / kBlock)),
-                           dim3(kBlock), 0, s, N, M, (int)K, A->level[1].offset, vals, x, y);
+        const dim3 grid((unsigned)((lanes + kBlock - 1) / kBlock));
+        const int32_t* off = A->level[1].offset;
+#define SPT_DIA_CASE(KT)                                                                       \
+  case KT:                                                                                     \
+    hipLaunchKernelGGL((dia_spmv_vec_kernel<T, KT>), grid, dim3(kBlock), 0, s, N, M, (int)K, off, \
+                       vals, x, y);                                                            \
+    break;
+        switch (K <= 16 ? (int)K : 0) {
+          SPT_DIA_CASE(1) SPT_DIA_CASE(2) SPT_DIA_CASE(3) SPT_DIA_CASE(4) SPT_DIA_CASE(5)
+          SPT_DIA_CASE(6) SPT_DIA_CASE(7) SPT_DIA_CASE(8) SPT_DIA_CASE(9) SPT_DIA_CASE(10)
+          SPT_DIA_CASE(11) SPT_DIA_CASE(12) SPT_DIA_CASE(13) SPT_DIA_CASE(14) SPT_DIA_CASE(15)
+          SPT_DIA_CASE(16)
+          default:
+            hipLaunchKernelGGL((dia_spmv_vec_kernel<T, 0>), grid, dim3(kBlock), 0, s, N, M, (int)K,
+                               off, vals, x, y);
+        }
+#undef SPT_DIA_CASE
       } else {
         hipLaunchKernelGGL(dia_spmv_kernel<T>, dim3((unsigned)((N + kBlock - 1) / kBlock)),
                            dim3(kBlock), 0, s, N, M, (int)K, A->level[1].offset, vals, x, y);
@@ -396,6 +437,7 @@ static spt_status spmv_typed(Format f, const spt_tensor* A, const T* x, T* y, vo
       if (N == 0) return SPT_OK;
       if (Wd >= INT32_MAX) return fail(SPT_ERR_UNSUPPORTED, "spmv: ELL width too large");
       constexpr int R = VecOf<T>::R;
+      if (Wd == 0 || A->level[2].N == 0) return launch_fill<T>(y, N, T(0), s);
       if (N % R == 0 && aligned16(vals) && aligned16(y) && aligned16(A->level[2].crd)) {
         const int64_t lanes = N / R;
         hipLaunchKernelGGL(ell_spmv_vec_kernel<T>, dim3((unsigned)((lanes + kBlock - 1) / kBlock)),
