@@ -36,15 +36,43 @@ constexpr int kTtvChunk = kTtvIPT * kBlock;
 __device__ __forceinline__ int ttv_slot(int e) { return e + e / kTtvIPT; }
 
 // heads[w] = number of (i,j) fiber starts among the entries of chunk w.
+// VEC: 16-byte coordinate loads (needs 16-byte aligned ci, cj).
+template <bool VEC>
 __global__ __launch_bounds__(kBlock) void ttv_count_kernel(int nnz, const int32_t* __restrict__ ci,
                                                            const int32_t* __restrict__ cj,
                                                            int32_t* __restrict__ heads) {
   const int base = blockIdx.x * kTtvChunk;
   int cnt = 0;
+  if (VEC) {
+    typedef int32_t i4 __attribute__((ext_vector_type(4)));
 #pragma unroll
-  for (int k = 0; k < kTtvIPT; ++k) {
-    const int p = base + k * kBlock + threadIdx.x;
-    if (p < nnz) cnt += (p == 0 || ci[p] != ci[p - 1] || cj[p] != cj[p - 1]) ? 1 : 0;
+    for (int q = 0; q < kTtvIPT / 4; ++q) {
+      const int p0 = base + (q * kBlock + threadIdx.x) * 4;
+      if (p0 + 4 <= nnz) {
+        const i4 a = ldg_stream(reinterpret_cast<const i4*>(ci + p0));
+        const i4 b = ldg_stream(reinterpret_cast<const i4*>(cj + p0));
+        int pa = -1, pb = -1;
+        if (p0 > 0) {
+          pa = ci[p0 - 1];
+          pb = cj[p0 - 1];
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          cnt += (a[r] != pa || b[r] != pb) ? 1 : 0;
+          pa = a[r];
+          pb = b[r];
+        }
+      } else {
+        for (int p = p0; p < nnz && p < p0 + 4; ++p)
+          cnt += (p == 0 || ci[p] != ci[p - 1] || cj[p] != cj[p - 1]) ? 1 : 0;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < kTtvIPT; ++k) {
+      const int p = base + k * kBlock + threadIdx.x;
+      if (p < nnz) cnt += (p == 0 || ci[p] != ci[p - 1] || cj[p] != cj[p - 1]) ? 1 : 0;
+    }
   }
   int total;
   block_inclusive_sum(cnt, &total);
@@ -61,7 +89,11 @@ __global__ void ttv_total_kernel(int nchunks, const int32_t* __restrict__ heads,
 // inside the chunk (append order = ascending (i,j), Section 3.4). The thread
 // holding a head appends the coordinates; the thread holding the fiber's end
 // stores the value. Carry protocol as in the SpMV kernel, keyed by output index.
-template <typename T>
+template <typename T> struct TtvVec;
+template <> struct TtvVec<double> { static constexpr int R = 2; typedef double type __attribute__((ext_vector_type(2))); typedef int32_t itype __attribute__((ext_vector_type(2))); };
+template <> struct TtvVec<float> { static constexpr int R = 4; typedef float type __attribute__((ext_vector_type(4))); typedef int32_t itype __attribute__((ext_vector_type(4))); };
+
+template <typename T, bool VEC>
 __global__ __launch_bounds__(kBlock) void ttv_coo_kernel(
     int nnz, const int32_t* __restrict__ ci, const int32_t* __restrict__ cj,
     const int32_t* __restrict__ ck, const T* __restrict__ vals, const T* __restrict__ c,
@@ -76,20 +108,45 @@ __global__ __launch_bounds__(kBlock) void ttv_coo_kernel(
   const int base = blockIdx.x * kTtvChunk;
   const int end = min(base + kTtvChunk, nnz);
   const int32_t fill_i = ci[end - 1], fill_j = cj[end - 1];
+  constexpr int R = TtvVec<T>::R;
+  using V = typename TtvVec<T>::type;
+  using IV = typename TtvVec<T>::itype;
 #pragma unroll
-  for (int k = 0; k < kTtvIPT; ++k) {
-    const int e = k * kBlock + tid;
-    const int p = base + e;
-    T prod = 0;
-    int32_t i = fill_i, j = fill_j;
-    if (p < end) {
-      i = ldg_stream(ci + p);
-      j = ldg_stream(cj + p);
-      prod = ldg_stream(vals + p) * c[ldg_stream(ck + p)];
+  for (int q = 0; q < kTtvIPT / R; ++q) {
+    const int e0 = (q * kBlock + tid) * R;
+    const int p0 = base + e0;
+    int32_t i[R], j[R], k[R];
+    T v[R];
+    bool ok[R];
+    if (VEC && p0 + R <= end) {
+      const IV iv = ldg_stream(reinterpret_cast<const IV*>(ci + p0));
+      const IV jv = ldg_stream(reinterpret_cast<const IV*>(cj + p0));
+      const IV kv = ldg_stream(reinterpret_cast<const IV*>(ck + p0));
+      const V vv = ldg_stream(reinterpret_cast<const V*>(vals + p0));
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        i[r] = iv[r];
+        j[r] = jv[r];
+        k[r] = kv[r];
+        v[r] = vv[r];
+        ok[r] = true;
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        ok[r] = p0 + r < end;
+        i[r] = ok[r] ? ldg_stream(ci + p0 + r) : fill_i;
+        j[r] = ok[r] ? ldg_stream(cj + p0 + r) : fill_j;
+        k[r] = ok[r] ? ldg_stream(ck + p0 + r) : 0;
+        v[r] = ok[r] ? ldg_stream(vals + p0 + r) : T(0);
+      }
     }
-    s_val[ttv_slot(e)] = prod;
-    s_i[ttv_slot(e)] = i;
-    s_j[ttv_slot(e)] = j;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      s_val[ttv_slot(e0 + r)] = ok[r] ? v[r] * c[k[r]] : T(0);
+      s_i[ttv_slot(e0 + r)] = i[r];
+      s_j[ttv_slot(e0 + r)] = j[r];
+    }
   }
   int32_t pi = -1, pj = -1;  // coordinates of the entry before this thread's items
   if (tid == 0 && base > 0) {
@@ -191,14 +248,21 @@ static spt_status ttv_coo_typed(const spt_tensor* B, const T* c, int32_t* out_i,
   T* cval = W.take<T>(nch);
   int32_t* scan_tmp = reinterpret_cast<int32_t*>(W.take<char>(scan_workspace(nch)));
   const int32_t *ci = B->level[0].crd, *cj = B->level[1].crd, *ck = B->level[2].crd;
-  hipLaunchKernelGGL(ttv_count_kernel, dim3(nch), dim3(kBlock), 0, s, nnz, ci, cj, heads);
+  auto al = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+  const bool vec = al(ci) && al(cj) && al(ck) && al(B->vals);
+  if (vec) hipLaunchKernelGGL(ttv_count_kernel<true>, dim3(nch), dim3(kBlock), 0, s, nnz, ci, cj, heads);
+  else hipLaunchKernelGGL(ttv_count_kernel<false>, dim3(nch), dim3(kBlock), 0, s, nnz, ci, cj, heads);
   SPT_CHECK_LAUNCH("ttv_count");
   spt_status st = device_scan_i32<false>(heads, off, nch, scan_tmp, s);
   if (st != SPT_OK) return st;
   hipLaunchKernelGGL(ttv_total_kernel, dim3(1), dim3(kWave), 0, s, nch, heads, off, out_nnz);
   SPT_CHECK_LAUNCH("ttv_total");
-  hipLaunchKernelGGL(ttv_coo_kernel<T>, dim3(nch), dim3(kBlock), 0, s, nnz, ci, cj, ck,
-                     static_cast<const T*>(B->vals), c, off, out_i, out_j, out_v, ckey, cval);
+  if (vec)
+    hipLaunchKernelGGL((ttv_coo_kernel<T, true>), dim3(nch), dim3(kBlock), 0, s, nnz, ci, cj, ck,
+                       static_cast<const T*>(B->vals), c, off, out_i, out_j, out_v, ckey, cval);
+  else
+    hipLaunchKernelGGL((ttv_coo_kernel<T, false>), dim3(nch), dim3(kBlock), 0, s, nnz, ci, cj, ck,
+                       static_cast<const T*>(B->vals), c, off, out_i, out_j, out_v, ckey, cval);
   SPT_CHECK_LAUNCH("ttv_coo");
   hipLaunchKernelGGL(carry_fixup_kernel<T>, dim3((nch + kBlock - 1) / kBlock), dim3(kBlock), 0, s,
                      nch, ckey, cval, out_v);

@@ -33,10 +33,10 @@ def gpu_spmv(spec, x, repeat=1, misalign=False):
     return outs[0] if repeat == 1 else outs
 
 
-def gpu_coo_to_csr(spec, order):
+def gpu_coo_to_csr(spec, order, misalign=False):
     import torch
     import paper_1804_10112_amd as spt
-    A = spt.DeviceTensor(spec)
+    A = spt.DeviceTensor(spec, misalign=misalign)
     N, nnz = spec.dims[0], len(spec.vals)
     pos = torch.full((N + 1,), -7, dtype=torch.int32, device="cuda")
     crd = torch.full((max(nnz, 1),), -7, dtype=torch.int32, device="cuda")
@@ -47,11 +47,11 @@ def gpu_coo_to_csr(spec, order):
     return pos.cpu().numpy(), crd.cpu().numpy()[:nnz], vals.cpu().numpy()[:nnz]
 
 
-def gpu_ttv(spec, c):
+def gpu_ttv(spec, c, misalign=False):
     """Returns (out_i, out_j, out_vals, count) for COO input, (None, None, out_vals, count) for CSF."""
     import torch
     import paper_1804_10112_amd as spt
-    B = spt.DeviceTensor(spec)
+    B = spt.DeviceTensor(spec, misalign=misalign)
     cd = torch.from_numpy(np.ascontiguousarray(c)).cuda()
     nnz = len(spec.vals)
     is_csf = spec.levels[1].kind == 1
@@ -69,10 +69,10 @@ def gpu_ttv(spec, c):
     return oi.cpu().numpy()[:n], oj.cpu().numpy()[:n], ov.cpu().numpy()[:n], n
 
 
-def gpu_mttkrp(spec, Cm, Dm):
+def gpu_mttkrp(spec, Cm, Dm, misalign=False):
     import torch
     import paper_1804_10112_amd as spt
-    B = spt.DeviceTensor(spec)
+    B = spt.DeviceTensor(spec, misalign=misalign)
     Cd = torch.from_numpy(np.ascontiguousarray(Cm)).cuda()
     Dd = torch.from_numpy(np.ascontiguousarray(Dm)).cuda()
     J = Cm.shape[1]

@@ -56,6 +56,16 @@ def test_degenerate_shapes(order):
     assert list(pos) == [0, 1, 2, 3, 4, 5] and np.array_equal(crd, c)
 
 
+@pytest.mark.parametrize("order", [0, 1])
+def test_buffers_that_are_not_16_byte_aligned(order):
+    N, M = 700, 900
+    r, c, v = wl.random_coo_entries(N, M, 20_000, seed=12, sort=False)
+    spec = wl.coo_spec(N, M, r, c, v, ordered=False)
+    pos, crd, vout = gpu_coo_to_csr(spec, order, misalign=True)
+    rpos, rcrd, rv, _ = oracle.coo_to_csr(N, r, c, v, order)
+    assert np.array_equal(pos, rpos) and np.array_equal(crd, rcrd) and np.array_equal(vout, rv)
+
+
 def test_sorted_flagged_input_skips_the_sort():
     N, M = 800, 900
     r, c, v = wl.random_coo_entries(N, M, 30_000, seed=6)

@@ -115,6 +115,23 @@ def test_mttkrp_degenerate_and_exact():
     assert np.array_equal(A, np.zeros((5, 32), np.float32))
 
 
+def test_buffers_that_are_not_16_byte_aligned():
+    dims = (300, 41, 57)
+    coo, csf = _tensor(dims, 9000, 11, np.float32)
+    c = wl.dense_vector(dims[2], 1, np.float32, "u01")
+    ri, rj, rv, rm = oracle.ttv(coo, c)
+    oi, oj, ov, n = gpu_ttv(coo, c, misalign=True)
+    assert n == len(ri) and np.array_equal(oi, ri) and np.array_equal(oj, rj)
+    assert_close(ov, rv, rm, np.float32, "ttv coo misaligned")
+    assert_close(gpu_ttv(csf, c, misalign=True)[2], rv, rm, np.float32, "ttv csf misaligned")
+    rng = np.random.default_rng(3)
+    Cm = rng.uniform(0, 1, (dims[1], 32)).astype(np.float32)
+    Dm = rng.uniform(0, 1, (dims[2], 32)).astype(np.float32)
+    ref, mag = oracle.mttkrp(coo, Cm, Dm)
+    assert_close(gpu_mttkrp(coo, Cm, Dm, misalign=True), ref, mag, np.float32, "mttkrp coo misaligned")
+    assert_close(gpu_mttkrp(csf, Cm, Dm, misalign=True), ref, mag, np.float32, "mttkrp csf misaligned")
+
+
 def test_scaled_config5():
     c5 = wl.config5(dims=(2000, 1600, 1000), nnz=400_000)
     _check_ttv(c5["coo"], c5["csf"], c5["c"], "c5 ttv")
