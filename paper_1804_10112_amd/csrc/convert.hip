@@ -89,6 +89,9 @@ __global__ __launch_bounds__(kBlock) void radix_scatter_kernel(
   __shared__ VT s_buf[kSortTile];
   int32_t* s_buf32 = reinterpret_cast<int32_t*>(s_buf);
   const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
+  // neighbouring tiles store to neighbouring addresses of every digit's run: keep them on
+  // one XCD so that partially written cache lines meet in the same L2
+  const int tile = xcd_contiguous_block_id();
   for (int q = tid; q < kWaves * kRadix; q += kBlock) (&s_cnt[0][0])[q] = 0;
   __syncthreads();
 
@@ -96,7 +99,7 @@ __global__ __launch_bounds__(kBlock) void radix_scatter_kernel(
   const int32_t* __restrict__ oth_in = key_is_row ? col_in : row_in;
   int32_t* __restrict__ key_out = key_is_row ? row_out : col_out;
   int32_t* __restrict__ oth_out = key_is_row ? col_out : row_out;
-  const int tile_base = blockIdx.x * kSortTile;
+  const int tile_base = tile * kSortTile;
   const int tile_n = min(kSortTile, n - tile_base);
   const int wave_base = tile_base + w * (kWave * kSortIPT);
   const uint64_t lanes_below = ((uint64_t)1 << lane) - 1;
@@ -143,7 +146,7 @@ __global__ __launch_bounds__(kBlock) void radix_scatter_kernel(
     }
     int all;
     int start = block_inclusive_sum(tot, &all) - tot;
-    s_gdelta[d] = off[(int64_t)d * ntiles + blockIdx.x] - start;
+    s_gdelta[d] = off[(int64_t)d * ntiles + tile] - start;
 #pragma unroll
     for (int u = 0; u < kWaves; ++u) {
       s_cnt[u][d] = start;
