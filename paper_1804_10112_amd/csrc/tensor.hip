@@ -105,7 +105,8 @@ __global__ __launch_bounds__(kBlock) void ttv_coo_kernel(
   __shared__ SegScanStorage<T> s_scan;
 
   const int tid = threadIdx.x;
-  const int base = blockIdx.x * kTtvChunk;
+  const int chunk = blockIdx.x;  // plain order: one sequential stream per array reads fastest
+  const int base = chunk * kTtvChunk;
   const int end = min(base + kTtvChunk, nnz);
   const int32_t fill_i = ci[end - 1], fill_j = cj[end - 1];
   constexpr int R = TtvVec<T>::R;
@@ -174,7 +175,7 @@ __global__ __launch_bounds__(kBlock) void ttv_coo_kernel(
   }
   const int cnt = __popc(headmask);
   int wg_heads;
-  int next_idx = chunk_off[blockIdx.x] + block_inclusive_sum(cnt, &wg_heads) - cnt;
+  int next_idx = chunk_off[chunk] + block_inclusive_sum(cnt, &wg_heads) - cnt;
 
   T acc = 0, lead = 0;
   int has_head = 0, last_key = -1;
@@ -196,15 +197,15 @@ __global__ __launch_bounds__(kBlock) void ttv_coo_kernel(
   }
 
   SegSum<T> in = block_seg_exclusive_scan<T>(SegSum<T>{has_head, acc, last_key}, s_scan);
-  const int carry_idx = chunk_off[blockIdx.x] - 1;  // fiber cut by the chunk start
+  const int carry_idx = chunk_off[chunk] - 1;  // fiber cut by the chunk start
   if (has_head) {
     const T total = in.v + lead;
     if (in.f) {
       out_v[in.k] = total;
     } else {
       const bool at_start = (tid == 0) && (headmask & 1u);
-      carry_key[blockIdx.x] = at_start ? -1 : carry_idx;
-      carry_val[blockIdx.x] = total;
+      carry_key[chunk] = at_start ? -1 : carry_idx;
+      carry_val[chunk] = total;
     }
   }
   if (tid == kBlock - 1) {
@@ -213,8 +214,8 @@ __global__ __launch_bounds__(kBlock) void ttv_coo_kernel(
     } else if (in.f) {
       out_v[in.k] = in.v + acc;
     } else {
-      carry_key[blockIdx.x] = carry_idx;
-      carry_val[blockIdx.x] = in.v + acc;
+      carry_key[chunk] = carry_idx;
+      carry_val[chunk] = in.v + acc;
     }
   }
 }
@@ -323,7 +324,8 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
   const int g = tid / G, gl = tid % G;
   const int j = blockIdx.y * G + gl;
   const bool jok = j < J;
-  const int chunk_base = blockIdx.x * CHUNK;
+  const int chunk = xcd_contiguous_block_id();
+  const int chunk_base = chunk * CHUNK;
   const int chunk_end = min(chunk_base + CHUNK, n);
 
   if (MODE == MT_CSF) {
@@ -523,8 +525,8 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
             else A[(int64_t)key * J + j] = total;
           }
         } else {  // precedes the first head of the chunk: carry (key < 0: nothing precedes)
-          if (jok) carry_vec[(int64_t)blockIdx.x * J + j] = total;
-          if (gl == 0 && blockIdx.y == 0) carry_key[blockIdx.x] = key < 0 ? -1 : key;
+          if (jok) carry_vec[(int64_t)chunk * J + j] = total;
+          if (gl == 0 && blockIdx.y == 0) carry_key[chunk] = key < 0 ? -1 : key;
           carried = true;
         }
         run = sh.tail[q][gl];
@@ -540,8 +542,8 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
         else A[(int64_t)last * J + j] = run;
       }
     } else if (!carried) {
-      if (jok) carry_vec[(int64_t)blockIdx.x * J + j] = run;
-      if (gl == 0 && blockIdx.y == 0) carry_key[blockIdx.x] = last;
+      if (jok) carry_vec[(int64_t)chunk * J + j] = run;
+      if (gl == 0 && blockIdx.y == 0) carry_key[chunk] = last;
     }
   }
 }
