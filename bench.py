@@ -163,6 +163,60 @@ def build_items(args):
     return items, cpu_jobs, keep
 
 
+def measure_ceilings():
+    """Achievable ceilings of this machine for the two access patterns that bound the path:
+    a pure streaming read (16 / 8 / 4 bytes per lane) and random gathers from tables of the
+    sizes of config 3's x (1M fp32) and config 4's x (4M fp64). Library probe kernels."""
+    import torch
+    import paper_1804_10112_amd as spt
+    dev = "cuda:0"
+    out = {}
+    nbytes = 1 << 30
+    src = torch.zeros(nbytes // 4, dtype=torch.float32, device=dev)
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+
+    def timed(fn, reps=10):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps * 1e-3
+
+    for lane in (16, 8, 4):
+        t = timed(lambda: spt.spt_probe_read(src, nbytes, lane, sink))
+        out[f"read_{lane}B_per_lane_GBs"] = round(nbytes / t / 1e9, 1)
+    n = 1 << 25
+    g = torch.Generator(device=dev)
+    g.manual_seed(1)
+    for name, rows, tdt, sdt in (("gather_f32_table_1M", 1_000_000, torch.float32, spt.SPT_F32),
+                                 ("gather_f64_table_4M", 4_000_000, torch.float64, spt.SPT_F64)):
+        idx = torch.randint(0, rows, (n,), dtype=torch.int32, device=dev, generator=g)
+        table = torch.zeros(rows, dtype=tdt, device=dev)
+        o = torch.empty(n, dtype=tdt, device=dev)
+        t = timed(lambda: spt.spt_probe_gather(idx, n, table, sdt, o))
+        out[name + "_Gelem_s"] = round(n / t / 1e9, 1)
+    del src
+    return out
+
+
+def read_traffic_file():
+    """HBM traffic per launch measured offline with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
+    kept as `name = bytes` lines in profiles/hbm_traffic_pmc.txt; {} if the file is absent."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_pmc.txt")
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            line = line.split("#")[0].strip()
+            if "=" in line:
+                k, v = line.split("=")
+                out[k.strip()] = int(float(v))
+    return out
+
+
 def cpu_baseline(cpu_jobs, budget_s=20.0):
     """The oracle's plain per-format loops (single thread, as the paper measured)
     on the same inputs, one call each, stopping once the time budget is spent."""
@@ -191,6 +245,7 @@ def main():
     ap.add_argument("--only", type=str, default="")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink every configuration (testing)")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy per step (known traffic, for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE); it is excluded from every figure")
@@ -211,16 +266,18 @@ def main():
         calib = lambda: cb.copy_(ca)
 
     def step(record):
+        # one event between consecutive calls: the end of call k is the start of call k+1
+        prev = None
+        if record:
+            prev = torch.cuda.Event(enable_timing=True)
+            prev.record(stream)
         for it in items:
+            it.run()
             if record:
-                a = torch.cuda.Event(enable_timing=True)
-                b = torch.cuda.Event(enable_timing=True)
-                a.record(stream)
-                it.run()
-                b.record(stream)
-                it.events.append((a, b))
-            else:
-                it.run()
+                e = torch.cuda.Event(enable_timing=True)
+                e.record(stream)
+                it.events.append((prev, e))
+                prev = e
         if calib is not None:
             calib()
 
@@ -234,13 +291,16 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
 
+    traffic = read_traffic_file()
     kernels = []
     for it in items:
         ms = float(np.mean([a.elapsed_time(b) for a, b in it.events]))
         gbs = it.bytes / (ms * 1e-3) / 1e9
         kernels.append({"name": it.name, "ms": round(ms, 4), "gflops": round(it.flops / (ms * 1e-3) / 1e9, 2),
                         "alg_gbs": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
-                        "alg_bytes": it.bytes})
+                        "alg_bytes": it.bytes, "traffic": traffic.get(it.name)})
+        if it.note:
+            kernels[-1]["note"] = it.note
     dom = max(kernels, key=lambda k: k["ms"])
     total_flops = sum(it.flops for it in items)
     out = {
@@ -255,10 +315,12 @@ def main():
                                + ", ".join(it.name for it in items), "scale": args.scale},
         "roofline": {"bound": "hbm", "kernel": dom["name"], "achieved": dom["alg_gbs"],
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom["frac_hbm_peak"],
-                     "traffic": None},
+                     "traffic": dom["traffic"]},
         "kernels": kernels,
         "library": spt.spt_version(),
     }
+    if not args.no_ceilings:
+        out["ceilings"] = measure_ceilings()
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cpu_jobs)
     print(json.dumps(out), flush=True)

@@ -182,6 +182,23 @@ const char* spt_last_error(void);
 /* Library version string, e.g. "spt 0.1 gfx950". */
 const char* spt_version(void);
 
+/*
+ * Measurement aids (no counterpart in the paper): the two access patterns that
+ * bound every kernel above, isolated, so that a benchmark can state the
+ * machine's achievable ceilings next to the kernels' figures.
+ *  spt_probe_read   streams `bytes` bytes of src (16-byte aligned, bytes a
+ *                   multiple of 16) once, lane_bytes = 4, 8 or 16 per lane
+ *                   load; nothing is written except when the data sums to a
+ *                   magic value (sink: device, >= 4 bytes).
+ *  spt_probe_gather out[p] = table[idx[p]] for p < n (idx: device int32 in
+ *                   range, table/out: dtype elements): the random cache-line
+ *                   gather of x / factor rows.
+ */
+spt_status spt_probe_read(const void* src, size_t bytes, int32_t lane_bytes, void* sink,
+                          void* stream);
+spt_status spt_probe_gather(const int32_t* idx, int64_t n, const void* table, int32_t dtype,
+                            void* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ SPT_ORDERED, SPT_UNIQUE = 1, 2
 SPT_F32, SPT_F64 = 0, 1
 
 SYMBOLS = ["spt_spmv", "spt_coo_to_csr", "spt_ttv", "spt_mttkrp", "spt_workspace_bytes",
-           "spt_last_error", "spt_version"]
+           "spt_last_error", "spt_version", "spt_probe_read", "spt_probe_gather"]
 
 
 class SptLevel(C.Structure):
@@ -71,6 +71,10 @@ def lib():
         L.spt_last_error.argtypes = []
         L.spt_version.restype = C.c_char_p
         L.spt_version.argtypes = []
+        L.spt_probe_read.restype = i32
+        L.spt_probe_read.argtypes = [vp, sz, i32, vp, vp]
+        L.spt_probe_gather.restype = i32
+        L.spt_probe_gather.argtypes = [vp, C.c_int64, vp, i32, vp, vp]
         _lib = L
     return _lib
 
@@ -144,6 +148,14 @@ def spt_ttv(B, c, out_crd0, out_crd1, out_vals, out_nnz_dev, ws=None, stream=Non
 def spt_mttkrp(B, Cm, Dm, J, A_out, ws=None, stream=None):
     p, n = _ws(ws)
     _check(lib().spt_mttkrp(_desc(B), _p(Cm), _p(Dm), J, _p(A_out), p, n, _stream(stream)))
+
+
+def spt_probe_read(src, nbytes, lane_bytes, sink, stream=None):
+    _check(lib().spt_probe_read(_p(src), nbytes, lane_bytes, _p(sink), _stream(stream)))
+
+
+def spt_probe_gather(idx, n, table, dtype, out, stream=None):
+    _check(lib().spt_probe_gather(_p(idx), n, _p(table), dtype, _p(out), _stream(stream)))
 
 
 class DeviceTensor:
