@@ -23,6 +23,7 @@ spt_status fail(spt_status code, const char* fmt, ...) {
 spt_status spmv_dispatch(Format f, const spt_tensor* A, const void* x, void* y, void* ws,
                          size_t ws_bytes, hipStream_t s);
 size_t seg_spmv_workspace(int64_t nnz);
+size_t coo_unordered_workspace(int dtype, int64_t nnz, int64_t nrows);
 spt_status coo_to_csr_dispatch(const spt_tensor* A, int32_t order, int32_t* pos_out,
                                int32_t* crd_out, void* vals_out, void* ws, size_t ws_bytes,
                                hipStream_t s);
@@ -245,7 +246,10 @@ size_t spt_workspace_bytes(int32_t op, const spt_tensor* T, int32_t J) {
   size_t n = 0;
   switch (op) {
     case SPT_OP_SPMV:
-      n = (f == Format::CSR || f == Format::COO2) ? seg_spmv_workspace(T->nvals) : 0;
+      if (f == Format::CSR || (f == Format::COO2 && (T->level[0].flags & SPT_ORDERED)))
+        n = seg_spmv_workspace(T->nvals);
+      else if (f == Format::COO2)
+        n = coo_unordered_workspace(T->dtype, T->nvals, T->level[0].N);
       break;
     case SPT_OP_COO_TO_CSR:
       n = f == Format::COO2 ? coo_to_csr_workspace(T) : 0;

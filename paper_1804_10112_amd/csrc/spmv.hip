@@ -327,6 +327,18 @@ __global__ __launch_bounds__(kBlock) void coo_atomic_spmv_kernel(
 
 // ---------------------------------------------------------------- launchers
 
+// binned scatter for large unordered COO (coo_bin.hip)
+template <typename T>
+spt_status coo_binned_spmv(int64_t nnz, int64_t nrows, const int32_t* row, const int32_t* col,
+                           const T* vals, const T* x, T* y, void* ws, size_t ws_bytes,
+                           hipStream_t s);
+size_t coo_binned_workspace(int dtype, int64_t nnz, int64_t nrows);
+constexpr int64_t kBinnedMinEntries = 1 << 15;  // below this one atomic per entry is cheaper
+
+size_t coo_unordered_workspace(int dtype, int64_t nnz, int64_t nrows) {
+  return nnz >= kBinnedMinEntries ? coo_binned_workspace(dtype, nnz, nrows) : 256;
+}
+
 constexpr int kSegIPT = 8;
 
 size_t seg_spmv_workspace(int64_t nnz) {
@@ -391,6 +403,9 @@ static spt_status spmv_typed(Format f, const spt_tensor* A, const T* x, T* y, vo
         return launch_seg<T, false>(nnz, N, A->level[0].crd, A->level[1].crd, vals, x, y, ws,
                                     ws_bytes, s);
       if (nnz >= INT32_MAX) return fail(SPT_ERR_UNSUPPORTED, "spmv: more than 2^31 entries");
+      if (nnz >= kBinnedMinEntries)
+        return coo_binned_spmv<T>(nnz, N, A->level[0].crd, A->level[1].crd, vals, x, y, ws, ws_bytes,
+                                  s);
       spt_status st = launch_fill<T>(y, N, T(0), s);
       if (st != SPT_OK || nnz == 0) return st;
       hipLaunchKernelGGL(coo_atomic_spmv_kernel<T>, dim3((unsigned)((nnz + kBlock - 1) / kBlock)),
