@@ -247,8 +247,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy per step (known traffic, for scaling "
-                         "rocprofv3 FETCH_SIZE / WRITE_SIZE); it is excluded from every figure")
+                    help="also run one 1 GiB streaming read and one 1 GiB fill per step (known traffic, "
+                         "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE); excluded from every figure")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported")
@@ -261,9 +261,13 @@ def main():
     stream = torch.cuda.current_stream()
     calib = None
     if args.calib_copy:
+        # known traffic: a 1 GiB streaming read (library probe) and a 1 GiB fill
         ca = torch.zeros(1 << 28, dtype=torch.float32, device="cuda:0")
-        cb = torch.empty_like(ca)
-        calib = lambda: cb.copy_(ca)
+        sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
+
+        def calib():
+            spt.spt_probe_read(ca, 1 << 30, 16, sink)
+            ca.zero_()
 
     def step(record):
         # one event between consecutive calls: the end of call k is the start of call k+1
