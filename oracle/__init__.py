@@ -53,6 +53,8 @@ def lib():
         L.orc_to_coo.argtypes = [vp, vp, vp]
         L.orc_spmv.restype = None
         L.orc_spmv.argtypes = [vp, vp, i64, vp, vp]
+        L.orc_spmv_sparse_x.restype = None
+        L.orc_spmv_sparse_x.argtypes = [vp, vp, i64, vp, vp]
         L.orc_coo_to_csr.restype = None
         L.orc_coo_to_csr.argtypes = [i64, i64, vp, vp, vp, i32, i32, vp, vp, vp, vp]
         L.orc_ttv.restype = i64
@@ -177,6 +179,18 @@ def spmv(spec, x):
     y = np.zeros(rows, np.float64)
     mag = np.zeros(rows, np.float64)
     lib().orc_spmv(T.ref, _ptr(x), rows, _ptr(y), _ptr(mag))
+    return y, mag
+
+
+def spmv_sparse_x(spec, xspec):
+    """Reference y = A x with x a 1st-order tensor (sparse vector or hash map)."""
+    T, X = OTensor(spec), OTensor(xspec)
+    if spec.vals.dtype != xspec.vals.dtype:
+        raise TypeError("x must have the dtype of A")
+    rows = spec.dims[0]
+    y = np.zeros(rows, np.float64)
+    mag = np.zeros(rows, np.float64)
+    lib().orc_spmv_sparse_x(T.ref, X.ref, rows, _ptr(y), _ptr(mag))
     return y, mag
 
 

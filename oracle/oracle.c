@@ -239,6 +239,42 @@ void orc_spmv(const orc_tensor* T, const void* x, int64_t rows, double* y,
   free(acc);
 }
 
+typedef struct {
+  const orc_tensor* T;
+  const orc_tensor* X;
+  long double* acc;
+  double* mag;
+} spmv_sx_ctx;
+static void spmv_sx_visit(void* vctx, const int64_t* c, int64_t p) {
+  spmv_sx_ctx* S = (spmv_sx_ctx*)vctx;
+  const orc_level* L = &S->X->lvl[0];
+  int64_t j = c[1], q = -1;
+  if (L->kind == ORC_HASHED) {
+    int32_t found = 0;
+    q = orc_hashed_locate(L, 0, j, &found);
+    if (!found) q = -1;
+  } else { /* compressed: scan the parent's segment for coordinate j */
+    for (int64_t r = L->pos[0]; r < L->pos[1]; ++r)
+      if (L->crd[r] == j) {
+        q = r;
+        break;
+      }
+  }
+  if (q < 0) return;
+  long double t = (long double)val_at(S->T, p) * (long double)val_at(S->X, q);
+  S->acc[c[0]] += t;
+  S->mag[c[0]] += fabs((double)t);
+}
+void orc_spmv_sparse_x(const orc_tensor* T, const orc_tensor* X, int64_t rows, double* y,
+                       double* mag) {
+  long double* acc = (long double*)calloc((size_t)(rows > 0 ? rows : 1), sizeof(long double));
+  for (int64_t i = 0; i < rows; ++i) mag[i] = 0.0;
+  spmv_sx_ctx S = {T, X, acc, mag};
+  orc_enumerate(T, spmv_sx_visit, &S);
+  for (int64_t i = 0; i < rows; ++i) y[i] = (double)acc[i];
+  free(acc);
+}
+
 /* Stable bottom-up merge sort of an index permutation by one or two int32 keys. */
 static int key_less(const int32_t* k0, const int32_t* k1, int64_t a, int64_t b) {
   if (k0[a] != k0[b]) return k0[a] < k0[b];

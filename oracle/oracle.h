@@ -67,6 +67,14 @@ void orc_to_coo(const orc_tensor* T, int64_t* coords_out, double* vals_out);
 void orc_spmv(const orc_tensor* T, const void* x, int64_t rows, double* y,
               double* mag);
 
+/* y = A x with x stored as a 1st-order tensor X (Section 5.4, Figure 16):
+ * one compressed level (sparse vector) or one hashed level (hash map). Every
+ * stored (i,j) of A looks x_j up in X: by the hashed level's locate function
+ * (Table 2), or, for the compressed level, in the list of X's stored
+ * coordinates (absent = 0). */
+void orc_spmv_sparse_x(const orc_tensor* T, const orc_tensor* X, int64_t rows, double* y,
+                       double* mag);
+
 /* COO -> CSR index assembly. order 0: by (row,col), ties keep input order;
  * order 1: by row, input order kept inside a row. pos via Table 3's
  * append_init / append_edges / append_finalize. perm_out[n] = input index of

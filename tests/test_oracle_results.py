@@ -283,3 +283,30 @@ def test_mttkrp_closed_forms():
     want = np.einsum("ikl,kj,lj->ij", _dense3(dims, ci, ck, cl, vi), Ci, Di)
     assert np.array_equal(oracle.mttkrp(si, Ci, Di)[0], want)
     assert np.array_equal(oracle.plain_mttkrp(si, Ci, Di, "coo"), want)
+
+
+# ------------------------------------------------------------------ SpMV with sparse / hashed x
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_spmv_sparse_and_hashed_x_vs_dense_expansion(dtype):
+    N, M = 41, 67
+    r, c, v = wl.random_coo_entries(N, M, 500, seed=61, dtype=dtype)
+    A = wl.csr_from_sorted_coo(N, M, r, c, v)
+    xc, xv = wl.random_sparse_vector(M, 20, seed=62, dtype=dtype)
+    xd = np.zeros(M, np.float64)
+    xd[xc] = xv                                   # independent dense expansion of x
+    want = _dense(N, M, r, c, v) @ xd
+    for W in (20, 23, 64, 200):                   # full table, prime, power of two, sparse table
+        y, mag = oracle.spmv_sparse_x(A, wl.hash_vector_spec(M, xc, xv, W))
+        np.testing.assert_allclose(y, want, rtol=0, atol=1e-13 * max(mag.max(), 1))
+    y, mag = oracle.spmv_sparse_x(A, wl.sparse_vector_spec(M, xc, xv))
+    np.testing.assert_allclose(y, want, rtol=0, atol=1e-13 * max(mag.max(), 1))
+    # agrees with the dense-x definition on the expanded vector, magnitudes included
+    y2, mag2 = oracle.spmv(A, xd.astype(dtype))
+    np.testing.assert_allclose(y, y2, rtol=0, atol=1e-13 * max(mag.max(), 1))
+    np.testing.assert_allclose(mag, mag2, rtol=1e-12, atol=1e-300)
+    # empty x gives y = 0
+    y, _ = oracle.spmv_sparse_x(A, wl.sparse_vector_spec(M, [], np.zeros(0, dtype)))
+    assert not y.any()
+    y, _ = oracle.spmv_sparse_x(A, wl.hash_vector_spec(M, [], np.zeros(0, dtype), 7))
+    assert not y.any()

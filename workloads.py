@@ -124,6 +124,34 @@ def csf3_spec(dims, pos0, crd0, pos1, crd1, pos2, crd2, vals, name="csf3") -> Te
     ], np.ascontiguousarray(vals), name)
 
 
+def sparse_vector_spec(M, crd, vals, name="spvec") -> TensorSpec:
+    """Sparse vector = one compressed level with pos = [0, nnz], ordered and unique."""
+    return TensorSpec((M,), [LevelSpec(COMPRESSED, 0, M, M=1, pos=_i32([0, len(vals)]),
+                                       crd=_i32(crd))], np.ascontiguousarray(vals), name)
+
+
+def hash_vector_spec(M, crd, vals, W, name="hashvec") -> TensorSpec:
+    """Hash-map vector = one hashed level of width W: coordinate i is stored at the first
+    free slot at or after i % W (wrapping), empty slots hold -1 (Table 2 / Table 3)."""
+    vals = np.asarray(vals)
+    table = np.full(W, -1, np.int32)
+    tv = np.zeros(W, vals.dtype)
+    for i, v in zip(np.asarray(crd).tolist(), vals.tolist()):
+        p = i % W
+        while table[p] != -1:
+            p = (p + 1) % W
+        table[p] = i
+        tv[p] = v
+    return TensorSpec((M,), [LevelSpec(HASHED, 0, M, M=W, crd=table, ordered=False)], tv, name)
+
+
+def random_sparse_vector(M, nnz, seed, dtype=np.float64, dist="u11"):
+    """(sorted distinct coordinates, values) of a random sparse vector."""
+    rng = np.random.default_rng(seed)
+    crd = np.sort(rng.choice(M, size=min(nnz, M), replace=False))
+    return _i32(crd), _values(rng, len(crd), dtype, dist)
+
+
 def csr_from_sorted_coo(N, M, row, col, vals, name="csr") -> TensorSpec:
     """Lay a row-sorted entry list out as CSR (segment bounds from a sorted search)."""
     pos = np.searchsorted(np.asarray(row), np.arange(N + 1), side="left")
