@@ -65,7 +65,9 @@ def build_items(args):
     want = set(args.only.split(",")) if args.only else None
 
     def on(name):
-        return want is None or name in want or name.split("_")[0] in want
+        if want is None:
+            return name != "x16"          # the vector-format sweep runs only on request
+        return name in want or name.split("_")[0] in want
 
     # ---- config 2: banded, 7 diagonals, fp64: DIA and CSR
     if on("c2"):
@@ -160,6 +162,33 @@ def build_items(args):
         cpu_jobs.append(("c5_mttkrp_coo", lambda o, t=c5["coo"], C=c5["C"], D=c5["D"]: o.plain_mttkrp(t, C, D, "coo"),
                          3 * J * nnz))
         del c5
+    # ---- on request (--only x16): CSR SpMV on config 3's matrix with x as dense array,
+    #      sparse vector and hash map at three densities (the experiment of Figure 16)
+    if on("x16"):
+        c3 = wl.config3(N=max(64, int(1_000_000 * s)))
+        N, nnz = c3["csr"].dims[0], c3["nnz"]
+        A = spt.DeviceTensor(c3["csr"])
+        y = torch.empty(N, dtype=torch.float32, device=dev)
+        ws = A.workspace(spt.SPT_OP_SPMV)
+        keep.extend([A, y, ws])
+        for dens in (1e-4, 1e-2, 0.5):
+            nx = max(1, int(N * dens))
+            xc, xv = wl.random_sparse_vector(N, nx, seed=7, dtype=np.float32, dist="n01")
+            xd = np.zeros(N, np.float32)
+            xd[xc] = xv
+            xdense = up(xd)
+            W = 1 << int(np.ceil(np.log2(2 * nx + 1)))      # load factor <= 0.5
+            Xs = spt.DeviceTensor(wl.sparse_vector_spec(N, xc, xv))
+            Xh = spt.DeviceTensor(wl.hash_vector_spec(N, xc, xv, W))
+            keep.extend([Xs, Xh])
+            tag = f"x16_d{dens:g}"
+            items.append(Item(tag + "_dense", lambda xdense=xdense: spt.spt_spmv(A, xdense, y, ws),
+                              2 * nnz, 8 * nnz + 12 * N))
+            items.append(Item(tag + "_sparse", lambda Xs=Xs: spt.spt_spmv_sparse_x(A, Xs, y, ws),
+                              2 * nnz, 8 * nnz + 8 * N + 8 * nx))
+            items.append(Item(tag + "_hash", lambda Xh=Xh: spt.spt_spmv_sparse_x(A, Xh, y, ws),
+                              2 * nnz, 8 * nnz + 8 * N + 8 * W))
+        del c3
     return items, cpu_jobs, keep
 
 

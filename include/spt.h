@@ -138,6 +138,21 @@ spt_status spt_spmv(const spt_tensor* A, const void* x, void* y, void* ws,
                     size_t ws_bytes, void* stream);
 
 /*
+ * y = A x with A in CSR and x stored as a 1st-order tensor (Section 5.4, Figure
+ * 16: dense array vs sparse vector vs hash map as the format of x):
+ *   sparse vector  one compressed level, ordered and unique: pos = [0, nnz_x]
+ *                  (M = 1 parent), crd ascending, vals[nnz_x]
+ *   hash map       one hashed level of width W = level.M: crd[W] with -1 = empty
+ *                  bucket, vals[W]; coordinate i lives at the first matching slot
+ *                  at or after i % W, probing linearly with wrap (locate, Table 2)
+ * x.nvals = number of entries of x's vals (nnz_x or W); same dtype as A.
+ * Every stored entry of A locates its column in x; absent coordinates count as
+ * 0. y is overwritten. Workspace as for spt_spmv on A.
+ */
+spt_status spt_spmv_sparse_x(const spt_tensor* A, const spt_tensor* x, void* y, void* ws,
+                             size_t ws_bytes, void* stream);
+
+/*
  * COO -> CSR (the conversion of Section 5.4 / Figure 14; pos is assembled as
  * Table 3's append_edges + append_finalize: per-row counts, then prefix sum).
  * pos_out[N+1], crd_out[nnz], vals_out[nnz]. If both COO levels are flagged

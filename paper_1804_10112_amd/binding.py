@@ -23,7 +23,8 @@ SPT_ORDERED, SPT_UNIQUE = 1, 2
 SPT_F32, SPT_F64 = 0, 1
 
 SYMBOLS = ["spt_spmv", "spt_coo_to_csr", "spt_ttv", "spt_mttkrp", "spt_workspace_bytes",
-           "spt_last_error", "spt_version", "spt_probe_read", "spt_probe_gather"]
+           "spt_last_error", "spt_version", "spt_probe_read", "spt_probe_gather",
+           "spt_spmv_sparse_x"]
 
 
 class SptLevel(C.Structure):
@@ -59,6 +60,8 @@ def lib():
         vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
         L.spt_spmv.restype = i32
         L.spt_spmv.argtypes = [vp, vp, vp, vp, sz, vp]
+        L.spt_spmv_sparse_x.restype = i32
+        L.spt_spmv_sparse_x.argtypes = [vp, vp, vp, vp, sz, vp]
         L.spt_coo_to_csr.restype = i32
         L.spt_coo_to_csr.argtypes = [vp, i32, vp, vp, vp, vp, sz, vp]
         L.spt_ttv.restype = i32
@@ -131,6 +134,11 @@ def spt_workspace_bytes(op, T, J=0) -> int:
 def spt_spmv(A, x, y, ws=None, stream=None):
     p, n = _ws(ws)
     _check(lib().spt_spmv(_desc(A), _p(x), _p(y), p, n, _stream(stream)))
+
+
+def spt_spmv_sparse_x(A, x, y, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(lib().spt_spmv_sparse_x(_desc(A), _desc(x), _p(y), p, n, _stream(stream)))
 
 
 def spt_coo_to_csr(A, order, pos_out, crd_out, vals_out, ws=None, stream=None):

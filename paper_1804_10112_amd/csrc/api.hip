@@ -23,6 +23,8 @@ spt_status fail(spt_status code, const char* fmt, ...) {
 spt_status spmv_dispatch(Format f, const spt_tensor* A, const void* x, void* y, void* ws,
                          size_t ws_bytes, hipStream_t s);
 size_t seg_spmv_workspace(int64_t nnz);
+spt_status spmv_sparse_x_dispatch(const spt_tensor* A, const spt_tensor* X, void* y, void* ws,
+                                  size_t ws_bytes, hipStream_t s);
 size_t coo_unordered_workspace(int dtype, int64_t nnz, int64_t nrows);
 spt_status coo_to_csr_dispatch(const spt_tensor* A, int32_t order, int32_t* pos_out,
                                int32_t* crd_out, void* vals_out, void* ws, size_t ws_bytes,
@@ -197,6 +199,36 @@ spt_status spt_spmv(const spt_tensor* A, const void* x, void* y, void* ws, size_
   if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
   if (!x || !y) return fail(SPT_ERR_INVALID_ARG, "spmv: x or y is null");
   return spmv_dispatch(f, A, x, y, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+spt_status spt_spmv_sparse_x(const spt_tensor* A, const spt_tensor* x, void* y, void* ws,
+                             size_t ws_bytes, void* stream) {
+  clear_error();
+  Format f = recognize(A);
+  if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
+  if (f != Format::CSR) return fail(SPT_ERR_UNSUPPORTED, "spmv_sparse_x: A must be CSR");
+  if (!x || !y) return fail(SPT_ERR_INVALID_ARG, "spmv_sparse_x: x or y is null");
+  if (x->order != 1 || x->nlevels != 1)
+    return fail(SPT_ERR_INVALID_ARG, "spmv_sparse_x: x must be a 1st-order tensor of one level");
+  if (x->dtype != A->dtype) return fail(SPT_ERR_INVALID_ARG, "spmv_sparse_x: x and A differ in dtype");
+  if (x->nvals < 0 || (x->nvals > 0 && !x->vals))
+    return fail(SPT_ERR_INVALID_ARG, "spmv_sparse_x: x.vals is null or nvals negative");
+  const spt_level& L = x->level[0];
+  if (L.mode != 0) return fail(SPT_ERR_INVALID_ARG, "spmv_sparse_x: x's level must encode mode 0");
+  if (L.kind == SPT_HASHED) {
+    if (L.flags & SPT_ORDERED)
+      return fail(SPT_ERR_INVALID_ARG, "spmv_sparse_x: a hashed level cannot be ordered (Table 1)");
+    if (!L.crd || L.M < 1 || x->nvals != L.M)
+      return fail(SPT_ERR_INVALID_ARG, "spmv_sparse_x: hashed x needs crd and nvals = W >= 1");
+  } else if (L.kind == SPT_COMPRESSED) {
+    if (!(L.flags & SPT_ORDERED) || !(L.flags & SPT_UNIQUE))
+      return fail(SPT_ERR_UNSUPPORTED, "spmv_sparse_x: a sparse vector x must be ordered and unique");
+    if (L.M != 1 || !L.pos || (!L.crd && x->nvals > 0))
+      return fail(SPT_ERR_INVALID_ARG, "spmv_sparse_x: sparse vector x needs pos, crd and M = 1");
+  } else {
+    return fail(SPT_ERR_UNSUPPORTED, "spmv_sparse_x: x must be a compressed or a hashed level");
+  }
+  return spmv_sparse_x_dispatch(A, x, y, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 spt_status spt_coo_to_csr(const spt_tensor* A, int32_t order, int32_t* pos_out, int32_t* crd_out,

@@ -176,10 +176,51 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 template <int IPT>
 __device__ __forceinline__ int lds_slot(int e) { return e + e / IPT; }
 
-template <typename T, bool CSR, int IPT, bool VEC>
+// How an entry's column is turned into x_j ("locate" into the vector operand,
+// Section 3.2): a dense array, an ordered sparse vector (binary search of its
+// crd), or a hash-map vector (Table 2's probing: start at j % W, step +1 with
+// wrap, stop at j, at an empty bucket (-1) or after a full cycle).
+template <typename T>
+struct DenseX {
+  const T* __restrict__ x;
+  __device__ __forceinline__ T at(int32_t j) const { return x[j]; }
+};
+template <typename T>
+struct SparseX {
+  const int32_t* __restrict__ crd;
+  const T* __restrict__ vals;
+  int n;
+  __device__ __forceinline__ T at(int32_t j) const {
+    int lo = 0, hi = n;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (crd[mid] < j) lo = mid + 1;
+      else hi = mid;
+    }
+    return (lo < n && crd[lo] == j) ? vals[lo] : T(0);
+  }
+};
+template <typename T>
+struct HashX {
+  const int32_t* __restrict__ crd;
+  const T* __restrict__ vals;
+  int W;
+  __device__ __forceinline__ T at(int32_t j) const {
+    int p = j % W;
+    for (int step = 0; step < W; ++step) {
+      const int32_t c = crd[p];
+      if (c == j) return vals[p];
+      if (c == -1) break;
+      p = p + 1 == W ? 0 : p + 1;
+    }
+    return T(0);
+  }
+};
+
+template <typename T, bool CSR, int IPT, bool VEC, class XP = DenseX<T>>
 __global__ __launch_bounds__(kBlock) void seg_spmv_kernel(
     int nnz, int nrows, const int32_t* __restrict__ pos_or_row, const int32_t* __restrict__ col,
-    const T* __restrict__ vals, const T* __restrict__ x, T* __restrict__ y,
+    const T* __restrict__ vals, const XP x, T* __restrict__ y,
     int32_t* __restrict__ carry_key, T* __restrict__ carry_val) {
   constexpr int CHUNK = IPT * kBlock;
   __shared__ T s_val[CHUNK + kBlock];
@@ -240,7 +281,7 @@ __global__ __launch_bounds__(kBlock) void seg_spmv_kernel(
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      s_val[lds_slot<IPT>(e0 + r)] = ok[r] ? v[r] * x[c[r]] : T(0);
+      s_val[lds_slot<IPT>(e0 + r)] = ok[r] ? v[r] * x.at(c[r]) : T(0);
       s_key[lds_slot<IPT>(e0 + r)] = key[r];
     }
   }
@@ -356,10 +397,10 @@ static spt_status launch_fill(T* out, int64_t n, T v, hipStream_t s) {
   return SPT_OK;
 }
 
-template <typename T, bool CSR>
-static spt_status launch_seg(int64_t nnz, int64_t nrows, const int32_t* pos_or_row,
-                             const int32_t* col, const T* vals, const T* x, T* y, void* ws,
-                             size_t ws_bytes, hipStream_t s) {
+template <typename T, bool CSR, class XP>
+static spt_status launch_seg_x(int64_t nnz, int64_t nrows, const int32_t* pos_or_row,
+                               const int32_t* col, const T* vals, const XP x, T* y, void* ws,
+                               size_t ws_bytes, hipStream_t s) {
   constexpr int CHUNK = kSegIPT * kBlock;
   if (nnz == 0) return launch_fill<T>(y, nrows, T(0), s);
   if (nnz + CHUNK >= INT32_MAX || nrows + 1 >= INT32_MAX)
@@ -377,16 +418,49 @@ static spt_status launch_seg(int64_t nnz, int64_t nrows, const int32_t* pos_or_r
   }
   const bool vec = aligned16(col) && aligned16(vals) && (CSR || aligned16(pos_or_row));
   if (vec)
-    hipLaunchKernelGGL((seg_spmv_kernel<T, CSR, kSegIPT, true>), dim3(nwg), dim3(kBlock), 0, s,
+    hipLaunchKernelGGL((seg_spmv_kernel<T, CSR, kSegIPT, true, XP>), dim3(nwg), dim3(kBlock), 0, s,
                        (int)nnz, (int)nrows, pos_or_row, col, vals, x, y, ckey, cval);
   else
-    hipLaunchKernelGGL((seg_spmv_kernel<T, CSR, kSegIPT, false>), dim3(nwg), dim3(kBlock), 0, s,
+    hipLaunchKernelGGL((seg_spmv_kernel<T, CSR, kSegIPT, false, XP>), dim3(nwg), dim3(kBlock), 0, s,
                        (int)nnz, (int)nrows, pos_or_row, col, vals, x, y, ckey, cval);
   SPT_CHECK_LAUNCH("seg_spmv");
   hipLaunchKernelGGL(carry_fixup_kernel<T>, dim3((nwg + kBlock - 1) / kBlock), dim3(kBlock), 0, s,
                      nwg, ckey, cval, y);
   SPT_CHECK_LAUNCH("carry_fixup");
   return SPT_OK;
+}
+
+template <typename T, bool CSR>
+static spt_status launch_seg(int64_t nnz, int64_t nrows, const int32_t* pos_or_row,
+                             const int32_t* col, const T* vals, const T* x, T* y, void* ws,
+                             size_t ws_bytes, hipStream_t s) {
+  return launch_seg_x<T, CSR, DenseX<T>>(nnz, nrows, pos_or_row, col, vals, DenseX<T>{x}, y, ws,
+                                         ws_bytes, s);
+}
+
+// y = A x, A in CSR, x a sparse vector (compressed level) or a hash map (hashed level).
+template <typename T>
+static spt_status spmv_sparse_x_typed(const spt_tensor* A, const spt_tensor* X, T* y, void* ws,
+                                      size_t ws_bytes, hipStream_t s) {
+  const spt_level& L = X->level[0];
+  const T* xv = static_cast<const T*>(X->vals);
+  const int64_t nnz = A->nvals, N = A->level[0].N;
+  const T* vals = static_cast<const T*>(A->vals);
+  if (X->nvals >= INT32_MAX) return fail(SPT_ERR_UNSUPPORTED, "spmv: x too large");
+  if (L.kind == SPT_HASHED) {
+    if (L.M < 1) return fail(SPT_ERR_INVALID_ARG, "spmv: hashed x needs a table width W >= 1");
+    return launch_seg_x<T, true, HashX<T>>(nnz, N, A->level[1].pos, A->level[1].crd, vals,
+                                           HashX<T>{L.crd, xv, (int)L.M}, y, ws, ws_bytes, s);
+  }
+  return launch_seg_x<T, true, SparseX<T>>(nnz, N, A->level[1].pos, A->level[1].crd, vals,
+                                           SparseX<T>{L.crd, xv, (int)X->nvals}, y, ws, ws_bytes, s);
+}
+
+spt_status spmv_sparse_x_dispatch(const spt_tensor* A, const spt_tensor* X, void* y, void* ws,
+                                  size_t ws_bytes, hipStream_t s) {
+  if (A->dtype == SPT_F64)
+    return spmv_sparse_x_typed<double>(A, X, static_cast<double*>(y), ws, ws_bytes, s);
+  return spmv_sparse_x_typed<float>(A, X, static_cast<float*>(y), ws, ws_bytes, s);
 }
 
 template <typename T>

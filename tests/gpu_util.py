@@ -81,3 +81,14 @@ def gpu_mttkrp(spec, Cm, Dm, misalign=False):
     spt.spt_mttkrp(B, Cd, Dd, J, A, ws)
     torch.cuda.synchronize()
     return A.cpu().numpy()
+
+
+def gpu_spmv_sparse_x(spec, xspec):
+    import torch
+    import paper_1804_10112_amd as spt
+    A = spt.DeviceTensor(spec)
+    X = spt.DeviceTensor(xspec)
+    y = torch.full((spec.dims[0],), float("nan"), dtype=A.torch_dtype, device="cuda")
+    spt.spt_spmv_sparse_x(A, X, y, A.workspace(spt.SPT_OP_SPMV))
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
