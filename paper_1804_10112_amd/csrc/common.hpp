@@ -65,9 +65,6 @@ __device__ __forceinline__ int xcd_contiguous_block_id() {
   return xcd * q + (xcd < rem ? xcd : rem) + slot;
 }
 
-// Accumulator used when partial sums of many workgroups are combined.
-template <typename T> struct Wide { using type = double; };
-
 // First index in sorted a[0..n) whose value is >= target, found by the whole
 // wave: every step probes 64 evenly spaced entries, so a 4M-entry array needs
 // 4 dependent loads instead of 22. All lanes return the same result.

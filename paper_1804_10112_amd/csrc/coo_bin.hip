@@ -9,7 +9,7 @@
 //      (row, v*x[col]) into 256 row-range bins (histogram, scan, stable scatter);
 //      the gather of x happens here, once per entry.
 //   2. accumulate: a workgroup owns a slice of one bin's entries and a sub-range
-//      of the bin's rows that fits LDS, adds the products with LDS atomics and
+//      of the bin's rows that fits LDS (128 KB: usually the whole bin), adds the products with LDS atomics and
 //      writes its rows: plain stores when it holds the whole bin, otherwise
 //      atomics onto the zero-filled y (one per touched row and slice).
 // Like the atomic kernel the result is order-dependent in the last bits
@@ -130,7 +130,9 @@ constexpr int kBinSlice = 1 << 18;
 
 template <typename T>
 struct BinRows {
-  static constexpr int value = 32768 / sizeof(T);  // 32 KB of LDS
+  // 128 KB of the CU's 160 KB LDS: with 256 bins every matrix of up to 2^22 (fp64) or 2^23
+  // (fp32) rows has a single sub-range, so each binned entry is read exactly once
+  static constexpr int value = 131072 / sizeof(T);
 };
 
 constexpr int kAccBlock = 1024;  // one workgroup streams a whole slice: it needs many loads in flight

@@ -589,7 +589,7 @@ static spt_status mttkrp_launch(Format f, const spt_tensor* B, const T* Cm, cons
   const int CHUNK2 = mttkrp_chunk(J, MT_LEVEL2);
   const int64_t I = B->level[0].N;
   const int64_t nnz64 = B->nvals;
-  if (nnz64 + CHUNK >= INT32_MAX || I * J >= ((int64_t)1 << 40))
+  if (nnz64 + CHUNK >= INT32_MAX || I * J >= ((int64_t)1 << 38))
     return fail(SPT_ERR_UNSUPPORTED, "mttkrp: tensor too large");
   if (I * J > 0) {
     hipLaunchKernelGGL(fill_t_kernel<T>, dim3((unsigned)((I * J + kBlock - 1) / kBlock)),

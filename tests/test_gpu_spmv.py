@@ -95,6 +95,22 @@ def test_power_law_rows_scaled_config4():
     assert np.bincount(r).max() > 2 * CHUNK      # a row really spans several chunks
 
 
+@pytest.mark.parametrize("dtype,N", [(np.float64, 6_000_000), (np.float32, 20_000_000)])
+def test_unordered_coo_with_more_rows_than_one_lds_window(dtype, N):
+    """Row count so large that a bin's rows need several LDS sub-ranges, and a row so long
+    that its bin is cut into several slices (slices combine with atomics)."""
+    rng = np.random.default_rng(4)
+    n = 700_000
+    row = rng.integers(0, N, n)
+    row[: n // 2] = N - 7                       # one heavy row: > 262144 entries in one bin
+    col = rng.integers(0, 1000, n)
+    v = rng.uniform(-1, 1, n).astype(dtype)
+    p = rng.permutation(n)
+    spec = wl.coo_spec(N, 1000, row[p], col[p], v[p], ordered=False)
+    x = wl.dense_vector(1000, 5, dtype)
+    _check(spec, x, f"unordered coo N={N}")
+
+
 def test_exact_integer_data_is_bit_exact():
     N, M = 3000, 2000
     r, c, v = wl.random_coo_entries(N, M, 50_000, seed=9, dtype=np.float32, dist="int")
