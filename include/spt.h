@@ -91,12 +91,18 @@ typedef enum {
  *          position is skipped, as the hashed level skips -1.
  *   offset range/offset: int32 offsets indexed by the coordinate of the
  *          enclosing diagonal level (DIA passes the same array to both)
+ *   max_children  optional hint for a compressed level: an upper bound on the
+ *          number of children of any one parent (CSR: the longest row), 0 =
+ *          unknown. Like the level properties of Section 3.3 it is a declared
+ *          invariant that only selects a faster loop: with a bound <= 16 CSR
+ *          SpMV runs one row per group of lanes instead of the entry-balanced
+ *          kernel. A bound that the data violates gives wrong results.
  */
 typedef struct {
   int32_t kind;
   int32_t mode;
   int32_t flags;
-  int32_t reserved;
+  int32_t max_children;
   int64_t N;
   int64_t M;
   const int32_t* pos;

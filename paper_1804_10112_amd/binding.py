@@ -29,7 +29,7 @@ SYMBOLS = ["spt_spmv", "spt_coo_to_csr", "spt_ttv", "spt_mttkrp", "spt_workspace
 
 class SptLevel(C.Structure):
     _fields_ = [("kind", C.c_int32), ("mode", C.c_int32), ("flags", C.c_int32),
-                ("reserved", C.c_int32), ("N", C.c_int64), ("M", C.c_int64),
+                ("max_children", C.c_int32), ("N", C.c_int64), ("M", C.c_int64),
                 ("pos", C.c_void_p), ("crd", C.c_void_p), ("offset", C.c_void_p)]
 
 
@@ -191,6 +191,7 @@ class DeviceTensor:
             o = t.level[k]
             o.kind, o.mode, o.N, o.M = int(lv.kind), int(lv.mode), int(lv.N), int(lv.M)
             o.flags = (SPT_ORDERED if lv.ordered else 0) | (SPT_UNIQUE if lv.unique else 0)
+            o.max_children = int(getattr(lv, "max_children", 0))
             for name in ("pos", "crd", "offset"):
                 a = getattr(lv, name)
                 if a is None:

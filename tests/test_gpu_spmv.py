@@ -157,6 +157,24 @@ def test_ell_scaled_config3_with_poisoned_padding(dtype, N):
     _check(z["ell"], z["x"], "ell all padding")
 
 
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("lo,hi", [(0, 3), (1, 7), (0, 12), (9, 16), (8, 32)])
+def test_csr_short_row_hint_selects_the_row_group_kernel(dtype, lo, hi):
+    """max_children <= 16 on the column level: one row per lane group (4/8/16 lanes by mean
+    length); larger bounds and no hint run the entry-balanced kernel; all match the oracle."""
+    c3 = wl.config3(N=5003, lo=lo, hi=hi, dtype=dtype)
+    hinted = c3["csr"]
+    assert hinted.levels[1].max_children == c3["W"] <= 64
+    lv = hinted.levels[1]
+    plain = wl.csr_spec(5003, 5003, lv.pos, lv.crd, hinted.vals)
+    ref, mag = oracle.spmv(hinted, c3["x"])
+    a, b = gpu_spmv(hinted, c3["x"], repeat=2)
+    assert_close(a, ref, mag, dtype, f"row-group kernel rows {lo}..{hi}")
+    assert np.array_equal(a, b)
+    assert_close(gpu_spmv(plain, c3["x"]), ref, mag, dtype, f"entry-balanced kernel rows {lo}..{hi}")
+    assert_close(gpu_spmv(hinted, c3["x"], misalign=True), ref, mag, dtype, "row-group, unaligned")
+
+
 def test_unsupported_and_invalid_descriptors_report_errors():
     import paper_1804_10112_amd as spt
     import torch

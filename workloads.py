@@ -34,6 +34,7 @@ class LevelSpec:
     offset: Optional[np.ndarray] = None
     ordered: bool = True
     unique: bool = True
+    max_children: int = 0     # optional declared bound on children per parent (0 = unknown)
 
 
 @dataclass
@@ -71,12 +72,14 @@ def coo_spec(N, M, row, col, vals, ordered=True, name="coo") -> TensorSpec:
     ], np.ascontiguousarray(vals), name)
 
 
-def csr_spec(N, M, pos, crd, vals, ordered=True, unique=True, name="csr") -> TensorSpec:
-    """CSR = (dense rows, compressed cols)."""
+def csr_spec(N, M, pos, crd, vals, ordered=True, unique=True, name="csr",
+             max_row=0) -> TensorSpec:
+    """CSR = (dense rows, compressed cols). max_row: declared bound on the row length
+    when the construction guarantees one (0 = unknown)."""
     return TensorSpec((N, M), [
         LevelSpec(DENSE, 0, N),
         LevelSpec(COMPRESSED, 1, M, M=N, pos=_i32(pos), crd=_i32(crd),
-                  ordered=ordered, unique=unique),
+                  ordered=ordered, unique=unique, max_children=max_row),
     ], np.ascontiguousarray(vals), name)
 
 
@@ -290,7 +293,7 @@ def config2(N=2_000_000, seed=SEED_BASE + 2, poison=False, dtype=np.float64):
     pos = np.concatenate([[0], np.cumsum(vt.sum(axis=1))])
     x = dense_vector(N, seed + 1000, dtype, "u11")
     return {"dia": dia_spec(N, N, off, diag, name="c2-dia"),
-            "csr": csr_spec(N, N, pos, cols, vals, name="c2-csr"),
+            "csr": csr_spec(N, N, pos, cols, vals, name="c2-csr", max_row=K),
             "x": x, "nnz": int(pos[-1])}
 
 
@@ -329,7 +332,7 @@ def config3(N=1_000_000, lo=8, hi=32, seed=SEED_BASE + 3, dtype=np.float32):
     pos = np.concatenate([[0], np.cumsum(L)])
     return {"ell": ell_spec(N, M, np.ascontiguousarray(crd.T), np.ascontiguousarray(v.T),
                             name="c3-ell"),
-            "csr": csr_spec(N, M, pos, crd[live], v[live], name="c3-csr"),
+            "csr": csr_spec(N, M, pos, crd[live], v[live], name="c3-csr", max_row=W),
             "x": x, "nnz": int(pos[-1]), "W": W}
 
 
