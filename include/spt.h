@@ -192,6 +192,15 @@ spt_status spt_mttkrp(const spt_tensor* B, const void* C, const void* D,
                       int32_t J, void* A_out, void* ws, size_t ws_bytes,
                       void* stream);
 
+/*
+ * SpDM, A = B C (Section 5.2, Figure 11): B an ordered COO matrix (N x M), C dense
+ * M x J, A_out dense N x J, both row-major; A_out is OVERWRITTEN (rows of B
+ * without entries give zero rows). 1 <= J <= 1024. Workspace: query with
+ * SPT_OP_MTTKRP on B and the same J (the kernels are shared with spt_mttkrp).
+ */
+spt_status spt_spdm(const spt_tensor* B, const void* C, int32_t J, void* A_out, void* ws,
+                    size_t ws_bytes, void* stream);
+
 /* Workspace size in bytes for `op` on tensor T (J only for MTTKRP).
  * Returns 0 for invalid descriptors (spt_last_error says why). Never fails for
  * a valid one; the result is always >= 256. */

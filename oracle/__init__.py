@@ -55,6 +55,10 @@ def lib():
         L.orc_spmv.argtypes = [vp, vp, i64, vp, vp]
         L.orc_spmv_sparse_x.restype = None
         L.orc_spmv_sparse_x.argtypes = [vp, vp, i64, vp, vp]
+        L.orc_spdm.restype = None
+        L.orc_spdm.argtypes = [vp, vp, i32, i64, vp, vp]
+        L.orc_plain_spdm_coo.restype = None
+        L.orc_plain_spdm_coo.argtypes = [i64, i64, vp, vp, vp, vp, i32, vp, i32]
         L.orc_coo_to_csr.restype = None
         L.orc_coo_to_csr.argtypes = [i64, i64, vp, vp, vp, i32, i32, vp, vp, vp, vp]
         L.orc_ttv.restype = i64
@@ -192,6 +196,27 @@ def spmv_sparse_x(spec, xspec):
     mag = np.zeros(rows, np.float64)
     lib().orc_spmv_sparse_x(T.ref, X.ref, rows, _ptr(y), _ptr(mag))
     return y, mag
+
+
+def spdm(spec, Cm):
+    """Reference A = B C (float64) and the magnitude sums."""
+    T = OTensor(spec)
+    Cm = _same_dtype(spec, Cm)
+    J = Cm.shape[1]
+    rows = spec.dims[0]
+    A = np.zeros((rows, J), np.float64)
+    mag = np.zeros((rows, J), np.float64)
+    lib().orc_spdm(T.ref, _ptr(Cm), J, rows, _ptr(A), _ptr(mag))
+    return A, mag
+
+
+def plain_spdm(spec, Cm):
+    Cm = _same_dtype(spec, Cm)
+    lv = spec.levels
+    A = np.zeros((spec.dims[0], Cm.shape[1]), spec.vals.dtype)
+    lib().orc_plain_spdm_coo(len(spec.vals), spec.dims[0], _ptr(lv[0].crd), _ptr(lv[1].crd),
+                             _ptr(spec.vals), _ptr(Cm), Cm.shape[1], _ptr(A), _is_f64(spec.vals.dtype))
+    return A
 
 
 def coo_to_csr(nrows, row, col, vals, order=0):

@@ -275,6 +275,33 @@ void orc_spmv_sparse_x(const orc_tensor* T, const orc_tensor* X, int64_t rows, d
   free(acc);
 }
 
+typedef struct {
+  const orc_tensor* T;
+  const void* C;
+  int32_t J;
+  long double* acc;
+  double* mag;
+} spdm_ctx;
+static void spdm_visit(void* vctx, const int64_t* co, int64_t p) {
+  spdm_ctx* S = (spdm_ctx*)vctx;
+  long double v = (long double)val_at(S->T, p);
+  for (int32_t j = 0; j < S->J; ++j) {
+    long double t = v * (long double)dense_at(S->C, S->T->is_f64, co[1] * S->J + j);
+    S->acc[co[0] * S->J + j] += t;
+    S->mag[co[0] * S->J + j] += fabs((double)t);
+  }
+}
+void orc_spdm(const orc_tensor* B, const void* C, int32_t J, int64_t rows, double* A,
+              double* mag) {
+  int64_t n = rows * J;
+  long double* acc = (long double*)calloc((size_t)(n > 0 ? n : 1), sizeof(long double));
+  for (int64_t q = 0; q < n; ++q) mag[q] = 0.0;
+  spdm_ctx S = {B, C, J, acc, mag};
+  orc_enumerate(B, spdm_visit, &S);
+  for (int64_t q = 0; q < n; ++q) A[q] = (double)acc[q];
+  free(acc);
+}
+
 /* Stable bottom-up merge sort of an index permutation by one or two int32 keys. */
 static int key_less(const int32_t* k0, const int32_t* k1, int64_t a, int64_t b) {
   if (k0[a] != k0[b]) return k0[a] < k0[b];
@@ -577,4 +604,21 @@ void orc_plain_mttkrp_csf(int64_t dim0, const int32_t* pos0, const int32_t* crd0
                           const void* vals, const void* C, const void* D,
                           int32_t J, void* A, int32_t is_f64) {
   if (is_f64) PLAIN_MTTKRP_CSF(double) else PLAIN_MTTKRP_CSF(float)
+}
+
+#define PLAIN_SPDM_COO(TY)                                              \
+  {                                                                     \
+    const TY* v = (const TY*)vals;                                      \
+    const TY* Cv = (const TY*)C;                                        \
+    TY* Av = (TY*)A;                                                    \
+    for (int64_t q = 0; q < rows * J; ++q) Av[q] = 0;                   \
+    for (int64_t p = 0; p < nnz; ++p) {                                 \
+      const TY* cr = Cv + (int64_t)col[p] * J;                          \
+      TY* ar = Av + (int64_t)row[p] * J;                                \
+      for (int32_t j = 0; j < J; ++j) ar[j] += v[p] * cr[j];            \
+    }                                                                   \
+  }
+void orc_plain_spdm_coo(int64_t nnz, int64_t rows, const int32_t* row, const int32_t* col,
+                        const void* vals, const void* C, int32_t J, void* A, int32_t is_f64) {
+  if (is_f64) PLAIN_SPDM_COO(double) else PLAIN_SPDM_COO(float)
 }

@@ -75,6 +75,11 @@ void orc_spmv(const orc_tensor* T, const void* x, int64_t rows, double* y,
 void orc_spmv_sparse_x(const orc_tensor* T, const orc_tensor* X, int64_t rows, double* y,
                        double* mag);
 
+/* SpDM A = B C (Section 5.2, Figure 11): B any matrix format, C dense cols x J
+ * row-major in B's dtype; A, mag: rows x J. */
+void orc_spdm(const orc_tensor* B, const void* C, int32_t J, int64_t rows, double* A,
+              double* mag);
+
 /* COO -> CSR index assembly. order 0: by (row,col), ties keep input order;
  * order 1: by row, input order kept inside a row. pos via Table 3's
  * append_init / append_edges / append_finalize. perm_out[n] = input index of
@@ -118,6 +123,8 @@ void orc_plain_mttkrp_coo(int64_t nnz, int64_t dim0, const int32_t* ci,
                           const int32_t* ck, const int32_t* cl, const void* vals,
                           const void* C, const void* D, int32_t J, void* A,
                           int32_t is_f64);
+void orc_plain_spdm_coo(int64_t nnz, int64_t rows, const int32_t* row, const int32_t* col,
+                        const void* vals, const void* C, int32_t J, void* A, int32_t is_f64);
 void orc_plain_mttkrp_csf(int64_t dim0, const int32_t* pos0, const int32_t* crd0,
                           const int32_t* pos1, const int32_t* crd1,
                           const int32_t* pos2, const int32_t* crd2,

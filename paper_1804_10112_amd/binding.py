@@ -24,7 +24,7 @@ SPT_F32, SPT_F64 = 0, 1
 
 SYMBOLS = ["spt_spmv", "spt_coo_to_csr", "spt_ttv", "spt_mttkrp", "spt_workspace_bytes",
            "spt_last_error", "spt_version", "spt_probe_read", "spt_probe_gather",
-           "spt_spmv_sparse_x"]
+           "spt_spmv_sparse_x", "spt_spdm"]
 
 
 class SptLevel(C.Structure):
@@ -68,6 +68,8 @@ def lib():
         L.spt_ttv.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.spt_mttkrp.restype = i32
         L.spt_mttkrp.argtypes = [vp, vp, vp, i32, vp, vp, sz, vp]
+        L.spt_spdm.restype = i32
+        L.spt_spdm.argtypes = [vp, vp, i32, vp, vp, sz, vp]
         L.spt_workspace_bytes.restype = sz
         L.spt_workspace_bytes.argtypes = [i32, vp, i32]
         L.spt_last_error.restype = C.c_char_p
@@ -164,6 +166,11 @@ def spt_probe_read(src, nbytes, lane_bytes, sink, stream=None):
 
 def spt_probe_gather(idx, n, table, dtype, out, stream=None):
     _check(lib().spt_probe_gather(_p(idx), n, _p(table), dtype, _p(out), _stream(stream)))
+
+
+def spt_spdm(B, Cm, J, A_out, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(lib().spt_spdm(_desc(B), _p(Cm), J, _p(A_out), p, n, _stream(stream)))
 
 
 class DeviceTensor:

@@ -37,6 +37,8 @@ size_t ttv_workspace(Format f, const spt_tensor* B);
 spt_status mttkrp_dispatch(Format f, const spt_tensor* B, const void* C, const void* D, int32_t J,
                            void* A_out, void* ws, size_t ws_bytes, hipStream_t s);
 size_t mttkrp_workspace(Format f, const spt_tensor* B, int32_t J);
+spt_status spdm_dispatch(const spt_tensor* B, const void* C, int32_t J, void* A_out, void* ws,
+                         size_t ws_bytes, hipStream_t s);
 
 static bool is(const spt_level& L, int kind) { return L.kind == kind; }
 static bool unique(const spt_level& L) { return (L.flags & SPT_UNIQUE) != 0; }
@@ -269,6 +271,17 @@ spt_status spt_mttkrp(const spt_tensor* B, const void* C, const void* D, int32_t
   if (J < 1 || J > 1024) return fail(SPT_ERR_INVALID_ARG, "mttkrp: J = %d outside [1,1024]", J);
   if (!C || !D || !A_out) return fail(SPT_ERR_INVALID_ARG, "mttkrp: null operand");
   return mttkrp_dispatch(f, B, C, D, J, A_out, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+spt_status spt_spdm(const spt_tensor* B, const void* C, int32_t J, void* A_out, void* ws,
+                    size_t ws_bytes, void* stream) {
+  clear_error();
+  Format f = recognize(B);
+  if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
+  if (f != Format::COO2) return fail(SPT_ERR_UNSUPPORTED, "spdm: B must be a COO matrix");
+  if (J < 1 || J > 1024) return fail(SPT_ERR_INVALID_ARG, "spdm: J = %d outside [1,1024]", J);
+  if (!C || !A_out) return fail(SPT_ERR_INVALID_ARG, "spdm: null operand");
+  return spdm_dispatch(B, C, J, A_out, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 size_t spt_workspace_bytes(int32_t op, const spt_tensor* T, int32_t J) {

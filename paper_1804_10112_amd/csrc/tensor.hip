@@ -284,7 +284,7 @@ static spt_status ttv_coo_typed(const spt_tensor* B, const T* c, int32_t* out_i,
 //          form, Section 5.3 / CSF being the more efficient format).
 // entries walked by one group of lanes, per mode: the CSF pre-phase is amortised over a
 // longer walk; the carry level is small and wants parallelism instead
-enum { MT_COO = 0, MT_LEVEL2 = 1, MT_CSF = 2 };
+enum { MT_COO = 0, MT_LEVEL2 = 1, MT_CSF = 2, MT_SPDM = 3 };
 template <int MODE> struct Epg { static constexpr int value = MODE == 2 ? 256 : (MODE == 1 ? 32 : 128); };
 constexpr int kU = 8;  // entries whose factor rows are in flight together
 
@@ -405,7 +405,7 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
   // cur = slice coordinate of the entry just before this group's first entry
   // (-1: there is none; -2: unknown but different, the group starts on a head)
   if (g0 < g1) {
-    if (MODE == MT_COO) cur = g0 > 0 ? ci[g0 - 1] : -1;
+    if (MODE == MT_COO || MODE == MT_SPDM) cur = g0 > 0 ? ci[g0 - 1] : -1;
     if (MODE == MT_LEVEL2) cur = g0 > 0 ? in_key[g0 - 1] : -1;
     if (MODE == MT_CSF) {
       if (g0 > chunk_base) cur = s_i[g0 - 1 - chunk_base];
@@ -418,10 +418,10 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
     int32_t ri = 0, rk = 0, rl = 0;
     T rv = 0;
     if (p_l < g1) {
-      if (MODE == MT_COO) {
+      if (MODE == MT_COO || MODE == MT_SPDM) {
         ri = ldg_stream(ci + p_l);
         rk = ldg_stream(ck + p_l);
-        rl = ldg_stream(cl + p_l);
+        if (MODE == MT_COO) rl = ldg_stream(cl + p_l);
         rv = ldg_stream(vals + p_l);
       } else if (MODE == MT_CSF) {
         ri = s_i[p_l - chunk_base];
@@ -455,8 +455,8 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
           const int k = __shfl(rk, sidx, G);
           const int l = __shfl(rl, sidx, G);
           vv[u] = __shfl(rv, sidx, G);
-          fb[u] = (live && jok) ? Dm[(int64_t)l * J + j] : T(0);
-          if (MODE == MT_COO) {
+          if (MODE != MT_SPDM) fb[u] = (live && jok) ? Dm[(int64_t)l * J + j] : T(0);
+          if (MODE == MT_COO || MODE == MT_SPDM) {
             fa[u] = (live && jok) ? Cm[(int64_t)k * J + j] : T(0);
           } else {  // CSF: C[k,:] only where a new (i,k) fiber piece starts
             fh[u] = live && (ii[u] != pi || k != pk);
@@ -492,6 +492,7 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
           }
           if (MODE == MT_CSF) t += vv[u] * fb[u];
           else if (MODE == MT_COO) acc += vv[u] * fa[u] * fb[u];
+          else if (MODE == MT_SPDM) acc += vv[u] * fa[u];
           else acc += fa[u];
         }
       }
@@ -610,7 +611,11 @@ static spt_status mttkrp_launch(Format f, const spt_tensor* B, const T* Cm, cons
   T* vec2 = W.take<T>((size_t)n2 * J);
   const unsigned jt = (unsigned)((J + G - 1) / G);
   const spt_level* L = B->level;
-  if (f == Format::COO3) {
+  if (f == Format::COO2) {  // SpDM: the same slice reduction with one dense factor
+    hipLaunchKernelGGL((mttkrp_kernel<T, G, MT_SPDM>), dim3(n1, jt), dim3(kBlock), 0, s, nnz, J,
+                       L[0].crd, L[1].crd, nullptr, static_cast<const T*>(B->vals), Cm, nullptr,
+                       nullptr, nullptr, nullptr, nullptr, 0, 0, nullptr, nullptr, A, key1, vec1);
+  } else if (f == Format::COO3) {
     hipLaunchKernelGGL((mttkrp_kernel<T, G, MT_COO>), dim3(n1, jt), dim3(kBlock), 0, s, nnz, J,
                        L[0].crd, L[1].crd, L[2].crd, static_cast<const T*>(B->vals), Cm, Dm, nullptr,
                        nullptr, nullptr, nullptr, 0, 0, nullptr, nullptr, A, key1, vec1);
@@ -643,6 +648,16 @@ static spt_status mttkrp_typed(Format f, const spt_tensor* B, const void* C, con
   if (mttkrp_group(J) == 32)
     return mttkrp_launch<T, 32>(f, B, Cm, Dm, J, static_cast<T*>(A), ws, ws_bytes, s);
   return mttkrp_launch<T, 64>(f, B, Cm, Dm, J, static_cast<T*>(A), ws, ws_bytes, s);
+}
+
+// SpDM A = B C (Section 5.2, Figure 11): B an ordered COO matrix, C and A dense row-major.
+spt_status spdm_dispatch(const spt_tensor* B, const void* C, int32_t J, void* A_out, void* ws,
+                         size_t ws_bytes, hipStream_t s) {
+  if (!(B->level[0].flags & SPT_ORDERED))
+    return fail(SPT_ERR_UNSUPPORTED, "spdm: the row level of B must be ordered");
+  if (B->dtype == SPT_F64)
+    return mttkrp_typed<double>(Format::COO2, B, C, nullptr, J, A_out, ws, ws_bytes, s);
+  return mttkrp_typed<float>(Format::COO2, B, C, nullptr, J, A_out, ws, ws_bytes, s);
 }
 
 spt_status mttkrp_dispatch(Format f, const spt_tensor* B, const void* C, const void* D, int32_t J,

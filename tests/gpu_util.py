@@ -92,3 +92,15 @@ def gpu_spmv_sparse_x(spec, xspec):
     spt.spt_spmv_sparse_x(A, X, y, A.workspace(spt.SPT_OP_SPMV))
     torch.cuda.synchronize()
     return y.cpu().numpy()
+
+
+def gpu_spdm(spec, Cm):
+    import torch
+    import paper_1804_10112_amd as spt
+    B = spt.DeviceTensor(spec)
+    Cd = torch.from_numpy(np.ascontiguousarray(Cm)).cuda()
+    J = Cm.shape[1]
+    A = torch.full((spec.dims[0], J), float("nan"), dtype=B.torch_dtype, device="cuda")
+    spt.spt_spdm(B, Cd, J, A, B.workspace(spt.SPT_OP_MTTKRP, J))
+    torch.cuda.synchronize()
+    return A.cpu().numpy()

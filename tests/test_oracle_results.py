@@ -310,3 +310,28 @@ def test_spmv_sparse_and_hashed_x_vs_dense_expansion(dtype):
     assert not y.any()
     y, _ = oracle.spmv_sparse_x(A, wl.hash_vector_spec(M, [], np.zeros(0, dtype), 7))
     assert not y.any()
+
+
+# ------------------------------------------------------------------ SpDM
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("J", [1, 5, 32])
+def test_spdm_vs_scipy_and_dense(dtype, J):
+    N, M = 29, 43
+    r, c, v = wl.random_coo_entries(N, M, 300, seed=81, dtype=dtype, duplicates=True)
+    Cm = np.random.default_rng(82).uniform(-1, 1, (M, J)).astype(dtype)
+    C64 = Cm.astype(np.float64)
+    want = _dense(N, M, r, c, v) @ C64
+    want_sp = sp.coo_matrix((v.astype(np.float64), (r, c)), shape=(N, M)).tocsr() @ C64
+    for spec in (wl.coo_spec(N, M, r, c, v), wl.csr_from_sorted_coo(N, M, r, c, v)):
+        A, mag = oracle.spdm(spec, Cm)
+        np.testing.assert_allclose(A, want, rtol=0, atol=1e-13 * max(mag.max(), 1))
+        np.testing.assert_allclose(A, want_sp, rtol=0, atol=1e-13 * max(mag.max(), 1))
+    tol = 1e-13 if dtype == np.float64 else 4e-6
+    P = oracle.plain_spdm(wl.coo_spec(N, M, r, c, v), Cm).astype(np.float64)
+    assert np.all(np.abs(P - A) <= tol * np.maximum(mag, 1e-30) + 1e-300)
+    # J = 1 is SpMV; C = I reproduces the dense matrix
+    y, _ = oracle.spmv(wl.coo_spec(N, M, r, c, v), Cm[:, 0].copy())
+    np.testing.assert_allclose(A[:, 0], y, rtol=0, atol=1e-15 * max(mag.max(), 1))
+    E, _ = oracle.spdm(wl.coo_spec(N, M, r, c, v), np.eye(M, dtype=dtype))
+    assert np.array_equal(E, _dense(N, M, r, c, v))
