@@ -59,6 +59,8 @@ def lib():
         L.orc_spdm.argtypes = [vp, vp, i32, i64, vp, vp]
         L.orc_plain_spdm_coo.restype = None
         L.orc_plain_spdm_coo.argtypes = [i64, i64, vp, vp, vp, vp, i32, vp, i32]
+        L.orc_innerprod.restype = C.c_double
+        L.orc_innerprod.argtypes = [vp, vp, vp, vp]
         L.orc_coo_to_csr.restype = None
         L.orc_coo_to_csr.argtypes = [i64, i64, vp, vp, vp, i32, i32, vp, vp, vp, vp]
         L.orc_ttv.restype = i64
@@ -217,6 +219,17 @@ def plain_spdm(spec, Cm):
     lib().orc_plain_spdm_coo(len(spec.vals), spec.dims[0], _ptr(lv[0].crd), _ptr(lv[1].crd),
                              _ptr(spec.vals), _ptr(Cm), Cm.shape[1], _ptr(A), _is_f64(spec.vals.dtype))
     return A
+
+
+def innerprod(bspec, cspec):
+    """Reference alpha = sum B_ijk C_ijk and the magnitude sum."""
+    if tuple(bspec.dims) != tuple(cspec.dims):
+        raise ValueError("operands differ in shape")
+    TB, TC = OTensor(bspec), OTensor(cspec)
+    dims = np.asarray(bspec.dims, np.int64)
+    mag = C.c_double(0.0)
+    a = lib().orc_innerprod(TB.ref, TC.ref, _ptr(dims), C.addressof(mag))
+    return float(a), float(mag.value)
 
 
 def coo_to_csr(nrows, row, col, vals, order=0):

@@ -302,6 +302,63 @@ void orc_spdm(const orc_tensor* B, const void* C, int32_t J, int64_t rows, doubl
   free(acc);
 }
 
+typedef struct {
+  int64_t key;
+  double val;
+} kv_pair;
+typedef struct {
+  const orc_tensor* T;
+  const int64_t* dims;
+  kv_pair* out;
+  int64_t n;
+} lin_ctx;
+static void lin_visit(void* vctx, const int64_t* co, int64_t p) {
+  lin_ctx* S = (lin_ctx*)vctx;
+  int64_t key = 0;
+  for (int m = 0; m < S->T->order; ++m) key = key * S->dims[m] + co[m];
+  S->out[S->n].key = key;
+  S->out[S->n].val = val_at(S->T, p);
+  ++S->n;
+}
+static int kv_cmp(const void* a, const void* b) {
+  int64_t x = ((const kv_pair*)a)->key, y = ((const kv_pair*)b)->key;
+  return x < y ? -1 : (x > y ? 1 : 0);
+}
+static kv_pair* linearise(const orc_tensor* T, const int64_t* dims, int64_t* n_out) {
+  int64_t n = orc_count(T);
+  kv_pair* a = (kv_pair*)malloc(sizeof(kv_pair) * (size_t)(n > 0 ? n : 1));
+  lin_ctx S = {T, dims, a, 0};
+  orc_enumerate(T, lin_visit, &S);
+  qsort(a, (size_t)n, sizeof(kv_pair), kv_cmp);
+  *n_out = n;
+  return a;
+}
+double orc_innerprod(const orc_tensor* B, const orc_tensor* C, const int64_t* dims, double* mag) {
+  long double space = 1.0L;
+  for (int m = 0; m < B->order; ++m) space *= (long double)dims[m];
+  *mag = 0.0;
+  if (B->order != C->order || space >= 9.0e18L) return NAN;
+  int64_t nb, nc;
+  kv_pair* b = linearise(B, dims, &nb);
+  kv_pair* c = linearise(C, dims, &nc);
+  long double acc = 0.0L;
+  int64_t pb = 0, pc = 0;
+  while (pb < nb && pc < nc) { /* two-way merge: advance the smaller coordinate */
+    if (b[pb].key < c[pc].key) ++pb;
+    else if (b[pb].key > c[pc].key) ++pc;
+    else {
+      long double t = (long double)b[pb].val * (long double)c[pc].val;
+      acc += t;
+      *mag += fabs((double)t);
+      ++pb;
+      ++pc;
+    }
+  }
+  free(b);
+  free(c);
+  return (double)acc;
+}
+
 /* Stable bottom-up merge sort of an index permutation by one or two int32 keys. */
 static int key_less(const int32_t* k0, const int32_t* k1, int64_t a, int64_t b) {
   if (k0[a] != k0[b]) return k0[a] < k0[b];

@@ -80,6 +80,13 @@ void orc_spmv_sparse_x(const orc_tensor* T, const orc_tensor* X, int64_t rows, d
 void orc_spdm(const orc_tensor* B, const void* C, int32_t J, int64_t rows, double* A,
               double* mag);
 
+/* INNERPROD alpha = sum_ijk B_ijk C_ijk (Section 5.3) of two tensors of equal order and
+ * dimensions dims[order], in any formats: both are walked, ordered by linearised coordinate,
+ * and co-iterated with the two-way merge of Section 4.4 (coordinates are assumed unique in
+ * each operand). Returns alpha; *mag receives sum |B C|. Returns NaN if the linearised
+ * coordinate would overflow 63 bits. */
+double orc_innerprod(const orc_tensor* B, const orc_tensor* C, const int64_t* dims, double* mag);
+
 /* COO -> CSR index assembly. order 0: by (row,col), ties keep input order;
  * order 1: by row, input order kept inside a row. pos via Table 3's
  * append_init / append_edges / append_finalize. perm_out[n] = input index of

@@ -335,3 +335,30 @@ def test_spdm_vs_scipy_and_dense(dtype, J):
     np.testing.assert_allclose(A[:, 0], y, rtol=0, atol=1e-15 * max(mag.max(), 1))
     E, _ = oracle.spdm(wl.coo_spec(N, M, r, c, v), np.eye(M, dtype=dtype))
     assert np.array_equal(E, _dense(N, M, r, c, v))
+
+
+# ------------------------------------------------------------------ INNERPROD
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_innerprod_vs_dense(dtype):
+    dims = (6, 5, 7)
+    bi, bj, bk, bv = wl.random_coo3_entries(dims, 90, seed=91, dtype=dtype, skew=1.5)
+    ci, cj, ck, cv = wl.random_coo3_entries(dims, 120, seed=92, dtype=dtype)
+    B, Cd = _dense3(dims, bi, bj, bk, bv), _dense3(dims, ci, cj, ck, cv)
+    want = float((B * Cd).sum())
+    assert 0 < np.count_nonzero(B * Cd) < min(len(bv), len(cv))     # a proper partial overlap
+    bcoo, ccoo = wl.coo3_spec(dims, bi, bj, bk, bv), wl.coo3_spec(dims, ci, cj, ck, cv)
+    ccsf = wl.csf3_from_sorted_coo(dims, ci, cj, ck, cv)
+    for c in (ccoo, ccsf):
+        a, mag = oracle.innerprod(bcoo, c)
+        assert abs(a - want) <= 1e-13 * max(mag, 1)
+        assert abs(mag - float(np.abs(B * Cd).sum())) <= 1e-12 * max(mag, 1)
+    assert oracle.innerprod(ccoo, bcoo)[0] == oracle.innerprod(bcoo, ccoo)[0]      # symmetric
+    sq, _ = oracle.innerprod(bcoo, bcoo)                                           # <B,B> = sum v^2
+    assert abs(sq - float((bv.astype(np.float64) ** 2).sum())) <= 1e-13 * sq
+    e = np.zeros(0, int)
+    assert oracle.innerprod(bcoo, wl.coo3_spec(dims, e, e, e, np.zeros(0, dtype)))[0] == 0.0
+    # disjoint supports
+    d1 = wl.coo3_spec((2, 2, 2), [0], [0], [0], np.ones(1, dtype))
+    d2 = wl.coo3_spec((2, 2, 2), [1], [1], [1], np.ones(1, dtype))
+    assert oracle.innerprod(d1, d2) == (0.0, 0.0)
