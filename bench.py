@@ -66,7 +66,7 @@ def build_items(args):
 
     def on(name):
         if want is None:
-            return name != "x16"          # the vector-format sweep runs only on request
+            return name not in ("x16", "n2")   # these groups run only on request
         return name in want or name.split("_")[0] in want
 
     # ---- config 2: banded, 7 diagonals, fp64: DIA and CSR
@@ -189,6 +189,27 @@ def build_items(args):
             items.append(Item(tag + "_hash", lambda Xh=Xh: spt.spt_spmv_sparse_x(A, Xh, y, ws),
                               2 * nnz, 8 * nnz + 8 * N + 8 * W))
         del c3
+    # ---- on request (--only n2): INNERPROD (Section 5.3) on config 5's tensor, with itself
+    #      and with a tensor holding every third of its coordinates
+    if on("n2"):
+        dims = tuple(max(16, int(d * s)) for d in (100_000, 80_000, 50_000))
+        c5 = wl.config5(dims=dims, nnz=max(1000, int(50_000_000 * s)))
+        b = c5["coo"]
+        nnz = c5["nnz"]
+        i, j, k = (np.asarray(L.crd) for L in b.levels)
+        sel = np.arange(0, nnz, 3)
+        third = wl.coo3_spec(dims, i[sel], j[sel], k[sel], b.vals[sel])
+        Bc, Bt = spt.DeviceTensor(b), spt.DeviceTensor(third)
+        alpha = torch.zeros(1, dtype=torch.float32, device=dev)
+        w1, w2 = Bc.workspace(spt.SPT_OP_INNERPROD), Bt.workspace(spt.SPT_OP_INNERPROD)
+        keep.extend([Bc, Bt, alpha, w1, w2])
+        items.append(Item("n2_innerprod_self", lambda: spt.spt_innerprod(Bc, Bc, alpha, w1),
+                          2 * nnz, 32 * nnz))
+        items.append(Item("n2_innerprod_third", lambda: spt.spt_innerprod(Bc, Bt, alpha, w1),
+                          2 * len(sel), 16 * nnz + 16 * len(sel)))
+        items.append(Item("n2_innerprod_third_rev", lambda: spt.spt_innerprod(Bt, Bc, alpha, w2),
+                          2 * len(sel), 16 * nnz + 16 * len(sel)))
+        del c5
     return items, cpu_jobs, keep
 
 

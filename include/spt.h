@@ -69,7 +69,8 @@ typedef enum {
   SPT_OP_SPMV = 0,
   SPT_OP_COO_TO_CSR = 1,
   SPT_OP_TTV = 2,
-  SPT_OP_MTTKRP = 3
+  SPT_OP_MTTKRP = 3,
+  SPT_OP_INNERPROD = 4
 } spt_op;
 
 /*
@@ -200,6 +201,17 @@ spt_status spt_mttkrp(const spt_tensor* B, const void* C, const void* D,
  */
 spt_status spt_spdm(const spt_tensor* B, const void* C, int32_t J, void* A_out, void* ws,
                     size_t ws_bytes, void* stream);
+
+/*
+ * INNERPROD, alpha = sum_ijk B_ijk C_ijk (Section 5.3): B and C both COO3 (or both COO
+ * matrices: alpha = sum_ij B_ij C_ij) of equal dimensions and dtype, every level ordered
+ * and each coordinate stored at most once per operand. Only coordinates stored in both
+ * contribute (the intersection merge of Section 4.4). *alpha_out: one DEVICE scalar of the
+ * operands' dtype, overwritten (0 if either operand is empty). Products and sums are
+ * formed in double. Workspace: query with SPT_OP_INNERPROD on B.
+ */
+spt_status spt_innerprod(const spt_tensor* B, const spt_tensor* C, void* alpha_out, void* ws,
+                         size_t ws_bytes, void* stream);
 
 /* Workspace size in bytes for `op` on tensor T (J only for MTTKRP).
  * Returns 0 for invalid descriptors (spt_last_error says why). Never fails for

@@ -40,6 +40,10 @@ size_t mttkrp_workspace(Format f, const spt_tensor* B, int32_t J);
 spt_status spdm_dispatch(const spt_tensor* B, const void* C, int32_t J, void* A_out, void* ws,
                          size_t ws_bytes, hipStream_t s);
 
+spt_status innerprod_dispatch(Format f, const spt_tensor* B, const spt_tensor* C, void* out,
+                              void* ws, size_t ws_bytes, hipStream_t s);
+size_t innerprod_workspace(int64_t nb);
+
 static bool is(const spt_level& L, int kind) { return L.kind == kind; }
 static bool unique(const spt_level& L) { return (L.flags & SPT_UNIQUE) != 0; }
 
@@ -284,6 +288,27 @@ spt_status spt_spdm(const spt_tensor* B, const void* C, int32_t J, void* A_out, 
   return spdm_dispatch(B, C, J, A_out, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
+spt_status spt_innerprod(const spt_tensor* B, const spt_tensor* C, void* alpha_out, void* ws,
+                         size_t ws_bytes, void* stream) {
+  clear_error();
+  Format fb = recognize(B);
+  if (fb == Format::Invalid || fb == Format::Unsupported) return status_of(fb);
+  Format fc = recognize(C);
+  if (fc == Format::Invalid || fc == Format::Unsupported) return status_of(fc);
+  if (fb != fc || (fb != Format::COO3 && fb != Format::COO2))
+    return fail(SPT_ERR_UNSUPPORTED, "innerprod: B and C must both be COO3 or both COO matrices");
+  if (B->dtype != C->dtype) return fail(SPT_ERR_INVALID_ARG, "innerprod: B and C differ in dtype");
+  if (!alpha_out) return fail(SPT_ERR_INVALID_ARG, "innerprod: alpha_out is null");
+  for (int k = 0; k < B->nlevels; ++k) {
+    if (B->level[k].N != C->level[k].N)
+      return fail(SPT_ERR_INVALID_ARG, "innerprod: dimension %d differs (%lld vs %lld)", k,
+                  (long long)B->level[k].N, (long long)C->level[k].N);
+    if (!(B->level[k].flags & C->level[k].flags & SPT_ORDERED))
+      return fail(SPT_ERR_UNSUPPORTED, "innerprod: every level of B and C must be ordered");
+  }
+  return innerprod_dispatch(fb, B, C, alpha_out, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
 size_t spt_workspace_bytes(int32_t op, const spt_tensor* T, int32_t J) {
   clear_error();
   Format f = recognize(T);
@@ -304,6 +329,9 @@ size_t spt_workspace_bytes(int32_t op, const spt_tensor* T, int32_t J) {
       break;
     case SPT_OP_MTTKRP:
       n = mttkrp_workspace(f, T, J);
+      break;
+    case SPT_OP_INNERPROD:
+      n = (f == Format::COO3 || f == Format::COO2) ? innerprod_workspace(T->nvals) : 0;
       break;
     default:
       fail(SPT_ERR_INVALID_ARG, "unknown op %d", op);

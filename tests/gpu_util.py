@@ -104,3 +104,13 @@ def gpu_spdm(spec, Cm):
     spt.spt_spdm(B, Cd, J, A, B.workspace(spt.SPT_OP_MTTKRP, J))
     torch.cuda.synchronize()
     return A.cpu().numpy()
+
+
+def gpu_innerprod(bspec, cspec):
+    import torch
+    import paper_1804_10112_amd as spt
+    B, Ct = spt.DeviceTensor(bspec), spt.DeviceTensor(cspec)
+    out = torch.full((1,), float("nan"), dtype=B.torch_dtype, device="cuda")
+    spt.spt_innerprod(B, Ct, out, B.workspace(spt.SPT_OP_INNERPROD))
+    torch.cuda.synchronize()
+    return float(out.cpu().numpy()[0])
