@@ -59,6 +59,8 @@ def lib():
         L.orc_spdm.argtypes = [vp, vp, i32, i64, vp, vp]
         L.orc_plain_spdm_coo.restype = None
         L.orc_plain_spdm_coo.argtypes = [i64, i64, vp, vp, vp, vp, i32, vp, i32]
+        L.orc_ttm.restype = C.c_int64
+        L.orc_ttm.argtypes = [vp, vp, C.c_int32, C.c_int64, C.c_int64, vp, vp, vp, vp]
         L.orc_innerprod.restype = C.c_double
         L.orc_innerprod.argtypes = [vp, vp, vp, vp]
         L.orc_coo_to_csr.restype = None
@@ -255,6 +257,22 @@ def ttv(spec, c):
     ov = np.zeros(cap, np.float64)
     om = np.zeros(cap, np.float64)
     n = lib().orc_ttv(T.ref, _ptr(c), cap, _ptr(oi), _ptr(oj), _ptr(ov), _ptr(om))
+    return oi[:n], oj[:n], ov[:n], om[:n]
+
+
+def ttm(spec, Cm):
+    """Reference TTM: (fibre i, fibre j, values[nfib, K], magnitudes[nfib, K]); Cm is K x L."""
+    T = OTensor(spec)
+    Cm = _same_dtype(spec, Cm)
+    K, L = Cm.shape
+    if L != spec.dims[2]:
+        raise ValueError("C must be K x dims[2]")
+    cap = max(lib().orc_count(T.ref), 1)
+    oi = np.zeros(cap, np.int32)
+    oj = np.zeros(cap, np.int32)
+    ov = np.zeros((cap, K), np.float64)
+    om = np.zeros((cap, K), np.float64)
+    n = lib().orc_ttm(T.ref, _ptr(Cm), K, L, cap, _ptr(oi), _ptr(oj), _ptr(ov), _ptr(om))
     return oi[:n], oj[:n], ov[:n], om[:n]
 
 

@@ -471,6 +471,61 @@ int64_t orc_ttv(const orc_tensor* B, const void* c, int64_t cap, int32_t* out_i,
 }
 
 typedef struct {
+  int64_t n;
+  int32_t *ki, *kj, *kl;
+  int64_t* leaf;
+} ttm_ctx;
+static void ttm_visit(void* vctx, const int64_t* co, int64_t p) {
+  ttm_ctx* S = (ttm_ctx*)vctx;
+  S->ki[S->n] = (int32_t)co[0];
+  S->kj[S->n] = (int32_t)co[1];
+  S->kl[S->n] = (int32_t)co[2];
+  S->leaf[S->n] = p;
+  ++S->n;
+}
+int64_t orc_ttm(const orc_tensor* B, const void* C, int32_t K, int64_t L, int64_t cap,
+                int32_t* out_i, int32_t* out_j, double* out_v, double* out_mag) {
+  int64_t total = orc_count(B);
+  size_t a = (size_t)(total > 0 ? total : 1);
+  ttm_ctx S = {0, (int32_t*)malloc(4 * a), (int32_t*)malloc(4 * a), (int32_t*)malloc(4 * a),
+               (int64_t*)malloc(8 * a)};
+  orc_enumerate(B, ttm_visit, &S);
+  int64_t* perm = (int64_t*)malloc(sizeof(int64_t) * a);
+  for (int64_t n = 0; n < total; ++n) perm[n] = n;
+  stable_sort_perm(total, perm, S.ki, S.kj);
+  int f = B->is_f64;
+  int64_t nout = 0, n = 0;
+  while (n < total) {
+    int32_t i = S.ki[perm[n]], j = S.kj[perm[n]];
+    int64_t first = n;
+    while (n < total && S.ki[perm[n]] == i && S.kj[perm[n]] == j) ++n;
+    if (nout < cap) {
+      out_i[nout] = i;
+      out_j[nout] = j;
+      for (int32_t k = 0; k < K; ++k) { /* A_ijk = sum over the fibre's l of B_ijl C_kl */
+        long double sum = 0.0L;
+        double mag = 0.0;
+        for (int64_t q = first; q < n; ++q) {
+          long double t = (long double)val_at(B, S.leaf[perm[q]]) *
+                          (long double)dense_at(C, f, (int64_t)k * L + S.kl[perm[q]]);
+          sum += t;
+          mag += fabs((double)t);
+        }
+        out_v[nout * K + k] = (double)sum;
+        out_mag[nout * K + k] = mag;
+      }
+    }
+    ++nout;
+  }
+  free(perm);
+  free(S.ki);
+  free(S.kj);
+  free(S.kl);
+  free(S.leaf);
+  return nout;
+}
+
+typedef struct {
   const orc_tensor* T;
   const void *C, *D;
   int32_t J;

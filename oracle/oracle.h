@@ -96,6 +96,13 @@ void orc_coo_to_csr(int64_t nnz, int64_t nrows, const int32_t* row,
                     int32_t order, int32_t* pos_out, int32_t* crd_out,
                     void* vals_out, int64_t* perm_out);
 
+/* TTM A_ijk = sum_l B_ijl C_kl (Section 5.3), C dense K x L row-major. One output fibre per
+ * distinct (i,j) holding a stored entry, ascending (i,j); fibre f holds K values
+ * out_v[f*K .. f*K+K) (and magnitudes sum |B C|). Returns the fibre count; outputs have
+ * capacity cap fibres. */
+int64_t orc_ttm(const orc_tensor* B, const void* C, int32_t K, int64_t L, int64_t cap,
+                int32_t* out_i, int32_t* out_j, double* out_v, double* out_mag);
+
 /* TTV A_ij = sum_k B_ijk c_k (Section 5.3): one output entry per distinct
  * (i,j) holding a stored entry, ascending (i,j). Returns the entry count;
  * outputs have capacity cap (= number of leaves is always enough). */

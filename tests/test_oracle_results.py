@@ -362,3 +362,42 @@ def test_innerprod_vs_dense(dtype):
     d1 = wl.coo3_spec((2, 2, 2), [0], [0], [0], np.ones(1, dtype))
     d2 = wl.coo3_spec((2, 2, 2), [1], [1], [1], np.ones(1, dtype))
     assert oracle.innerprod(d1, d2) == (0.0, 0.0)
+
+
+# ------------------------------------------------------------------ TTM
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("K", [1, 3, 7])
+def test_ttm_vs_dense_einsum(dtype, K):
+    dims = (5, 4, 6)
+    ci, cj, cl, v = wl.random_coo3_entries(dims, 70, seed=61, dtype=dtype, skew=1.5)
+    Cm = np.random.default_rng(62 + K).uniform(-1, 1, (K, 6)).astype(dtype)     # C_kl: K x L, not square
+    B = _dense3(dims, ci, cj, cl, v)
+    want = np.einsum("ijl,kl->ijk", B, Cm.astype(np.float64))
+    fib = np.unique(ci.astype(np.int64) * 4 + cj)
+    for spec in (wl.coo3_spec(dims, ci, cj, cl, v), wl.csf3_from_sorted_coo(dims, ci, cj, cl, v)):
+        oi, oj, ov, om = oracle.ttm(spec, Cm)
+        assert np.array_equal(oi.astype(np.int64) * 4 + oj, fib)            # one fibre per stored (i,j), ascending
+        assert ov.shape == (len(fib), K)
+        np.testing.assert_allclose(ov, want[oi, oj, :], rtol=0, atol=1e-14 * max(om.max(), 1))
+        magwant = np.einsum("ijl,kl->ijk", np.abs(B), np.abs(Cm.astype(np.float64)))
+        np.testing.assert_allclose(om, magwant[oi, oj, :], rtol=1e-12)
+
+
+def test_ttm_closed_forms():
+    dims = (4, 3, 5)
+    ci, cj, cl, v = wl.random_coo3_entries(dims, 30, seed=63, dtype=np.float64)
+    B = _dense3(dims, ci, cj, cl, v)
+    spec = wl.coo3_spec(dims, ci, cj, cl, v)
+    oi, oj, ov, _ = oracle.ttm(spec, np.eye(5))                     # C = I: the fibres themselves
+    assert np.array_equal(ov, B[oi, oj, :])
+    c = wl.dense_vector(5, 64, np.float64, "u11")
+    ti, tj, tv, _ = oracle.ttv(spec, c)                             # K = 1 is TTV with c = C[0,:]
+    oi, oj, ov, _ = oracle.ttm(spec, c[None, :])
+    assert np.array_equal(oi, ti) and np.array_equal(oj, tj) and np.array_equal(ov[:, 0], tv)
+    sel = np.zeros((2, 5))
+    sel[0, 3] = 1.0
+    sel[1, 1] = 2.0
+    oi, oj, ov, _ = oracle.ttm(spec, sel)                           # rows of C pick slices l = 3 and 2 * (l = 1)
+    assert np.array_equal(ov[:, 0], B[oi, oj, 3]) and np.array_equal(ov[:, 1], 2 * B[oi, oj, 1])
+    assert len(oracle.ttm(wl.coo3_spec((2, 2, 2), [], [], [], np.zeros(0)), np.ones((3, 2)))[0]) == 0
