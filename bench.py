@@ -209,6 +209,22 @@ def build_items(args):
                           2 * len(sel), 16 * nnz + 16 * len(sel)))
         items.append(Item("n2_innerprod_third_rev", lambda: spt.spt_innerprod(Bt, Bc, alpha, w2),
                           2 * len(sel), 16 * nnz + 16 * len(sel)))
+        # TTM (Section 5.3) with K = 32 on the same tensor, COO and CSF
+        K = 32
+        Bf = spt.DeviceTensor(c5["csf"])
+        nfib = len(c5["csf"].levels[1].crd)
+        Ck = up(np.random.default_rng(9).uniform(0, 1, (K, dims[2])).astype(np.float32))
+        ti = torch.empty(nnz, dtype=torch.int32, device=dev)
+        tj = torch.empty(nnz, dtype=torch.int32, device=dev)
+        tv = torch.empty(nfib, K, dtype=torch.float32, device=dev)
+        tcnt = torch.zeros(1, dtype=torch.int64, device=dev)
+        w3, w4 = Bc.workspace(spt.SPT_OP_TTM, K), Bf.workspace(spt.SPT_OP_TTM, K)
+        keep.extend([Bf, ti, tj, tv, tcnt, w3, w4])
+        out_b = 4 * K * nfib
+        items.append(Item("n2_ttm_coo", lambda: spt.spt_ttm(Bc, Ck, K, ti, tj, tv, tcnt, w3),
+                          2 * K * nnz, 16 * nnz + 8 * nfib + out_b, "output fibres dominate the bytes"))
+        items.append(Item("n2_ttm_csf", lambda: spt.spt_ttm(Bf, Ck, K, None, None, tv, tcnt, w4),
+                          2 * K * nnz, 8 * nnz + 4 * nfib + out_b, "output fibres dominate the bytes"))
         del c5
     return items, cpu_jobs, keep
 

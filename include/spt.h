@@ -70,7 +70,8 @@ typedef enum {
   SPT_OP_COO_TO_CSR = 1,
   SPT_OP_TTV = 2,
   SPT_OP_MTTKRP = 3,
-  SPT_OP_INNERPROD = 4
+  SPT_OP_INNERPROD = 4,
+  SPT_OP_TTM = 5
 } spt_op;
 
 /*
@@ -203,6 +204,22 @@ spt_status spt_spdm(const spt_tensor* B, const void* C, int32_t J, void* A_out, 
                     size_t ws_bytes, void* stream);
 
 /*
+ * TTM, A_ijk = sum_l B_ijl C_kl (Section 5.3), contracting the dimension of B's last level
+ * with the dense matrix C: K x L row-major, L = that dimension, 1 <= K <= 1024. B: COO3 or
+ * CSF3, ordered. Every (i,j) fibre of B that holds a stored entry yields all K values, so the
+ * output stores its last dimension as a dense level: fibre f owns out_vals[f*K .. f*K+K).
+ *  COO3 input: fibres ascend in (i,j); out_crd0/out_crd1 (capacity nnz) receive their
+ *    coordinates, out_vals needs capacity nnz*K, *out_nfib_dev (device int64, required)
+ *    receives the number of fibres.
+ *  CSF3 input: the output shares B's two upper levels: one fibre per position of level 1
+ *    (B.level[2].M fibres); out_crd0/out_crd1 are ignored, out_nfib_dev may be NULL.
+ * Workspace: SPT_OP_TTM with J = K.
+ */
+spt_status spt_ttm(const spt_tensor* B, const void* C, int32_t K, int32_t* out_crd0,
+                   int32_t* out_crd1, void* out_vals, int64_t* out_nfib_dev, void* ws,
+                   size_t ws_bytes, void* stream);
+
+/*
  * INNERPROD, alpha = sum_ijk B_ijk C_ijk (Section 5.3): B and C both COO3 (or both COO
  * matrices: alpha = sum_ij B_ij C_ij) of equal dimensions and dtype, every level ordered
  * and each coordinate stored at most once per operand. Only coordinates stored in both
@@ -213,7 +230,7 @@ spt_status spt_spdm(const spt_tensor* B, const void* C, int32_t J, void* A_out, 
 spt_status spt_innerprod(const spt_tensor* B, const spt_tensor* C, void* alpha_out, void* ws,
                          size_t ws_bytes, void* stream);
 
-/* Workspace size in bytes for `op` on tensor T (J only for MTTKRP).
+/* Workspace size in bytes for `op` on tensor T (J only for MTTKRP and TTM).
  * Returns 0 for invalid descriptors (spt_last_error says why). Never fails for
  * a valid one; the result is always >= 256. */
 size_t spt_workspace_bytes(int32_t op, const spt_tensor* T, int32_t J);

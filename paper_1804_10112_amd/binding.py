@@ -17,14 +17,14 @@ _SO = os.path.join(_HERE, "libspt.so")
 _lib = None
 
 SPT_OK, SPT_ERR_INVALID_ARG, SPT_ERR_UNSUPPORTED, SPT_ERR_WORKSPACE, SPT_ERR_DEVICE = range(5)
-SPT_OP_SPMV, SPT_OP_COO_TO_CSR, SPT_OP_TTV, SPT_OP_MTTKRP, SPT_OP_INNERPROD = range(5)
+SPT_OP_SPMV, SPT_OP_COO_TO_CSR, SPT_OP_TTV, SPT_OP_MTTKRP, SPT_OP_INNERPROD, SPT_OP_TTM = range(6)
 SPT_ORDER_ROW_COL, SPT_ORDER_ROW_STABLE = 0, 1
 SPT_ORDERED, SPT_UNIQUE = 1, 2
 SPT_F32, SPT_F64 = 0, 1
 
 SYMBOLS = ["spt_spmv", "spt_coo_to_csr", "spt_ttv", "spt_mttkrp", "spt_workspace_bytes",
            "spt_last_error", "spt_version", "spt_probe_read", "spt_probe_gather",
-           "spt_spmv_sparse_x", "spt_spdm", "spt_innerprod"]
+           "spt_spmv_sparse_x", "spt_spdm", "spt_innerprod", "spt_ttm"]
 
 
 class SptLevel(C.Structure):
@@ -68,6 +68,8 @@ def lib():
         L.spt_ttv.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.spt_mttkrp.restype = i32
         L.spt_mttkrp.argtypes = [vp, vp, vp, i32, vp, vp, sz, vp]
+        L.spt_ttm.restype = i32
+        L.spt_ttm.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
         L.spt_innerprod.restype = i32
         L.spt_innerprod.argtypes = [vp, vp, vp, vp, sz, vp]
         L.spt_spdm.restype = i32
@@ -173,6 +175,12 @@ def spt_probe_gather(idx, n, table, dtype, out, stream=None):
 def spt_spdm(B, Cm, J, A_out, ws=None, stream=None):
     p, n = _ws(ws)
     _check(lib().spt_spdm(_desc(B), _p(Cm), J, _p(A_out), p, n, _stream(stream)))
+
+
+def spt_ttm(B, Cm, K, out_crd0, out_crd1, out_vals, out_nfib_dev, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(lib().spt_ttm(_desc(B), _p(Cm), K, _p(out_crd0), _p(out_crd1), _p(out_vals),
+                         _p(out_nfib_dev), p, n, _stream(stream)))
 
 
 def spt_innerprod(B, Ct, alpha_out, ws=None, stream=None):

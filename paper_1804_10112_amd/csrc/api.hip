@@ -40,6 +40,10 @@ size_t mttkrp_workspace(Format f, const spt_tensor* B, int32_t J);
 spt_status spdm_dispatch(const spt_tensor* B, const void* C, int32_t J, void* A_out, void* ws,
                          size_t ws_bytes, hipStream_t s);
 
+spt_status ttm_dispatch(Format f, const spt_tensor* B, const void* C, int32_t K, int32_t* out_crd0,
+                        int32_t* out_crd1, void* out_vals, int64_t* out_nfib_dev, void* ws,
+                        size_t ws_bytes, hipStream_t s);
+size_t ttm_workspace(Format f, const spt_tensor* B, int32_t K);
 spt_status innerprod_dispatch(Format f, const spt_tensor* B, const spt_tensor* C, void* out,
                               void* ws, size_t ws_bytes, hipStream_t s);
 size_t innerprod_workspace(int64_t nb);
@@ -288,6 +292,22 @@ spt_status spt_spdm(const spt_tensor* B, const void* C, int32_t J, void* A_out, 
   return spdm_dispatch(B, C, J, A_out, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
+spt_status spt_ttm(const spt_tensor* B, const void* C, int32_t K, int32_t* out_crd0,
+                   int32_t* out_crd1, void* out_vals, int64_t* out_nfib_dev, void* ws,
+                   size_t ws_bytes, void* stream) {
+  clear_error();
+  Format f = recognize(B);
+  if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
+  if (f != Format::COO3 && f != Format::CSF3)
+    return fail(SPT_ERR_UNSUPPORTED, "ttm: B must be COO3 or CSF3");
+  if (K < 1 || K > 1024) return fail(SPT_ERR_INVALID_ARG, "ttm: K = %d outside [1,1024]", K);
+  if (!C || !out_vals) return fail(SPT_ERR_INVALID_ARG, "ttm: null operand");
+  if (f == Format::COO3 && (!out_crd0 || !out_crd1 || !out_nfib_dev))
+    return fail(SPT_ERR_INVALID_ARG, "ttm: COO output needs out_crd0, out_crd1 and out_nfib_dev");
+  return ttm_dispatch(f, B, C, K, out_crd0, out_crd1, out_vals, out_nfib_dev, ws, ws_bytes,
+                      static_cast<hipStream_t>(stream));
+}
+
 spt_status spt_innerprod(const spt_tensor* B, const spt_tensor* C, void* alpha_out, void* ws,
                          size_t ws_bytes, void* stream) {
   clear_error();
@@ -329,6 +349,9 @@ size_t spt_workspace_bytes(int32_t op, const spt_tensor* T, int32_t J) {
       break;
     case SPT_OP_MTTKRP:
       n = mttkrp_workspace(f, T, J);
+      break;
+    case SPT_OP_TTM:
+      n = (f == Format::COO3 || f == Format::CSF3) ? ttm_workspace(f, T, J) : 0;
       break;
     case SPT_OP_INNERPROD:
       n = (f == Format::COO3 || f == Format::COO2) ? innerprod_workspace(T->nvals) : 0;

@@ -319,6 +319,13 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
   __shared__ int32_t s_k[MODE == MT_CSF ? CHUNK : 1];
   __shared__ int s_bounds[4];
   __shared__ int s_mark0;
+  // SpDM closes a row every few entries. A store issued between two batches of gathers
+  // makes the next batch wait for the store's acknowledgement (loads and stores retire
+  // through one counter), so closed rows are parked in LDS and written out in bursts.
+  constexpr int kRowBuf = 16;
+  __shared__ T s_rowv[MODE == MT_SPDM ? NG : 1][MODE == MT_SPDM ? kRowBuf : 1][G];
+  __shared__ int s_rowk[MODE == MT_SPDM ? NG : 1][MODE == MT_SPDM ? kRowBuf : 1];
+  int nbuf = 0;
 
   const int tid = threadIdx.x;
   const int g = tid / G, gl = tid % G;
@@ -483,9 +490,15 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
               lead = acc;
               has_head = 1;
               first_close = cur;
-            } else if (jok && cur >= 0) {
-              if (MODE == MT_LEVEL2) A[(int64_t)cur * J + j] += acc;
-              else A[(int64_t)cur * J + j] = acc;
+            } else if (cur >= 0) {
+              if (MODE == MT_SPDM) {
+                s_rowv[g][nbuf][gl] = acc;
+                if (gl == 0) s_rowk[g][nbuf] = cur;
+                ++nbuf;
+              } else if (jok) {
+                if (MODE == MT_LEVEL2) A[(int64_t)cur * J + j] += acc;
+                else A[(int64_t)cur * J + j] = acc;
+              }
             }
             acc = 0;
             cur = i;
@@ -496,7 +509,16 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
           else acc += fa[u];
         }
       }
+      if (MODE == MT_SPDM && nbuf > kRowBuf - kU) {
+        for (int r = 0; r < nbuf; ++r)
+          if (jok) __builtin_nontemporal_store(s_rowv[g][r][gl], &A[(int64_t)s_rowk[g][r] * J + j]);
+        nbuf = 0;
+      }
     }
+  }
+  if (MODE == MT_SPDM) {
+    for (int r = 0; r < nbuf; ++r)
+      if (jok) __builtin_nontemporal_store(s_rowv[g][r][gl], &A[(int64_t)s_rowk[g][r] * J + j]);
   }
   if (MODE == MT_CSF) acc += c_cur * t;
 
@@ -583,16 +605,21 @@ size_t mttkrp_workspace(Format, const spt_tensor* B, int32_t J) {
          align_up((size_t)n2 * 4, 256) + align_up((size_t)n2 * J * 8, 256) + 256;
 }
 
+// rows_override / cols_override (SpDM mode only): row and column index per stored entry taken
+// from these arrays instead of B's first two levels, and no zero fill of A (every output row
+// then has at least one entry, and rows with entries are stored, not accumulated).
 template <typename T, int G>
 static spt_status mttkrp_launch(Format f, const spt_tensor* B, const T* Cm, const T* Dm, int J,
-                                T* A, void* ws, size_t ws_bytes, hipStream_t s) {
+                                T* A, void* ws, size_t ws_bytes, hipStream_t s,
+                                const int32_t* rows_override = nullptr,
+                                const int32_t* cols_override = nullptr) {
   const int CHUNK = mttkrp_chunk(J, f == Format::CSF3 ? MT_CSF : MT_COO);
   const int CHUNK2 = mttkrp_chunk(J, MT_LEVEL2);
   const int64_t I = B->level[0].N;
   const int64_t nnz64 = B->nvals;
   if (nnz64 + CHUNK >= INT32_MAX || I * J >= ((int64_t)1 << 38))
     return fail(SPT_ERR_UNSUPPORTED, "mttkrp: tensor too large");
-  if (I * J > 0) {
+  if (I * J > 0 && !rows_override) {
     hipLaunchKernelGGL(fill_t_kernel<T>, dim3((unsigned)((I * J + kBlock - 1) / kBlock)),
                        dim3(kBlock), 0, s, A, I * J, T(0));
     SPT_CHECK_LAUNCH("mttkrp fill");
@@ -613,8 +640,10 @@ static spt_status mttkrp_launch(Format f, const spt_tensor* B, const T* Cm, cons
   const spt_level* L = B->level;
   if (f == Format::COO2) {  // SpDM: the same slice reduction with one dense factor
     hipLaunchKernelGGL((mttkrp_kernel<T, G, MT_SPDM>), dim3(n1, jt), dim3(kBlock), 0, s, nnz, J,
-                       L[0].crd, L[1].crd, nullptr, static_cast<const T*>(B->vals), Cm, nullptr,
-                       nullptr, nullptr, nullptr, nullptr, 0, 0, nullptr, nullptr, A, key1, vec1);
+                       rows_override ? rows_override : L[0].crd,
+                       cols_override ? cols_override : L[1].crd, nullptr,
+                       static_cast<const T*>(B->vals), Cm, nullptr, nullptr, nullptr, nullptr, nullptr,
+                       0, 0, nullptr, nullptr, A, key1, vec1);
   } else if (f == Format::COO3) {
     hipLaunchKernelGGL((mttkrp_kernel<T, G, MT_COO>), dim3(n1, jt), dim3(kBlock), 0, s, nnz, J,
                        L[0].crd, L[1].crd, L[2].crd, static_cast<const T*>(B->vals), Cm, Dm, nullptr,
@@ -642,12 +671,16 @@ static spt_status mttkrp_launch(Format f, const spt_tensor* B, const T* Cm, cons
 
 template <typename T>
 static spt_status mttkrp_typed(Format f, const spt_tensor* B, const void* C, const void* D, int J,
-                               void* A, void* ws, size_t ws_bytes, hipStream_t s) {
+                               void* A, void* ws, size_t ws_bytes, hipStream_t s,
+                               const int32_t* rows_override = nullptr,
+                               const int32_t* cols_override = nullptr) {
   const T* Cm = static_cast<const T*>(C);
   const T* Dm = static_cast<const T*>(D);
   if (mttkrp_group(J) == 32)
-    return mttkrp_launch<T, 32>(f, B, Cm, Dm, J, static_cast<T*>(A), ws, ws_bytes, s);
-  return mttkrp_launch<T, 64>(f, B, Cm, Dm, J, static_cast<T*>(A), ws, ws_bytes, s);
+    return mttkrp_launch<T, 32>(f, B, Cm, Dm, J, static_cast<T*>(A), ws, ws_bytes, s, rows_override,
+                                cols_override);
+  return mttkrp_launch<T, 64>(f, B, Cm, Dm, J, static_cast<T*>(A), ws, ws_bytes, s, rows_override,
+                              cols_override);
 }
 
 // SpDM A = B C (Section 5.2, Figure 11): B an ordered COO matrix, C and A dense row-major.
@@ -671,12 +704,194 @@ spt_status mttkrp_dispatch(Format f, const spt_tensor* B, const void* C, const v
 
 // ================================================================ TTV dispatch
 
-size_t ttv_workspace(Format f, const spt_tensor* B) {
-  return f == Format::COO3 ? ttv_coo_workspace(B->nvals) : seg_spmv_workspace(B->nvals);
-}
-
 __global__ void set_i64_kernel(int64_t* out, int64_t v) {
   if (threadIdx.x == 0 && blockIdx.x == 0) *out = v;
+}
+
+// ================================================================ TTM
+//
+// A_ijk = sum_l B_ijl C_kl (Section 5.3): every (i,j) fibre of B yields one dense fibre of K
+// values, A[f, :] = sum over the fibre's entries of B_ijl * C[:, l]. With the fibre index as
+// row and l as column this is the sparse-times-dense reduction of SpDM against C transposed,
+// so TTM = (fibre index per entry) + (C transposed into the workspace) + the SpDM kernels.
+
+// COO: fid[p] = index of the (i,j) fibre of entry p; the thread holding a fibre's first
+// entry appends its coordinates (append order = ascending (i,j)). Chunks as in ttv_count_kernel.
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void fiber_ids_kernel(int nnz, const int32_t* __restrict__ ci,
+                                                           const int32_t* __restrict__ cj,
+                                                           const int32_t* __restrict__ chunk_off,
+                                                           int32_t* __restrict__ fid,
+                                                           int32_t* __restrict__ out_i,
+                                                           int32_t* __restrict__ out_j) {
+  typedef int32_t i4 __attribute__((ext_vector_type(4)));
+  static_assert(kTtvIPT == 8, "two 16-byte loads per array and thread");
+  const int p0 = blockIdx.x * kTtvChunk + threadIdx.x * kTtvIPT;
+  int32_t li[kTtvIPT], lj[kTtvIPT];
+  int32_t qi = -1, qj = -1;
+  if (p0 > 0 && p0 < nnz) {
+    qi = ci[p0 - 1];
+    qj = cj[p0 - 1];
+  }
+  const bool full = VEC && p0 + kTtvIPT <= nnz;
+  if (full) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const i4 a = *reinterpret_cast<const i4*>(ci + p0 + 4 * h);
+      const i4 b = *reinterpret_cast<const i4*>(cj + p0 + 4 * h);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        li[4 * h + r] = a[r];
+        lj[4 * h + r] = b[r];
+      }
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < kTtvIPT; ++k) {
+      li[k] = p0 + k < nnz ? ci[p0 + k] : -1;
+      lj[k] = p0 + k < nnz ? cj[p0 + k] : -1;
+    }
+  }
+  unsigned headmask = 0;
+#pragma unroll
+  for (int k = 0; k < kTtvIPT; ++k) {
+    if (p0 + k < nnz && (li[k] != qi || lj[k] != qj)) headmask |= 1u << k;
+    qi = li[k];
+    qj = lj[k];
+  }
+  const int cnt = __popc(headmask);
+  int total;
+  int running = chunk_off[blockIdx.x] + block_inclusive_sum(cnt, &total) - cnt - 1;
+  int32_t lf[kTtvIPT];
+#pragma unroll
+  for (int k = 0; k < kTtvIPT; ++k) {
+    if (headmask & (1u << k)) {
+      ++running;
+      out_i[running] = li[k];
+      out_j[running] = lj[k];
+    }
+    lf[k] = running;
+  }
+  if (full) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      i4 v;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) v[r] = lf[4 * h + r];
+      *reinterpret_cast<i4*>(fid + p0 + 4 * h) = v;
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < kTtvIPT; ++k)
+      if (p0 + k < nnz) fid[p0 + k] = lf[k];
+  }
+}
+
+// CSF: the fibre of entry p is the position f of level 1 with pos2[f] <= p < pos2[f+1].
+__global__ __launch_bounds__(kBlock) void expand_fiber_ids_kernel(int nfib,
+                                                                  const int32_t* __restrict__ pos2,
+                                                                  int32_t* __restrict__ fid) {
+  const int f = blockIdx.x * kBlock + threadIdx.x;
+  if (f >= nfib) return;
+  const int a = pos2[f], b = pos2[f + 1];
+  for (int p = a; p < b; ++p) fid[p] = f;
+}
+
+// Ct[l * K + k] = C[k * L + l]
+template <typename T>
+__global__ __launch_bounds__(kBlock) void transpose_kernel(int K, int64_t L, const T* __restrict__ C,
+                                                           T* __restrict__ Ct) {
+  const int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (idx >= L * K) return;
+  const int64_t l = idx / K;
+  const int k = (int)(idx % K);
+  Ct[idx] = C[(int64_t)k * L + l];
+}
+
+size_t ttm_workspace(Format f, const spt_tensor* B, int32_t K) {
+  if (K < 1) K = 1;
+  const int64_t nnz = B->nvals, L = B->level[2].N;
+  size_t n = align_up((size_t)nnz * 4, 256) + align_up((size_t)L * K * 8, 256) +
+             mttkrp_workspace(Format::COO2, B, K);
+  if (f == Format::COO3) n += ttv_coo_workspace(nnz);
+  return n + 256;
+}
+
+template <typename T>
+static spt_status ttm_typed(Format f, const spt_tensor* B, const T* C, int K, int32_t* out_i,
+                            int32_t* out_j, T* out_v, int64_t* out_nfib, void* ws, size_t ws_bytes,
+                            hipStream_t s) {
+  const int64_t nnz64 = B->nvals, L = B->level[2].N;
+  if (nnz64 + kTtvChunk >= INT32_MAX) return fail(SPT_ERR_UNSUPPORTED, "ttm: more than 2^31 entries");
+  const int nnz = (int)nnz64;
+  if (nnz == 0) {
+    if (out_nfib) {
+      hipLaunchKernelGGL(set_i64_kernel, dim3(1), dim3(kWave), 0, s, out_nfib, (int64_t)0);
+      SPT_CHECK_LAUNCH("ttm set count");
+    }
+    return SPT_OK;
+  }
+  if (!ws || ws_bytes < ttm_workspace(f, B, K))
+    return fail(SPT_ERR_WORKSPACE, "ttm: workspace of %zu bytes needed, %zu given",
+                ttm_workspace(f, B, K), ws_bytes);
+  Workspace W(ws, ws_bytes);
+  int32_t* fid = W.take<int32_t>(nnz);
+  T* Ct = W.take<T>((size_t)L * K);
+  if (f == Format::COO3) {
+    const int nch = (nnz + kTtvChunk - 1) / kTtvChunk;
+    int32_t* heads = W.take<int32_t>(nch);
+    int32_t* off = W.take<int32_t>(nch);
+    int32_t* scan_tmp = reinterpret_cast<int32_t*>(W.take<char>(scan_workspace(nch)));
+    const int32_t *ci = B->level[0].crd, *cj = B->level[1].crd;
+    const bool vec = ((reinterpret_cast<uintptr_t>(ci) | reinterpret_cast<uintptr_t>(cj)) & 15) == 0;
+    if (vec) hipLaunchKernelGGL(ttv_count_kernel<true>, dim3(nch), dim3(kBlock), 0, s, nnz, ci, cj, heads);
+    else hipLaunchKernelGGL(ttv_count_kernel<false>, dim3(nch), dim3(kBlock), 0, s, nnz, ci, cj, heads);
+    SPT_CHECK_LAUNCH("ttm count");
+    spt_status st = device_scan_i32<false>(heads, off, nch, scan_tmp, s);
+    if (st != SPT_OK) return st;
+    hipLaunchKernelGGL(ttv_total_kernel, dim3(1), dim3(kWave), 0, s, nch, heads, off, out_nfib);
+    SPT_CHECK_LAUNCH("ttm total");
+    if (vec)  // fid comes from the 256-byte aligned workspace
+      hipLaunchKernelGGL(fiber_ids_kernel<true>, dim3(nch), dim3(kBlock), 0, s, nnz, ci, cj, off, fid,
+                         out_i, out_j);
+    else
+      hipLaunchKernelGGL(fiber_ids_kernel<false>, dim3(nch), dim3(kBlock), 0, s, nnz, ci, cj, off, fid,
+                         out_i, out_j);
+    SPT_CHECK_LAUNCH("ttm fiber ids");
+  } else {
+    const int64_t nfib = B->level[2].M;
+    if (nfib + 1 >= INT32_MAX) return fail(SPT_ERR_UNSUPPORTED, "ttm: tensor too large");
+    if (out_nfib) {
+      hipLaunchKernelGGL(set_i64_kernel, dim3(1), dim3(kWave), 0, s, out_nfib, nfib);
+      SPT_CHECK_LAUNCH("ttm set count");
+    }
+    hipLaunchKernelGGL(expand_fiber_ids_kernel, dim3((unsigned)((nfib + kBlock - 1) / kBlock)),
+                       dim3(kBlock), 0, s, (int)nfib, B->level[2].pos, fid);
+    SPT_CHECK_LAUNCH("ttm expand fibre ids");
+  }
+  hipLaunchKernelGGL(transpose_kernel<T>, dim3((unsigned)((L * K + kBlock - 1) / kBlock)),
+                     dim3(kBlock), 0, s, K, L, C, Ct);
+  SPT_CHECK_LAUNCH("ttm transpose");
+  void* rest = static_cast<char*>(ws) + W.used;
+  return mttkrp_typed<T>(Format::COO2, B, Ct, nullptr, K, out_v, rest, ws_bytes - W.used, s, fid,
+                         B->level[2].crd);
+}
+
+spt_status ttm_dispatch(Format f, const spt_tensor* B, const void* C, int32_t K, int32_t* out_crd0,
+                        int32_t* out_crd1, void* out_vals, int64_t* out_nfib_dev, void* ws,
+                        size_t ws_bytes, hipStream_t s) {
+  for (int k = 0; k < 3; ++k)
+    if (!(B->level[k].flags & SPT_ORDERED))
+      return fail(SPT_ERR_UNSUPPORTED, "ttm: every level of B must be ordered");
+  if (B->dtype == SPT_F64)
+    return ttm_typed<double>(f, B, static_cast<const double*>(C), K, out_crd0, out_crd1,
+                             static_cast<double*>(out_vals), out_nfib_dev, ws, ws_bytes, s);
+  return ttm_typed<float>(f, B, static_cast<const float*>(C), K, out_crd0, out_crd1,
+                          static_cast<float*>(out_vals), out_nfib_dev, ws, ws_bytes, s);
+}
+
+size_t ttv_workspace(Format f, const spt_tensor* B) {
+  return f == Format::COO3 ? ttv_coo_workspace(B->nvals) : seg_spmv_workspace(B->nvals);
 }
 
 spt_status ttv_dispatch(Format f, const spt_tensor* B, const void* c, int32_t* out_crd0,

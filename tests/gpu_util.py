@@ -114,3 +114,27 @@ def gpu_innerprod(bspec, cspec):
     spt.spt_innerprod(B, Ct, out, B.workspace(spt.SPT_OP_INNERPROD))
     torch.cuda.synchronize()
     return float(out.cpu().numpy()[0])
+
+
+def gpu_ttm(spec, Cm, is_csf=False, fiber_capacity=None, misalign=False):
+    """Returns (fibre i, fibre j, values[nfib, K]); i and j are None for CSF input."""
+    import torch
+    import paper_1804_10112_amd as spt
+    B = spt.DeviceTensor(spec, misalign=misalign)
+    Cd = torch.from_numpy(np.ascontiguousarray(Cm)).cuda()
+    K = Cm.shape[0]
+    cap = len(spec.vals) if fiber_capacity is None else fiber_capacity
+    oi = torch.full((max(cap, 1),), -7, dtype=torch.int32, device="cuda")
+    oj = torch.full((max(cap, 1),), -7, dtype=torch.int32, device="cuda")
+    ov = torch.full((max(cap, 1), K), float("nan"), dtype=B.torch_dtype, device="cuda")
+    cnt = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    ws = B.workspace(spt.SPT_OP_TTM, K)
+    if is_csf:
+        spt.spt_ttm(B, Cd, K, None, None, ov, cnt, ws)
+    else:
+        spt.spt_ttm(B, Cd, K, oi, oj, ov, cnt, ws)
+    torch.cuda.synchronize()
+    n = int(cnt.item())
+    if is_csf:
+        return None, None, ov.cpu().numpy()[:n]
+    return oi.cpu().numpy()[:n], oj.cpu().numpy()[:n], ov.cpu().numpy()[:n]
