@@ -359,6 +359,47 @@ double orc_innerprod(const orc_tensor* B, const orc_tensor* C, const int64_t* di
   return (double)acc;
 }
 
+static void emit_sum(int order, const int64_t* dims, int64_t key, double v, double mag,
+                     int64_t n, int64_t cap, int32_t* const* out_crd, double* out_v,
+                     double* out_mag) {
+  if (n >= cap) return;
+  for (int m = order - 1; m >= 0; --m) { /* undo the linearisation, last dimension first */
+    out_crd[m][n] = (int32_t)(key % dims[m]);
+    key /= dims[m];
+  }
+  out_v[n] = v;
+  out_mag[n] = mag;
+}
+int64_t orc_add(const orc_tensor* B, const orc_tensor* C, const int64_t* dims, int64_t cap,
+                int32_t* const* out_crd, double* out_v, double* out_mag) {
+  long double space = 1.0L;
+  for (int m = 0; m < B->order; ++m) space *= (long double)dims[m];
+  if (B->order != C->order || space >= 9.0e18L) return -1;
+  int64_t nb, nc;
+  kv_pair* b = linearise(B, dims, &nb);
+  kv_pair* c = linearise(C, dims, &nc);
+  int64_t pb = 0, pc = 0, n = 0;
+  while (pb < nb || pc < nc) { /* union: the smaller coordinate, or both when equal */
+    if (pc >= nc || (pb < nb && b[pb].key < c[pc].key)) {
+      emit_sum(B->order, dims, b[pb].key, b[pb].val, fabs(b[pb].val), n++, cap, out_crd, out_v,
+               out_mag);
+      ++pb;
+    } else if (pb >= nb || c[pc].key < b[pb].key) {
+      emit_sum(B->order, dims, c[pc].key, c[pc].val, fabs(c[pc].val), n++, cap, out_crd, out_v,
+               out_mag);
+      ++pc;
+    } else {
+      emit_sum(B->order, dims, b[pb].key, b[pb].val + c[pc].val,
+               fabs(b[pb].val) + fabs(c[pc].val), n++, cap, out_crd, out_v, out_mag);
+      ++pb;
+      ++pc;
+    }
+  }
+  free(b);
+  free(c);
+  return n;
+}
+
 /* Stable bottom-up merge sort of an index permutation by one or two int32 keys. */
 static int key_less(const int32_t* k0, const int32_t* k1, int64_t a, int64_t b) {
   if (k0[a] != k0[b]) return k0[a] < k0[b];

@@ -87,6 +87,16 @@ void orc_spdm(const orc_tensor* B, const void* C, int32_t J, int64_t rows, doubl
  * coordinate would overflow 63 bits. */
 double orc_innerprod(const orc_tensor* B, const orc_tensor* C, const int64_t* dims, double* mag);
 
+/* A = B + C with a sparse result (Section 5.2 matrix addition, Section 5.3 PLUS): the union
+ * merge of Section 4.4 over both operands ordered by linearised coordinate; a coordinate
+ * stored in both gives one entry holding the sum, a coordinate stored in one gives that entry
+ * (results that cancel to zero stay stored). Coordinates are assumed unique per operand.
+ * out_crd: order arrays of capacity cap each (out_crd[m][n] = coordinate m of entry n),
+ * out_v / out_mag (|b| + |c|) capacity cap. Returns the entry count (-1: 63-bit overflow of
+ * the linearised coordinate or operands of different order). */
+int64_t orc_add(const orc_tensor* B, const orc_tensor* C, const int64_t* dims, int64_t cap,
+                int32_t* const* out_crd, double* out_v, double* out_mag);
+
 /* COO -> CSR index assembly. order 0: by (row,col), ties keep input order;
  * order 1: by row, input order kept inside a row. pos via Table 3's
  * append_init / append_edges / append_finalize. perm_out[n] = input index of

@@ -401,3 +401,59 @@ def test_ttm_closed_forms():
     oi, oj, ov, _ = oracle.ttm(spec, sel)                           # rows of C pick slices l = 3 and 2 * (l = 1)
     assert np.array_equal(ov[:, 0], B[oi, oj, 3]) and np.array_equal(ov[:, 1], 2 * B[oi, oj, 1])
     assert len(oracle.ttm(wl.coo3_spec((2, 2, 2), [], [], [], np.zeros(0)), np.ones((3, 2)))[0]) == 0
+
+
+# ------------------------------------------------------------------ sparse add (union merge)
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_add_matrices_vs_scipy(dtype):
+    N, M = 40, 53
+    r1, c1, v1 = wl.random_coo_entries(N, M, 500, seed=71, dtype=dtype)
+    r2, c2, v2 = wl.random_coo_entries(N, M, 700, seed=72, dtype=dtype)
+    S = (sp.coo_matrix((v1.astype(np.float64), (r1, c1)), shape=(N, M)).tocsr() +
+         sp.coo_matrix((v2.astype(np.float64), (r2, c2)), shape=(N, M)).tocsr())
+    S.sort_indices()
+    S = S.tocoo()                                    # row-major, columns ascending
+    shared = len(r1) + len(r2) - S.nnz
+    assert 0 < shared < min(len(r1), len(r2))        # a proper partial overlap
+    bcoo, ccoo = wl.coo_spec(N, M, r1, c1, v1), wl.coo_spec(N, M, r2, c2, v2)
+    bcsr, ccsr = wl.csr_from_sorted_coo(N, M, r1, c1, v1), wl.csr_from_sorted_coo(N, M, r2, c2, v2)
+    for b, c in ((bcoo, ccoo), (bcsr, ccsr), (bcoo, ccsr)):
+        (ri, ci), v, mag = oracle.add(b, c)
+        assert np.array_equal(ri, S.row) and np.array_equal(ci, S.col)
+        np.testing.assert_allclose(v, S.data, rtol=0, atol=1e-15)
+    # magnitudes: |b| + |c|
+    Sa = (abs(sp.coo_matrix((v1.astype(np.float64), (r1, c1)), shape=(N, M)).tocsr()) +
+          abs(sp.coo_matrix((v2.astype(np.float64), (r2, c2)), shape=(N, M)).tocsr()))
+    Sa.sort_indices()
+    np.testing.assert_allclose(mag, Sa.tocoo().data, rtol=0, atol=1e-15)
+
+
+def test_add_third_order_vs_dense_and_closed_forms():
+    dims = (6, 5, 7)
+    bi, bj, bk, bv = wl.random_coo3_entries(dims, 90, seed=73, dtype=np.float64, skew=1.5)
+    ci, cj, ck, cv = wl.random_coo3_entries(dims, 120, seed=74, dtype=np.float64)
+    b, c = wl.coo3_spec(dims, bi, bj, bk, bv), wl.coo3_spec(dims, ci, cj, ck, cv)
+    D = _dense3(dims, bi, bj, bk, bv) + _dense3(dims, ci, cj, ck, cv)
+    support = (_dense3(dims, bi, bj, bk, np.ones(len(bv))) + _dense3(dims, ci, cj, ck, np.ones(len(cv)))) > 0
+    (oi, oj, ok), v, _ = oracle.add(b, c)
+    lin = (oi.astype(np.int64) * 5 + oj) * 7 + ok
+    assert np.all(np.diff(lin) > 0)                                   # ordered, unique
+    assert np.array_equal(lin, np.flatnonzero(support.ravel()))       # exactly the union
+    np.testing.assert_allclose(v, D[oi, oj, ok], rtol=0, atol=1e-15)
+    # commutative in coordinates and values
+    (pi, pj, pk), pv, _ = oracle.add(c, b)
+    assert np.array_equal(pi, oi) and np.array_equal(pj, oj) and np.array_equal(pk, ok) and np.array_equal(pv, v)
+    # B + B = 2B on B's structure; B + (-B) keeps the structure with explicit zeros
+    (qi, qj, qk), qv, _ = oracle.add(b, b)
+    assert np.array_equal(qi, bi) and np.array_equal(qk, bk) and np.array_equal(qv, 2 * bv)
+    neg = wl.coo3_spec(dims, bi, bj, bk, -bv)
+    (zi, _, _), zv, zm = oracle.add(b, neg)
+    assert len(zi) == len(bv) and np.all(zv == 0) and np.array_equal(zm, 2 * np.abs(bv))
+    # empty operand: the other one unchanged
+    e = np.zeros(0, int)
+    (ei, ej, ek), ev, _ = oracle.add(b, wl.coo3_spec(dims, e, e, e, np.zeros(0)))
+    assert np.array_equal(ei, bi) and np.array_equal(ej, bj) and np.array_equal(ek, bk) and np.array_equal(ev, bv)
+    # CSF operands walk to the same result
+    (fi, fj, fk), fv, _ = oracle.add(wl.csf3_from_sorted_coo(dims, bi, bj, bk, bv), c)
+    assert np.array_equal(fi, oi) and np.array_equal(fk, ok) and np.array_equal(fv, v)
