@@ -66,7 +66,7 @@ def build_items(args):
 
     def on(name):
         if want is None:
-            return name not in ("x16", "n2")   # these groups run only on request
+            return name not in ("x16", "n2", "n3")   # these groups run only on request
         return name in want or name.split("_")[0] in want
 
     # ---- config 2: banded, 7 diagonals, fp64: DIA and CSR
@@ -226,6 +226,49 @@ def build_items(args):
         items.append(Item("n2_ttm_csf", lambda: spt.spt_ttm(Bf, Ck, K, None, None, tv, tcnt, w4),
                           2 * K * nnz, 8 * nnz + 4 * nfib + out_b, "output fibres dominate the bytes"))
         del c5
+    # ---- on request (--only n3): sparse addition with sparse result. PLUS on config 5's tensor
+    #      and a 10M-entry tensor of the same generator; COO and CSR matrix addition on config 4's
+    #      sorted matrix and every second of its entries
+    if on("n3"):
+        dims = tuple(max(16, int(d * s)) for d in (100_000, 80_000, 50_000))
+        c5 = wl.config5(dims=dims, nnz=max(1000, int(50_000_000 * s)))
+        nb = c5["nnz"]
+        ci, cj, ck, cv = wl.random_coo3_entries(dims, max(200, int(10_000_000 * s)), wl.SEED_BASE + 55,
+                                                np.float32, "u01", skew=1.5)
+        Bc, Cc = spt.DeviceTensor(c5["coo"]), spt.DeviceTensor(wl.coo3_spec(dims, ci, cj, ck, cv))
+        nc = len(cv)
+        cap = nb + nc
+        o0, o1, o2 = (torch.empty(cap, dtype=torch.int32, device=dev) for _ in range(3))
+        ov = torch.empty(cap, dtype=torch.float32, device=dev)
+        ocnt = torch.zeros(1, dtype=torch.int64, device=dev)
+        wsa = torch.empty(spt.spt_add_workspace_bytes(Bc, Cc), dtype=torch.uint8, device=dev)
+        keep.extend([Bc, Cc, o0, o1, o2, ov, ocnt, wsa])
+        items.append(Item("n3_plus_coo3", lambda: spt.spt_add(Bc, Cc, None, o0, o1, o2, ov, ocnt, wsa),
+                          nc, 32 * (nb + nc), "read 16 B + write <= 16 B per stored entry"))
+        del c5
+        n4 = max(1024, int(4_000_000 * s))
+        c4 = wl.config4(N=n4, nnz_target=int(60_000_000 * s), max_row=max(8, int(200_000 * s)), with_sorted=True)
+        rs, cs, vs = c4["sorted"]
+        half = slice(0, len(vs), 2)
+        nb, nc = len(vs), len(vs[half])
+        cap = nb + nc
+        q0, q1 = (torch.empty(cap, dtype=torch.int32, device=dev) for _ in range(2))
+        qpos = torch.empty(n4 + 1, dtype=torch.int32, device=dev)
+        qv = torch.empty(cap, dtype=torch.float64, device=dev)
+        for fmt, mk in (("coo", wl.coo_spec), ("csr", wl.csr_from_sorted_coo)):
+            Bm = spt.DeviceTensor(mk(n4, n4, rs, cs, vs))
+            Cm2 = spt.DeviceTensor(mk(n4, n4, rs[half], cs[half], 0.5 * vs[half]))
+            wsm = torch.empty(spt.spt_add_workspace_bytes(Bm, Cm2), dtype=torch.uint8, device=dev)
+            keep.extend([Bm, Cm2, wsm])
+            if fmt == "coo":
+                run = lambda Bm=Bm, Cm2=Cm2, wsm=wsm: spt.spt_add(Bm, Cm2, None, q0, q1, None, qv, ocnt, wsm)
+                byt = 16 * (nb + nc) + 16 * nb
+            else:
+                run = lambda Bm=Bm, Cm2=Cm2, wsm=wsm: spt.spt_add(Bm, Cm2, qpos, None, q1, None, qv, ocnt, wsm)
+                byt = 12 * (nb + nc) + 12 * nb + 12 * (n4 + 1)
+            items.append(Item(f"n3_add_{fmt}", run, nc, byt))
+        keep.extend([q0, q1, qpos, qv])
+        del c4
     return items, cpu_jobs, keep
 
 

@@ -230,6 +230,26 @@ spt_status spt_ttm(const spt_tensor* B, const void* C, int32_t K, int32_t* out_c
 spt_status spt_innerprod(const spt_tensor* B, const spt_tensor* C, void* alpha_out, void* ws,
                          size_t ws_bytes, void* stream);
 
+/*
+ * A = B + C with a sparse result: matrix addition on COO or CSR (Section 5.2) and 3rd-order
+ * PLUS on COO (Section 5.3). B and C: the same format (both COO matrices, both CSR, or both
+ * COO3), dimensions and dtype, every level ordered, each coordinate stored at most once per
+ * operand. The result has one entry per coordinate stored in B or C (the union merge of
+ * Section 4.4), ordered, holding b, c or the rounded sum b + c; sums that cancel stay stored.
+ * Outputs need capacity nnz(B) + nnz(C) entries; *out_nnz_dev (device int64, required)
+ * receives the entry count.
+ *   COO matrices: out_crd0 (rows), out_crd1 (cols), out_vals; out_pos, out_crd2 ignored.
+ *   COO3:         out_crd0, out_crd1, out_crd2, out_vals; out_pos ignored.
+ *   CSR:          out_pos[N+1] (Table 3: counts, then running sum), out_crd1 (cols), out_vals;
+ *                 out_crd0, out_crd2 ignored.
+ * Workspace: spt_add_workspace_bytes(B, C), about 4 bytes per stored entry of both operands
+ * (CSR: 12).
+ */
+spt_status spt_add(const spt_tensor* B, const spt_tensor* C, int32_t* out_pos, int32_t* out_crd0,
+                   int32_t* out_crd1, int32_t* out_crd2, void* out_vals, int64_t* out_nnz_dev,
+                   void* ws, size_t ws_bytes, void* stream);
+size_t spt_add_workspace_bytes(const spt_tensor* B, const spt_tensor* C);
+
 /* Workspace size in bytes for `op` on tensor T (J only for MTTKRP and TTM).
  * Returns 0 for invalid descriptors (spt_last_error says why). Never fails for
  * a valid one; the result is always >= 256. */

@@ -24,7 +24,8 @@ SPT_F32, SPT_F64 = 0, 1
 
 SYMBOLS = ["spt_spmv", "spt_coo_to_csr", "spt_ttv", "spt_mttkrp", "spt_workspace_bytes",
            "spt_last_error", "spt_version", "spt_probe_read", "spt_probe_gather",
-           "spt_spmv_sparse_x", "spt_spdm", "spt_innerprod", "spt_ttm"]
+           "spt_spmv_sparse_x", "spt_spdm", "spt_innerprod", "spt_ttm",
+           "spt_add", "spt_add_workspace_bytes"]
 
 
 class SptLevel(C.Structure):
@@ -68,6 +69,10 @@ def lib():
         L.spt_ttv.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.spt_mttkrp.restype = i32
         L.spt_mttkrp.argtypes = [vp, vp, vp, i32, vp, vp, sz, vp]
+        L.spt_add.restype = i32
+        L.spt_add.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.spt_add_workspace_bytes.restype = sz
+        L.spt_add_workspace_bytes.argtypes = [vp, vp]
         L.spt_ttm.restype = i32
         L.spt_ttm.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
         L.spt_innerprod.restype = i32
@@ -181,6 +186,19 @@ def spt_ttm(B, Cm, K, out_crd0, out_crd1, out_vals, out_nfib_dev, ws=None, strea
     p, n = _ws(ws)
     _check(lib().spt_ttm(_desc(B), _p(Cm), K, _p(out_crd0), _p(out_crd1), _p(out_vals),
                          _p(out_nfib_dev), p, n, _stream(stream)))
+
+
+def spt_add(B, Ct, out_pos, out_crd0, out_crd1, out_crd2, out_vals, out_nnz_dev, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(lib().spt_add(_desc(B), _desc(Ct), _p(out_pos), _p(out_crd0), _p(out_crd1), _p(out_crd2),
+                         _p(out_vals), _p(out_nnz_dev), p, n, _stream(stream)))
+
+
+def spt_add_workspace_bytes(B, Ct):
+    n = lib().spt_add_workspace_bytes(_desc(B), _desc(Ct))
+    if n == 0:
+        raise SptError(SPT_ERR_INVALID_ARG, spt_last_error())
+    return n
 
 
 def spt_innerprod(B, Ct, alpha_out, ws=None, stream=None):

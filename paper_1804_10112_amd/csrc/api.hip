@@ -48,6 +48,11 @@ spt_status innerprod_dispatch(Format f, const spt_tensor* B, const spt_tensor* C
                               void* ws, size_t ws_bytes, hipStream_t s);
 size_t innerprod_workspace(int64_t nb);
 
+spt_status add_dispatch(Format f, const spt_tensor* B, const spt_tensor* C, int32_t* out_pos,
+                        int32_t* out_crd0, int32_t* out_crd1, int32_t* out_crd2, void* out_vals,
+                        int64_t* out_nnz, void* ws, size_t ws_bytes, hipStream_t s);
+size_t add_workspace(Format f, const spt_tensor* B, const spt_tensor* C);
+
 static bool is(const spt_level& L, int kind) { return L.kind == kind; }
 static bool unique(const spt_level& L) { return (L.flags & SPT_UNIQUE) != 0; }
 
@@ -327,6 +332,51 @@ spt_status spt_innerprod(const spt_tensor* B, const spt_tensor* C, void* alpha_o
       return fail(SPT_ERR_UNSUPPORTED, "innerprod: every level of B and C must be ordered");
   }
   return innerprod_dispatch(fb, B, C, alpha_out, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+// Common operand checks of spt_add; returns the shared format or sets the error.
+static spt_status add_operands(const spt_tensor* B, const spt_tensor* C, Format* f_out) {
+  Format fb = recognize(B);
+  if (fb == Format::Invalid || fb == Format::Unsupported) return status_of(fb);
+  Format fc = recognize(C);
+  if (fc == Format::Invalid || fc == Format::Unsupported) return status_of(fc);
+  if (fb != fc || (fb != Format::COO2 && fb != Format::COO3 && fb != Format::CSR))
+    return fail(SPT_ERR_UNSUPPORTED, "add: B and C must both be COO matrices, both CSR or both COO3");
+  if (B->dtype != C->dtype) return fail(SPT_ERR_INVALID_ARG, "add: B and C differ in dtype");
+  for (int k = 0; k < B->nlevels; ++k) {
+    if (B->level[k].N != C->level[k].N)
+      return fail(SPT_ERR_INVALID_ARG, "add: dimension %d differs (%lld vs %lld)", k,
+                  (long long)B->level[k].N, (long long)C->level[k].N);
+    if (fb == Format::CSR && k == 0) continue;  // the dense row level is ordered by construction
+    if (!(B->level[k].flags & C->level[k].flags & SPT_ORDERED))
+      return fail(SPT_ERR_UNSUPPORTED, "add: every level of B and C must be ordered");
+  }
+  *f_out = fb;
+  return SPT_OK;
+}
+
+spt_status spt_add(const spt_tensor* B, const spt_tensor* C, int32_t* out_pos, int32_t* out_crd0,
+                   int32_t* out_crd1, int32_t* out_crd2, void* out_vals, int64_t* out_nnz_dev,
+                   void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  Format f;
+  spt_status st = add_operands(B, C, &f);
+  if (st != SPT_OK) return st;
+  if (!out_crd1 || !out_vals || !out_nnz_dev)
+    return fail(SPT_ERR_INVALID_ARG, "add: out_crd1, out_vals and out_nnz_dev are required");
+  if (f == Format::CSR && !out_pos) return fail(SPT_ERR_INVALID_ARG, "add: CSR result needs out_pos");
+  if (f != Format::CSR && !out_crd0) return fail(SPT_ERR_INVALID_ARG, "add: COO result needs out_crd0");
+  if (f == Format::COO3 && !out_crd2) return fail(SPT_ERR_INVALID_ARG, "add: COO3 result needs out_crd2");
+  return add_dispatch(f, B, C, out_pos, out_crd0, out_crd1, out_crd2, out_vals, out_nnz_dev, ws,
+                      ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+size_t spt_add_workspace_bytes(const spt_tensor* B, const spt_tensor* C) {
+  clear_error();
+  Format f;
+  if (add_operands(B, C, &f) != SPT_OK) return 0;
+  const size_t n = add_workspace(f, B, C);
+  return n < 256 ? 256 : n;
 }
 
 size_t spt_workspace_bytes(int32_t op, const spt_tensor* T, int32_t J) {

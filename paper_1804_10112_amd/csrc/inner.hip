@@ -20,82 +20,13 @@
 // Products are added in double in a fixed order (lane-strided over a tile's C
 // entries, shuffle tree, wave order, tile order): the result is reproducible bit for bit.
 #include "common.hpp"
+#include "merge.hpp"
 
 namespace spt {
 
 constexpr int kIpVT = 7;                   // merge steps per lane: 18 KB of LDS, 8 workgroups per CU
 constexpr int kIpTile = kBlock * kIpVT;    // merge steps per tile
 constexpr int kIpMaxGrid = 4096;           // workgroups (and partial sums); tiles beyond are looped
-
-// ---- coordinate keys -------------------------------------------------------
-struct Key3 {
-  int32_t i, j, k;
-};
-__device__ __forceinline__ bool key_le(const Key3& a, const Key3& b) {
-  if (a.i != b.i) return a.i < b.i;
-  if (a.j != b.j) return a.j < b.j;
-  return a.k <= b.k;
-}
-__device__ __forceinline__ bool key_eq(const Key3& a, const Key3& b) {
-  return a.i == b.i && a.j == b.j && a.k == b.k;
-}
-__device__ __forceinline__ bool key_le(uint64_t a, uint64_t b) { return a <= b; }
-__device__ __forceinline__ bool key_eq(uint64_t a, uint64_t b) { return a == b; }
-
-// Loaders turn position p of a COO operand into a key. a2 == nullptr for matrices.
-struct PackedLoader {
-  typedef uint64_t Key;
-  const int32_t *a0, *a1, *a2;
-  int s0, s1;  // shifts of the first and second coordinate
-  __device__ __forceinline__ Key load(int p) const {
-    uint64_t k = (static_cast<uint64_t>(static_cast<uint32_t>(a0[p])) << s0) |
-                 (static_cast<uint64_t>(static_cast<uint32_t>(a1[p])) << s1);
-    if (a2) k |= static_cast<uint32_t>(a2[p]);
-    return k;
-  }
-  __device__ __forceinline__ static Key none() { return ~0ull; }
-};
-struct TripleLoader {
-  typedef Key3 Key;
-  const int32_t *a0, *a1, *a2;
-  __device__ __forceinline__ Key load(int p) const {
-    Key3 k;
-    k.i = a0[p];
-    k.j = a1[p];
-    k.k = a2 ? a2[p] : 0;
-    return k;
-  }
-  __device__ __forceinline__ static Key none() { return Key3{-1, -1, -1}; }
-};
-
-// Number of B entries among the first d entries of the merge of B and C (ties: B
-// first). The predicate "B[x] precedes C[d-1-x]" is true for small x and false for
-// large x; the answer is the first x where it fails. Plain bisection, one lane per
-// diagonal: tens of thousands of diagonals are searched at once, and their first
-// probes fall on the same few cache lines.
-template <typename KL>
-__device__ __forceinline__ int merge_path(const KL& kb, const KL& kc, int nb, int nc, int64_t d) {
-  int lo = static_cast<int>(d > nc ? d - nc : 0);
-  int hi = static_cast<int>(d < nb ? d : nb);
-  while (lo < hi) {
-    const int mid = lo + ((hi - lo) >> 1);
-    if (key_le(kb.load(mid), kc.load(static_cast<int>(d - 1 - mid)))) lo = mid + 1; else hi = mid;
-  }
-  return lo;
-}
-
-// xs[t] = merge-path crossing of the first diagonal of tile t, t = 0..ntiles.
-template <typename KL>
-__global__ __launch_bounds__(kBlock) void merge_partition_kernel(const KL kb, const KL kc, int nb,
-                                                                 int nc, int ntiles,
-                                                                 int* __restrict__ xs) {
-  const int t = blockIdx.x * kBlock + threadIdx.x;
-  if (t > ntiles) return;
-  const int64_t total = static_cast<int64_t>(nb) + nc;
-  int64_t d = static_cast<int64_t>(t) * kIpTile;
-  if (d > total) d = total;
-  xs[t] = merge_path(kb, kc, nb, nc, d);
-}
 
 template <typename T, typename KL>
 __global__ __launch_bounds__(kBlock) void innerprod_kernel(const KL kb, const KL kc,
@@ -195,12 +126,6 @@ size_t innerprod_workspace(int64_t) {
   return align_up(kIpMaxGrid * sizeof(double), 256) + align_up(max_tiles * sizeof(int), 256);
 }
 
-static int bits_of(int64_t extent) {
-  int b = 1;
-  while (b < 63 && (int64_t{1} << b) < extent) ++b;
-  return b;
-}
-
 template <typename T>
 static spt_status innerprod_typed(const spt_tensor* B, const spt_tensor* C, void* out, void* ws,
                                   size_t ws_bytes, hipStream_t s) {
@@ -222,19 +147,19 @@ static spt_status innerprod_typed(const spt_tensor* B, const spt_tensor* C, void
   const T* cv = static_cast<const T*>(C->vals);
   if (ntiles > 0) {
     const int pgrid = (ntiles + 1 + kBlock - 1) / kBlock;
-    const int w1 = bits_of(B->level[1].N), w2 = third ? bits_of(B->level[2].N) : 0;
-    if (bits_of(B->level[0].N) + w1 + w2 <= 63) {
+    const int w1 = key_bits_of(B->level[1].N), w2 = third ? key_bits_of(B->level[2].N) : 0;
+    if (key_bits_of(B->level[0].N) + w1 + w2 <= 63) {
       PackedLoader kb{B->level[0].crd, B->level[1].crd, b2, w1 + w2, w2};
       PackedLoader kc{C->level[0].crd, C->level[1].crd, c2, w1 + w2, w2};
       hipLaunchKernelGGL(merge_partition_kernel<PackedLoader>, dim3(pgrid), dim3(kBlock), 0, s, kb, kc,
-                         nb, nc, ntiles, xs);
+                         nb, nc, ntiles, kIpTile, xs);
       hipLaunchKernelGGL((innerprod_kernel<T, PackedLoader>), dim3(grid), dim3(kBlock), 0, s, kb,
                          kc, bv, cv, nb, nc, ntiles, xs, partial);
     } else {
       TripleLoader kb{B->level[0].crd, B->level[1].crd, b2};
       TripleLoader kc{C->level[0].crd, C->level[1].crd, c2};
       hipLaunchKernelGGL(merge_partition_kernel<TripleLoader>, dim3(pgrid), dim3(kBlock), 0, s, kb, kc,
-                         nb, nc, ntiles, xs);
+                         nb, nc, ntiles, kIpTile, xs);
       hipLaunchKernelGGL((innerprod_kernel<T, TripleLoader>), dim3(grid), dim3(kBlock), 0, s, kb,
                          kc, bv, cv, nb, nc, ntiles, xs, partial);
     }

@@ -138,3 +138,29 @@ def gpu_ttm(spec, Cm, is_csf=False, fiber_capacity=None, misalign=False):
     if is_csf:
         return None, None, ov.cpu().numpy()[:n]
     return oi.cpu().numpy()[:n], oj.cpu().numpy()[:n], ov.cpu().numpy()[:n]
+
+
+def gpu_add(bspec, cspec, fmt, misalign=False):
+    """fmt 'coo', 'coo3' or 'csr'. Returns (list of index arrays, values): for 'csr' the index
+    arrays are [pos, cols], else the coordinate arrays."""
+    import torch
+    import paper_1804_10112_amd as spt
+    B, Ct = spt.DeviceTensor(bspec, misalign=misalign), spt.DeviceTensor(cspec, misalign=misalign)
+    cap = max(len(bspec.vals) + len(cspec.vals), 1)
+    i32 = lambda n: torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    c0, c1, c2 = i32(cap), i32(cap), i32(cap)
+    pos = i32(bspec.dims[0] + 1)
+    ov = torch.full((cap,), float("nan"), dtype=B.torch_dtype, device="cuda")
+    cnt = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    ws = torch.empty(spt.spt_add_workspace_bytes(B, Ct), dtype=torch.uint8, device="cuda")
+    spt.spt_add(B, Ct, pos if fmt == "csr" else None, None if fmt == "csr" else c0, c1,
+                c2 if fmt == "coo3" else None, ov, cnt, ws)
+    torch.cuda.synchronize()
+    n = int(cnt.item())
+    v = ov.cpu().numpy()[:n]
+    if fmt == "csr":
+        return [pos.cpu().numpy(), c1.cpu().numpy()[:n]], v
+    idx = [c0.cpu().numpy()[:n], c1.cpu().numpy()[:n]]
+    if fmt == "coo3":
+        idx.append(c2.cpu().numpy()[:n])
+    return idx, v

@@ -1,0 +1,182 @@
+"""GPU parity: spt_add (sparse A = B + C on COO matrices, CSR matrices and 3rd-order COO)
+vs the oracle's union merge. Coordinates and pos bit-exact, values within tolerance (they are a
+copy or one rounded sum, so fp64 results are in fact equal)."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from gpu_util import assert_close, gpu_add
+
+pytestmark = pytest.mark.gpu
+
+
+def _matrices(N, M, nb, nc, seed, dtype, fmt):
+    r1, c1, v1 = wl.random_coo_entries(N, M, nb, seed=seed, dtype=dtype)
+    r2, c2, v2 = wl.random_coo_entries(N, M, nc, seed=seed + 1, dtype=dtype)
+    if fmt == "csr":
+        return wl.csr_from_sorted_coo(N, M, r1, c1, v1), wl.csr_from_sorted_coo(N, M, r2, c2, v2)
+    return wl.coo_spec(N, M, r1, c1, v1), wl.coo_spec(N, M, r2, c2, v2)
+
+
+def _check_matrix(b, c, fmt, dtype, what, misalign=False):
+    (ri, ci), rv, rm = oracle.add(b, c)
+    idx, gv = gpu_add(b, c, fmt, misalign=misalign)
+    if fmt == "csr":
+        pos = np.concatenate([[0], np.cumsum(np.bincount(ri, minlength=b.dims[0]))])
+        assert np.array_equal(idx[0], pos), f"{what}: pos"
+        assert np.array_equal(idx[1], ci), f"{what}: cols"
+    else:
+        assert np.array_equal(idx[0], ri) and np.array_equal(idx[1], ci), f"{what}: coordinates"
+    assert_close(gv, rv, rm, dtype, what)
+    return len(ri)
+
+
+@pytest.mark.parametrize("fmt", ["coo", "csr"])
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("nb,nc", [(1, 1), (50, 70), (895, 897), (1792, 1792), (1793, 3000),
+                                   (30_000, 41_000), (60_000, 500)])
+def test_add_matrices(fmt, dtype, nb, nc):
+    b, c = _matrices(300, 257, nb, nc, seed=1000 + nb, dtype=dtype, fmt=fmt)
+    n = _check_matrix(b, c, fmt, dtype, f"add {fmt} {nb}+{nc}")
+    if min(nb, nc) >= 30_000:
+        assert n < nb + nc                      # supports overlap
+
+
+@pytest.mark.parametrize("fmt", ["coo", "csr"])
+def test_add_skewed_rows_empty_rows_and_misaligned(fmt):
+    # power-law rows with long empty stretches: rows far longer than a chunk, many empty rows
+    c4 = wl.config4(N=20_000, nnz_target=300_000, max_row=30_000, with_sorted=True)
+    rs, cs, vs = c4["sorted"]
+    N = 20_000
+    r2, c2, v2 = wl.random_coo_entries(N, N, 150_000, seed=5, dtype=np.float64)
+    half = slice(0, len(vs), 2)                 # plus every second entry of B itself: many twins
+    key = np.concatenate([r2.astype(np.int64) * N + c2, rs[half].astype(np.int64) * N + cs[half]])
+    vals = np.concatenate([v2, vs[half] * 0.5])
+    key, first = np.unique(key, return_index=True)
+    r2, c2, v2 = (key // N).astype(np.int32), (key % N).astype(np.int32), vals[first]
+    mk = wl.csr_from_sorted_coo if fmt == "csr" else wl.coo_spec
+    b, c = mk(N, N, rs, cs, vs), mk(N, N, r2, c2, v2)
+    n = _check_matrix(b, c, fmt, np.float64, f"add {fmt} skewed")
+    assert n <= len(vs) + len(v2) - len(vs[half]) + 10
+    _check_matrix(b, c, fmt, np.float64, f"add {fmt} skewed misaligned", misalign=True)
+    _check_matrix(c, b, fmt, np.float64, f"add {fmt} skewed swapped")
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("nb,nc", [(100, 90), (20_000, 30_000), (5_000, 450_000)])
+def test_plus_third_order(dtype, nb, nc):
+    dims = (64, 64, 128) if nc > 100_000 else (40, 30, 50)
+    bi, bj, bk, bv = wl.random_coo3_entries(dims, nb, 1100 + nb, dtype=dtype, dist="u11", skew=1.3)
+    ci, cj, ck, cv = wl.random_coo3_entries(dims, nc, 1101 + nb, dtype=dtype, dist="u11")
+    b, c = wl.coo3_spec(dims, bi, bj, bk, bv), wl.coo3_spec(dims, ci, cj, ck, cv)
+    (ri, rj, rk), rv, rm = oracle.add(b, c)
+    idx, gv = gpu_add(b, c, "coo3")
+    assert np.array_equal(idx[0], ri) and np.array_equal(idx[1], rj) and np.array_equal(idx[2], rk)
+    assert_close(gv, rv, rm, dtype, "plus")
+    idx2, gv2 = gpu_add(c, b, "coo3")                                   # commutative, bit for bit
+    assert all(np.array_equal(a, b_) for a, b_ in zip(idx, idx2)) and np.array_equal(gv, gv2)
+
+
+def test_add_special_operands():
+    dims = (30, 20, 25)
+    bi, bj, bk, bv = wl.random_coo3_entries(dims, 6000, 7, dtype=np.float64, dist="u11")
+    b = wl.coo3_spec(dims, bi, bj, bk, bv)
+    idx, v = gpu_add(b, b, "coo3")                                      # B + B = 2B on B's structure
+    assert np.array_equal(idx[0], bi) and np.array_equal(idx[2], bk) and np.array_equal(v, 2 * bv)
+    idx, v = gpu_add(b, wl.coo3_spec(dims, bi, bj, bk, -bv), "coo3")     # cancellation keeps the entries
+    assert len(v) == len(bv) and np.all(v == 0)
+    e = np.zeros(0, np.int32)
+    empty = wl.coo3_spec(dims, e, e, e, np.zeros(0, np.float64))
+    for x, y in ((b, empty), (empty, b)):
+        idx, v = gpu_add(x, y, "coo3")
+        assert np.array_equal(idx[1], bj) and np.array_equal(v, bv)
+    idx, v = gpu_add(empty, empty, "coo3")
+    assert len(v) == 0
+    # disjoint supports interleave
+    k1 = np.unique((bi.astype(np.int64) * 20 + bj) * 25 + 2 * (bk // 2), return_index=True)[1]
+    d1 = wl.coo3_spec(dims, bi[k1], bj[k1], (2 * (bk // 2))[k1], bv[k1])
+    sel = (2 * (bk // 2) + 1 < 25)[k1]
+    d2 = wl.coo3_spec(dims, bi[k1][sel], bj[k1][sel], (2 * (bk // 2) + 1)[k1][sel], bv[k1][sel])
+    idx, v = gpu_add(d1, d2, "coo3")
+    assert len(v) == len(k1) + int(sel.sum())
+    # a CSR matrix whose last rows are empty, plus one whose first rows are empty
+    N = 50
+    top = wl.csr_from_sorted_coo(N, N, np.array([0, 0, 3], np.int32), np.array([1, 7, 2], np.int32), np.ones(3))
+    bot = wl.csr_from_sorted_coo(N, N, np.array([3, 49], np.int32), np.array([2, 49], np.int32), np.ones(2))
+    (pos, cols), v = gpu_add(top, bot, "csr")
+    assert list(cols) == [1, 7, 2, 49] and list(v) == [1, 1, 2, 1]
+    assert pos[0] == 0 and pos[1] == 2 and pos[4] == 3 and pos[49] == 3 and pos[50] == 4
+
+
+def test_add_errors():
+    import torch
+    import paper_1804_10112_amd as spt
+    b, c = _matrices(30, 30, 100, 100, seed=1, dtype=np.float32, fmt="coo")
+    B, Ct = spt.DeviceTensor(b), spt.DeviceTensor(c)
+    i = torch.zeros(200, dtype=torch.int32, device="cuda")
+    v = torch.zeros(200, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ws = torch.empty(spt.spt_add_workspace_bytes(B, Ct), dtype=torch.uint8, device="cuda")
+    with pytest.raises(spt.SptError):
+        spt.spt_add(B, Ct, None, i, i, None, v, None, ws)                # count pointer required
+    with pytest.raises(spt.SptError) as e:
+        spt.spt_add(B, Ct, None, i, i, None, v, cnt, None)
+    assert "workspace" in str(e.value)
+    csr = spt.DeviceTensor(_matrices(30, 30, 100, 100, seed=1, dtype=np.float32, fmt="csr")[1])
+    with pytest.raises(spt.SptError):
+        spt.spt_add(B, csr, None, i, i, None, v, cnt, ws)                # mixed formats
+    other = spt.DeviceTensor(_matrices(30, 31, 100, 100, seed=1, dtype=np.float32, fmt="coo")[1])
+    with pytest.raises(spt.SptError):
+        spt.spt_add(B, other, None, i, i, None, v, cnt, ws)
+    r, cc, vv = wl.random_coo_entries(30, 30, 100, seed=3, dtype=np.float32, sort=False)
+    unordered = wl.coo_spec(30, 30, r, cc, vv, ordered=False)
+    with pytest.raises(spt.SptError):
+        spt.spt_add(B, spt.DeviceTensor(unordered), None, i, i, None, v, cnt, ws)
+
+
+def test_plus_full_size():
+    """Configuration 5's tensor (50M entries) plus a second tensor of the same generator (other
+    seed, 10M entries): coordinates against numpy's union of the linearised keys, values against
+    the definition through searchsorted, and a window of slices against the oracle."""
+    cfg = wl.config5()
+    b = cfg["coo"]
+    dims = b.dims
+    bi, bj, bk = (np.asarray(L.crd) for L in b.levels)
+    ci, cj, ck, cv = wl.random_coo3_entries(dims, 10_000_000, wl.SEED_BASE + 55, np.float32, "u01", skew=1.5)
+    c = wl.coo3_spec(dims, ci, cj, ck, cv)
+    lin = lambda i, j, k: (i.astype(np.int64) * dims[1] + j) * dims[2] + k
+    kb, kc = lin(bi, bj, bk), lin(ci, cj, ck)
+    idx, gv = gpu_add(b, c, "coo3")
+    kg = lin(*idx)
+    union = np.union1d(kb, kc)
+    assert len(union) < len(kb) + len(kc)                               # the supports do overlap
+    assert np.array_equal(kg, union)
+    want = np.zeros(len(union), np.float32)
+    want[np.searchsorted(union, kb)] = b.vals
+    pc = np.searchsorted(union, kc)
+    want[pc] = want[pc] + cv                                            # one fp32 rounding, as on the GPU
+    assert np.array_equal(gv, want)
+    # slices 1000..1019 of both operands through the oracle
+    sb, sc = (bi >= 1000) & (bi < 1020), (ci >= 1000) & (ci < 1020)
+    (ri, rj, rk), rv, rm = oracle.add(wl.coo3_spec(dims, bi[sb], bj[sb], bk[sb], b.vals[sb]),
+                                      wl.coo3_spec(dims, ci[sc], cj[sc], ck[sc], cv[sc]))
+    sg = (idx[0] >= 1000) & (idx[0] < 1020)
+    assert np.array_equal(idx[0][sg], ri) and np.array_equal(idx[1][sg], rj) and np.array_equal(idx[2][sg], rk)
+    assert_close(gv[sg], rv, rm, np.float32, "plus full size window")
+
+
+def test_csr_add_full_size():
+    """Configuration 4's matrix in CSR (60M entries, rows up to 10^5 long) plus every second
+    of its entries scaled: the structure must be B's own, pos included, values b + 0.5 b."""
+    c4 = wl.config4(with_sorted=True)
+    rs, cs, vs = c4["sorted"]
+    N = c4["coo"].dims[0]
+    b = wl.csr_from_sorted_coo(N, N, rs, cs, vs)
+    half = slice(0, len(vs), 2)
+    c = wl.csr_from_sorted_coo(N, N, rs[half], cs[half], 0.5 * vs[half])
+    (pos, cols), gv = gpu_add(b, c, "csr")
+    assert np.array_equal(pos, b.levels[1].pos) and np.array_equal(cols, cs)
+    want = vs.copy()
+    want[half] = vs[half] + 0.5 * vs[half]
+    assert np.array_equal(gv, want)
