@@ -161,8 +161,8 @@ spt_status spt_spmv_sparse_x(const spt_tensor* A, const spt_tensor* x, void* y, 
                              size_t ws_bytes, void* stream);
 
 /*
- * COO -> CSR (the conversion of Section 5.4 / Figure 14; pos is assembled as
- * Table 3's append_edges + append_finalize: per-row counts, then prefix sum).
+ * COO -> CSR (the conversion of Section 5.4 / Figure 14; pos holds what Table 3's
+ * append_edges + append_finalize produce, the running sum of the per-row counts).
  * pos_out[N+1], crd_out[nnz], vals_out[nnz]. If both COO levels are flagged
  * SPT_ORDERED the sort is skipped. Index outputs are exact.
  */

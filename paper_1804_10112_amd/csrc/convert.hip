@@ -5,10 +5,10 @@
 //      significant bits of the column (ROW_COL order only) and then of the row.
 //      Every pass is histogram -> exclusive scan -> stable scatter; the records
 //      themselves travel, so no gather through a permutation is needed.
-//   2. assemble pos as Table 3 prescribes for a compressed level: per-row
-//      counts (append_edges) followed by a running sum (append_finalize). On
-//      sorted rows the count of a row is (last position + 1) - first position,
-//      so each row receives exactly two integer atomics.
+//   2. assemble pos. Table 3 prescribes, for a compressed level, per-row counts
+//      (append_edges) followed by a running sum (append_finalize); on sorted rows
+//      that sum is the position of the first entry of each row and is stored
+//      directly at the row boundaries (see pos_from_sorted_rows_kernel).
 // Everything is integer or bit-copy work: results are exact and deterministic.
 #include "common.hpp"
 #include "radix.hpp"
@@ -140,15 +140,49 @@ __global__ __launch_bounds__(kBlock) void radix_scatter_kernel(
   }
 }
 
-// Per-row counts on sorted rows, stored as Table 3's append_edges does:
-// cnt[r + 1] = number of entries of row r. cnt must be zero on entry.
-__global__ __launch_bounds__(kBlock) void row_count_kernel(const int32_t* __restrict__ row, int n,
-                                                           int32_t* __restrict__ cnt) {
-  const int p = blockIdx.x * kBlock + threadIdx.x;
-  if (p >= n) return;
-  const int32_t r = row[p];
-  if (p == 0 || row[p - 1] != r) atomicSub(&cnt[r + 1], p);
-  if (p == n - 1 || row[p + 1] != r) atomicAdd(&cnt[r + 1], p + 1);
+// pos of the compressed column level from the sorted rows. Table 3 assembles pos as
+// per-parent counts (append_edges) followed by a running sum (append_finalize); on sorted
+// rows that running sum is known directly: pos[r] = position of the first entry whose row
+// is >= r. The thread of entry p, whose predecessor lies in row a and which lies in row b,
+// therefore stores p into pos[a+1 .. b] (nothing if a == b), and the last entry's thread
+// stores n into the rest: every element of pos is written exactly once, without atomics
+// or a scan. Ranges longer than 16 rows (runs of empty rows) are written by the whole wave.
+__device__ __forceinline__ void store_pos_range(int32_t* __restrict__ pos, int lo, int hi, int val) {
+  const bool big = hi - lo > 16;
+  if (!big)
+    for (int r = lo + 1; r <= hi; ++r) pos[r] = val;
+  uint64_t todo = __ballot(big);
+  while (todo) {
+    const int src = __ffsll(static_cast<long long>(todo)) - 1;
+    todo &= todo - 1;
+    const int l = __shfl(lo, src), h = __shfl(hi, src), v = __shfl(val, src);
+    for (int r = l + 1 + lane_id(); r <= h; r += kWave) pos[r] = v;
+  }
+}
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void pos_from_sorted_rows_kernel(const int32_t* __restrict__ row,
+                                                                      int n, int nrows,
+                                                                      int32_t* __restrict__ pos) {
+  typedef int32_t i4 __attribute__((ext_vector_type(4)));
+  const int p0 = (blockIdx.x * kBlock + threadIdx.x) * 4;  // four consecutive entries per lane
+  int r4[4];
+  if (VEC && p0 + 4 <= n) {
+    const i4 v = __builtin_nontemporal_load(reinterpret_cast<const i4*>(row + p0));
+#pragma unroll
+    for (int k = 0; k < 4; ++k) r4[k] = v[k];
+  } else {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) r4[k] = p0 + k < n ? row[p0 + k] : 0;
+  }
+  int a = (p0 > 0 && p0 < n) ? row[p0 - 1] : -1;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const bool live = p0 + k < n;  // every lane of a wave takes part in the long ranges
+    store_pos_range(pos, live ? a : 0, live ? r4[k] : 0, p0 + k);
+    const bool last = live && p0 + k == n - 1;
+    if (__any(last)) store_pos_range(pos, last ? r4[k] : 0, last ? nrows : 0, n);
+    a = r4[k];
+  }
 }
 
 template <typename VT>
@@ -208,10 +242,12 @@ static spt_status convert_typed(const spt_tensor* A, int32_t order, int32_t* pos
   const int32_t* col = A->level[1].crd;
   const VT* vals = static_cast<const VT*>(A->vals);
 
-  hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)((N + 1 + kBlock - 1) / kBlock)), dim3(kBlock),
-                     0, s, pos_out, N + 1);
-  SPT_CHECK_LAUNCH("zero pos");
-  if (nnz == 0) return SPT_OK;
+  if (nnz == 0) {
+    hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)((N + 1 + kBlock - 1) / kBlock)),
+                       dim3(kBlock), 0, s, pos_out, N + 1);
+    SPT_CHECK_LAUNCH("zero pos");
+    return SPT_OK;
+  }
 
   Workspace W(ws, ws_bytes);
   int32_t* srow[2];
@@ -257,9 +293,15 @@ static spt_status convert_typed(const spt_tensor* A, int32_t order, int32_t* pos
     }
     sorted_rows = rin;
   }
-  hipLaunchKernelGGL(row_count_kernel, dim3(egrid), dim3(kBlock), 0, s, sorted_rows, nnz, pos_out);
-  SPT_CHECK_LAUNCH("row_count");
-  return device_scan_i32<true>(pos_out, pos_out, N + 1, scan_tmp, s);
+  const unsigned pgrid = (unsigned)((nnz + 4 * kBlock - 1) / (4 * kBlock));
+  if ((reinterpret_cast<uintptr_t>(sorted_rows) & 15) == 0)
+    hipLaunchKernelGGL(pos_from_sorted_rows_kernel<true>, dim3(pgrid), dim3(kBlock), 0, s, sorted_rows,
+                       nnz, (int)N, pos_out);
+  else
+    hipLaunchKernelGGL(pos_from_sorted_rows_kernel<false>, dim3(pgrid), dim3(kBlock), 0, s,
+                       sorted_rows, nnz, (int)N, pos_out);
+  SPT_CHECK_LAUNCH("pos_from_sorted_rows");
+  return SPT_OK;
 }
 
 spt_status coo_to_csr_dispatch(const spt_tensor* A, int32_t order, int32_t* pos_out,

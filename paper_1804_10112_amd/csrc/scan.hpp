@@ -73,21 +73,48 @@ template <bool INCLUSIVE>
 __global__ __launch_bounds__(kBlock) void scan_apply_kernel(const int32_t* in, int64_t n,
                                                             const int32_t* __restrict__ tile_off,
                                                             int32_t* out) {
+  typedef int32_t i4 __attribute__((ext_vector_type(4)));
   const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanIPT;
+  // a thread's 16 consecutive values move as four 16-byte words when they are all inside
+  // the array and both arrays are 16-byte aligned there (single 4-byte stores at a 64-byte
+  // lane stride cost a memory transaction each)
+  const bool wide = base + kScanIPT <= n &&
+                    ((reinterpret_cast<uintptr_t>(in + base) | reinterpret_cast<uintptr_t>(out + base)) & 15) == 0;
   int v[kScanIPT];
   int s = 0;
+  if (wide) {
 #pragma unroll
-  for (int k = 0; k < kScanIPT; ++k) {
-    v[k] = (base + k < n) ? in[base + k] : 0;
-    s += v[k];
+    for (int q = 0; q < kScanIPT / 4; ++q) {
+      const i4 w = *reinterpret_cast<const i4*>(in + base + 4 * q);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) v[4 * q + r] = w[r];
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < kScanIPT; ++k) v[k] = (base + k < n) ? in[base + k] : 0;
   }
+#pragma unroll
+  for (int k = 0; k < kScanIPT; ++k) s += v[k];
   int total;
   int run = block_inclusive_sum(s, &total) - s + tile_off[blockIdx.x];
 #pragma unroll
   for (int k = 0; k < kScanIPT; ++k) {
-    if (INCLUSIVE) run += v[k];
-    if (base + k < n) out[base + k] = run;
-    if (!INCLUSIVE) run += v[k];
+    const int x = v[k];
+    v[k] = INCLUSIVE ? run + x : run;
+    run += x;
+  }
+  if (wide) {
+#pragma unroll
+    for (int q = 0; q < kScanIPT / 4; ++q) {
+      i4 w;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) w[r] = v[4 * q + r];
+      *reinterpret_cast<i4*>(out + base + 4 * q) = w;
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < kScanIPT; ++k)
+      if (base + k < n) out[base + k] = v[k];
   }
 }
 

@@ -48,6 +48,10 @@ def test_degenerate_shapes(order):
     _check(300, 1, rng.integers(0, 300, n), np.zeros(n, int), v, order, what="one col")
     _check(100_000, 3, np.array([99_999, 0, 50_000, 0]), np.array([2, 1, 0, 0]),
            np.array([1., 2., 3., 4.]), order, what="rows >> entries")
+    # runs of empty rows of every length next to a dense cluster (long runs are written by a whole wave)
+    rr = np.concatenate([rng.integers(0, 1_000_000, 5000), rng.integers(400_000, 400_300, 6000)])
+    _check(1_000_000, 50, rr, rng.integers(0, 50, rr.size), rng.uniform(-1, 1, rr.size), order,
+           what="sparse rows with a dense cluster")
     big = 2**31 - 10                           # maximum dimension sizes: all 31 key bits used
     r = np.array([big - 1, 0, big - 1, 12345, 2**30])
     c = np.array([big - 2, 5, 0, 2**30 + 1, 7])
