@@ -61,6 +61,14 @@ def lib():
         L.orc_plain_spdm_coo.argtypes = [i64, i64, vp, vp, vp, vp, i32, vp, i32]
         L.orc_ttm.restype = C.c_int64
         L.orc_ttm.argtypes = [vp, vp, C.c_int32, C.c_int64, C.c_int64, vp, vp, vp, vp]
+        L.orc_pack_csf.restype = C.c_int64
+        L.orc_pack_csf.argtypes = [vp] * 10
+        L.orc_pack_ell.restype = C.c_int64
+        L.orc_pack_ell.argtypes = [vp, vp, C.c_int64, vp, vp]
+        L.orc_dia_offsets.restype = C.c_int64
+        L.orc_dia_offsets.argtypes = [vp, vp, C.c_int64, vp]
+        L.orc_pack_dia.restype = None
+        L.orc_pack_dia.argtypes = [vp, vp, C.c_int64, vp, vp]
         L.orc_add.restype = C.c_int64
         L.orc_add.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp]
         L.orc_innerprod.restype = C.c_double
@@ -252,6 +260,47 @@ def add(bspec, cspec):
     if n < 0:
         raise ValueError("orc_add: unsupported operands")
     return [c[:n] for c in crd], v[:n], mag[:n]
+
+
+def pack_csf(spec):
+    """(pos0, crd0, pos1, crd1, pos2, crd2, vals) of the tensor packed as CSF."""
+    T = OTensor(spec)
+    n = max(lib().orc_count(T.ref), 1)
+    dims = np.asarray(spec.dims, np.int64)
+    i32 = lambda m: np.zeros(m, np.int32)
+    pos0, crd0, pos1, crd1, pos2, crd2 = i32(2), i32(n), i32(n + 1), i32(n), i32(n + 1), i32(n)
+    vals = np.zeros(n, np.float64)
+    counts = np.zeros(2, np.int64)
+    nnz = lib().orc_pack_csf(T.ref, _ptr(dims), _ptr(pos0), _ptr(crd0), _ptr(pos1), _ptr(crd1),
+                             _ptr(pos2), _ptr(crd2), _ptr(vals), _ptr(counts))
+    if nnz < 0:
+        raise ValueError("orc_pack_csf: unsupported tensor")
+    n0, n1 = int(counts[0]), int(counts[1])
+    return pos0, crd0[:n0], pos1[:n0 + 1], crd1[:n1], pos2[:n1 + 1], crd2[:nnz], vals[:nnz]
+
+
+def pack_ell(spec, W):
+    """(crd[W, N], vals[W, N], longest row) of the matrix packed as ELL with W slots."""
+    T = OTensor(spec)
+    N = spec.dims[0]
+    dims = np.asarray(spec.dims, np.int64)
+    crd = np.zeros((W, N), np.int32)
+    vals = np.zeros((W, N), np.float64)
+    longest = lib().orc_pack_ell(T.ref, _ptr(dims), W, _ptr(crd), _ptr(vals))
+    return crd, vals, int(longest)
+
+
+def pack_dia(spec):
+    """(offsets[K], vals[K, N]) of the matrix packed as DIA."""
+    T = OTensor(spec)
+    N, M = spec.dims
+    dims = np.asarray(spec.dims, np.int64)
+    offsets = np.zeros(N + M, np.int32)
+    K = int(lib().orc_dia_offsets(T.ref, _ptr(dims), len(offsets), _ptr(offsets)))
+    offsets = np.ascontiguousarray(offsets[:K])
+    vals = np.zeros((K, N), np.float64)
+    lib().orc_pack_dia(T.ref, _ptr(dims), K, _ptr(offsets), _ptr(vals))
+    return offsets, vals
 
 
 def coo_to_csr(nrows, row, col, vals, order=0):

@@ -400,6 +400,100 @@ int64_t orc_add(const orc_tensor* B, const orc_tensor* C, const int64_t* dims, i
   return n;
 }
 
+int64_t orc_pack_csf(const orc_tensor* B, const int64_t* dims, int32_t* pos0, int32_t* crd0,
+                     int32_t* pos1, int32_t* crd1, int32_t* pos2, int32_t* crd2, double* vals,
+                     int64_t* counts) {
+  long double space = (long double)dims[0] * (long double)dims[1] * (long double)dims[2];
+  if (B->order != 3 || space >= 9.0e18L) return -1;
+  int64_t n;
+  kv_pair* e = linearise(B, dims, &n);
+  int64_t n0 = 0, n1 = 0; /* entries appended to level 0 and level 1 so far */
+  int64_t pi = -1, pj = -1;
+  for (int64_t p = 0; p < n; ++p) {
+    int64_t k = e[p].key % dims[2], j = (e[p].key / dims[2]) % dims[1],
+            i = e[p].key / (dims[2] * dims[1]);
+    int new_slice = p == 0 || i != pi;
+    if (new_slice) {
+      crd0[n0] = (int32_t)i; /* append_coord on level 0 */
+      pos1[n0] = (int32_t)n1; /* its segment of level 1 starts here */
+      ++n0;
+    }
+    if (new_slice || j != pj) {
+      crd1[n1] = (int32_t)j;
+      pos2[n1] = (int32_t)p;
+      ++n1;
+    }
+    crd2[p] = (int32_t)k;
+    vals[p] = e[p].val;
+    pi = i;
+    pj = j;
+  }
+  pos0[0] = 0;
+  pos0[1] = (int32_t)n0; /* append_edges / append_finalize: each segment ends where the next starts */
+  pos1[n0] = (int32_t)n1;
+  pos2[n1] = (int32_t)n;
+  counts[0] = n0;
+  counts[1] = n1;
+  free(e);
+  return n;
+}
+
+int64_t orc_pack_ell(const orc_tensor* A, const int64_t* dims, int64_t W, int32_t* crd,
+                     double* vals) {
+  int64_t N = dims[0], M = dims[1], n;
+  for (int64_t q = 0; q < W * N; ++q) {
+    crd[q] = -1;
+    vals[q] = 0.0;
+  }
+  kv_pair* e = linearise(A, dims, &n);
+  int64_t longest = 0, row = -1, k = 0;
+  for (int64_t p = 0; p < n; ++p) {
+    int64_t i = e[p].key / M, j = e[p].key % M;
+    k = i == row ? k + 1 : 0; /* slot = rank of the entry inside its row */
+    row = i;
+    if (k < W) {
+      crd[k * N + i] = (int32_t)j;
+      vals[k * N + i] = e[p].val;
+    }
+    if (k + 1 > longest) longest = k + 1;
+  }
+  free(e);
+  return longest;
+}
+
+static int i64_cmp(const void* a, const void* b) {
+  int64_t x = *(const int64_t*)a, y = *(const int64_t*)b;
+  return x < y ? -1 : (x > y ? 1 : 0);
+}
+int64_t orc_dia_offsets(const orc_tensor* A, const int64_t* dims, int64_t cap, int32_t* offsets) {
+  int64_t M = dims[1], n;
+  kv_pair* e = linearise(A, dims, &n);
+  int64_t* d = (int64_t*)malloc(sizeof(int64_t) * (size_t)(n > 0 ? n : 1));
+  for (int64_t p = 0; p < n; ++p) d[p] = e[p].key % M - e[p].key / M;
+  qsort(d, (size_t)n, sizeof(int64_t), i64_cmp);
+  int64_t K = 0;
+  for (int64_t p = 0; p < n; ++p)
+    if (p == 0 || d[p] != d[p - 1]) {
+      if (K < cap) offsets[K] = (int32_t)d[p];
+      ++K;
+    }
+  free(d);
+  free(e);
+  return K;
+}
+void orc_pack_dia(const orc_tensor* A, const int64_t* dims, int64_t K, const int32_t* offsets,
+                  double* vals) {
+  int64_t N = dims[0], M = dims[1], n;
+  for (int64_t q = 0; q < K * N; ++q) vals[q] = 0.0;
+  kv_pair* e = linearise(A, dims, &n);
+  for (int64_t p = 0; p < n; ++p) {
+    int64_t i = e[p].key / M, j = e[p].key % M;
+    for (int64_t d = 0; d < K; ++d) /* locate the diagonal, then insert */
+      if (offsets[d] == j - i) vals[d * N + i] = e[p].val;
+  }
+  free(e);
+}
+
 /* Stable bottom-up merge sort of an index permutation by one or two int32 keys. */
 static int key_less(const int32_t* k0, const int32_t* k1, int64_t a, int64_t b) {
   if (k0[a] != k0[b]) return k0[a] < k0[b];

@@ -97,6 +97,32 @@ double orc_innerprod(const orc_tensor* B, const orc_tensor* C, const int64_t* di
 int64_t orc_add(const orc_tensor* B, const orc_tensor* C, const int64_t* dims, int64_t cap,
                 int32_t* const* out_crd, double* out_v, double* out_mag);
 
+/* Packing a tensor (any format) into CSF, ELL or DIA, Section 3.4: the entries are walked,
+ * ordered by linearised coordinate, and appended (CSF, ELL) or inserted (DIA) into the
+ * target's levels. Values are returned as double (exact for fp32 and fp64 sources).
+ *
+ * orc_pack_csf, 3rd order: level k has pos_k and crd_k (pos0 has 2 entries); a coordinate is
+ * appended to level 0 / 1 when it differs from the previous entry's (i) / (i,j), every entry
+ * appends its k to level 2; append_edges closes a parent's segment, so pos holds running
+ * sums. counts[0], counts[1] = slices, fibres. Arrays need capacity nnz (+1 for pos).
+ * Returns nnz, or -1 on overflow of the linearised coordinate.
+ *
+ * orc_pack_ell: cell (k, i) at k*N + i holds the k-th stored entry of row i (columns
+ * ascending); unused cells have crd -1 and value 0. Rows longer than W lose their tail.
+ * Returns the longest row.
+ *
+ * orc_dia_offsets: the distinct values of col - row, ascending (at most cap are written);
+ * returns their number K. orc_pack_dia: cell (d, i) at d*N + i = the entry of row i on
+ * diagonal offsets[d], zero where none is stored (coordinates unique). */
+int64_t orc_pack_csf(const orc_tensor* B, const int64_t* dims, int32_t* pos0, int32_t* crd0,
+                     int32_t* pos1, int32_t* crd1, int32_t* pos2, int32_t* crd2, double* vals,
+                     int64_t* counts);
+int64_t orc_pack_ell(const orc_tensor* A, const int64_t* dims, int64_t W, int32_t* crd,
+                     double* vals);
+int64_t orc_dia_offsets(const orc_tensor* A, const int64_t* dims, int64_t cap, int32_t* offsets);
+void orc_pack_dia(const orc_tensor* A, const int64_t* dims, int64_t K, const int32_t* offsets,
+                  double* vals);
+
 /* COO -> CSR index assembly. order 0: by (row,col), ties keep input order;
  * order 1: by row, input order kept inside a row. pos via Table 3's
  * append_init / append_edges / append_finalize. perm_out[n] = input index of

@@ -457,3 +457,89 @@ def test_add_third_order_vs_dense_and_closed_forms():
     # CSF operands walk to the same result
     (fi, fj, fk), fv, _ = oracle.add(wl.csf3_from_sorted_coo(dims, bi, bj, bk, bv), c)
     assert np.array_equal(fi, oi) and np.array_equal(fk, ok) and np.array_equal(fv, v)
+
+
+# ------------------------------------------------------------------ packing into CSF / ELL / DIA
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_pack_csf_roundtrip_and_independent_builder(dtype):
+    dims = (6, 5, 7)
+    ci, cj, ck, v = wl.random_coo3_entries(dims, 120, seed=81, dtype=dtype, skew=1.5)
+    perm = np.random.default_rng(0).permutation(len(v))                 # the packer orders the entries itself
+    shuffled = wl.coo3_spec(dims, ci[perm], cj[perm], ck[perm], v[perm], ordered=False)
+    pos0, crd0, pos1, crd1, pos2, crd2, vals = oracle.pack_csf(shuffled)
+    # independent construction with numpy's unique
+    assert np.array_equal(crd0, np.unique(ci))
+    fib = np.unique(ci.astype(np.int64) * 5 + cj)
+    assert np.array_equal(crd1, fib % 5) and len(crd1) == len(fib)
+    assert list(pos0) == [0, len(crd0)] and pos1[-1] == len(crd1) and pos2[-1] == len(v)
+    assert np.array_equal(np.diff(pos1), np.bincount(np.searchsorted(crd0, fib // 5), minlength=len(crd0)))
+    assert np.array_equal(crd2, ck) and np.array_equal(vals, v.astype(np.float64))
+    # walking the packed levels (Table 2 interpreter) gives back the sorted entries
+    packed = wl.csf3_spec(dims, pos0, crd0, pos1, crd1, pos2, crd2, vals.astype(dtype))
+    c, w = oracle.to_coo(packed)
+    assert np.array_equal(c[0], ci) and np.array_equal(c[1], cj) and np.array_equal(c[2], ck)
+    assert np.array_equal(w, v.astype(np.float64))
+    # and the generator's own numpy builder agrees array by array
+    ref = wl.csf3_from_sorted_coo(dims, ci, cj, ck, v)
+    for lv, (p_, c_) in zip(ref.levels, ((pos0, crd0), (pos1, crd1), (pos2, crd2))):
+        assert np.array_equal(lv.pos, p_) and np.array_equal(lv.crd, c_)
+    e = np.zeros(0, int)
+    out = oracle.pack_csf(wl.coo3_spec(dims, e, e, e, np.zeros(0, dtype)))
+    assert list(out[0]) == [0, 0] and list(out[2]) == [0] and list(out[4]) == [0]
+
+
+def test_pack_ell_vs_rows_and_roundtrip():
+    N, M = 30, 40
+    r, c, v = wl.random_coo_entries(N, M, 300, seed=82, dtype=np.float64)
+    coo = wl.coo_spec(N, M, r, c, v)
+    lens = np.bincount(r, minlength=N)
+    W = int(lens.max())
+    crd, vals, longest = oracle.pack_ell(coo, W)
+    assert longest == W
+    for i in range(N):                                                   # row by row, from the definition
+        cols, vs = c[r == i], v[r == i]
+        assert np.array_equal(crd[:len(cols), i], cols) and np.all(crd[len(cols):, i] == -1)
+        assert np.array_equal(vals[:len(cols), i], vs) and np.all(vals[len(cols):, i] == 0)
+    c2, w2 = oracle.to_coo(wl.ell_spec(N, M, crd, vals))                  # walk of the ELL levels
+    order = np.lexsort((c2[1], c2[0]))
+    assert np.array_equal(c2[0][order], r) and np.array_equal(c2[1][order], c) and np.array_equal(w2[order], v)
+    x = wl.dense_vector(M, 5, np.float64)
+    assert np.allclose(oracle.spmv(wl.ell_spec(N, M, crd, vals), x)[0], oracle.spmv(coo, x)[0], atol=1e-14)
+    # too few slots: the tails of long rows are dropped, the longest row is still reported
+    crd3, vals3, longest3 = oracle.pack_ell(coo, 3)
+    assert longest3 == W and np.count_nonzero(crd3 >= 0) == int(np.minimum(lens, 3).sum())
+    # CSR source walks to the same cells
+    crd4, vals4, _ = oracle.pack_ell(wl.csr_from_sorted_coo(N, M, r, c, v), W)
+    assert np.array_equal(crd4, crd) and np.array_equal(vals4, vals)
+
+
+def test_pack_dia_vs_scipy():
+    N, M = 25, 31
+    rng = np.random.default_rng(83)
+    offs = np.array([-20, -3, 0, 1, 7, 29])
+    r, c = [], []
+    for o in offs:                                                        # a banded matrix with holes
+        i = np.arange(max(0, -o), min(N, M - o))
+        i = i[rng.random(len(i)) < 0.7]
+        r.append(i)
+        c.append(i + o)
+    r, c = np.concatenate(r), np.concatenate(c)
+    order = np.lexsort((c, r))
+    r, c = r[order], c[order]
+    v = rng.uniform(-1, 1, len(r))
+    coo = wl.coo_spec(N, M, r, c, v)
+    offsets, vals = oracle.pack_dia(coo)
+    assert np.array_equal(offsets, offs)
+    D = sp.dia_matrix(sp.coo_matrix((v, (r, c)), shape=(N, M)))           # scipy: data[d, j] = A[j - off, j]
+    so = np.argsort(D.offsets)
+    assert np.array_equal(D.offsets[so], offsets)
+    for d, o in enumerate(offsets):
+        for i in range(N):
+            j = i + o
+            want = D.data[so[d], j] if 0 <= j < M and j < D.data.shape[1] else 0.0
+            assert vals[d, i] == want
+    c2, w2 = oracle.to_coo(wl.dia_spec(N, M, offsets, vals))              # walk of (dense, range, offset)
+    dense = np.zeros((N, M))
+    dense[c2[0], c2[1]] = w2
+    assert np.array_equal(dense, sp.coo_matrix((v, (r, c)), shape=(N, M)).toarray())
