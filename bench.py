@@ -66,7 +66,7 @@ def build_items(args):
 
     def on(name):
         if want is None:
-            return name not in ("x16", "n2", "n3")   # these groups run only on request
+            return name not in ("x16", "n2", "n3", "n4")   # these groups run only on request
         return name in want or name.split("_")[0] in want
 
     # ---- config 2: banded, 7 diagonals, fp64: DIA and CSR
@@ -269,7 +269,58 @@ def build_items(args):
             items.append(Item(f"n3_add_{fmt}", run, nc, byt))
         keep.extend([q0, q1, qpos, qv])
         del c4
+    # ---- on request (--only n4): packers. Config 5's COO -> CSF, config 3's CSR -> ELL,
+    #      config 2's matrix (as COO) -> DIA offsets + values
+    if on("n4"):
+        dims = tuple(max(16, int(d * s)) for d in (100_000, 80_000, 50_000))
+        c5 = wl.config5(dims=dims, nnz=max(1000, int(50_000_000 * s)))
+        nnz = c5["nnz"]
+        nfib, nsl = len(c5["csf"].levels[1].crd), len(c5["csf"].levels[0].crd)
+        Bc = spt.DeviceTensor(c5["coo"])
+        i32 = lambda m: torch.empty(m, dtype=torch.int32, device=dev)
+        pk = [i32(2), i32(nnz), i32(nnz + 1), i32(nnz), i32(nnz + 1), i32(nnz)]
+        pv = torch.empty(nnz, dtype=torch.float32, device=dev)
+        pc = torch.zeros(2, dtype=torch.int64, device=dev)
+        wp = Bc.workspace(spt.SPT_OP_TO_CSF)
+        keep.extend([Bc, pk, pv, pc, wp])
+        items.append(Item("n4_coo3_to_csf", lambda: spt.spt_coo3_to_csf(Bc, *pk, pv, pc, wp), 0,
+                          16 * nnz + 8 * nnz + 8 * nnz + 8 * nfib + 8 * nsl,
+                          "(i,j) read twice (count, fill), k and values copied"))
+        del c5
+        c3 = wl.config3(N=max(64, int(1_000_000 * s)))
+        N3, W3, nnz3 = c3["csr"].dims[0], c3["W"], c3["nnz"]
+        Ac = spt.DeviceTensor(c3["csr"])
+        ec = i32(W3 * N3)
+        ev = torch.empty(W3 * N3, dtype=torch.float32, device=dev)
+        el = torch.zeros(1, dtype=torch.int32, device=dev)
+        keep.extend([Ac, ec, ev, el])
+        items.append(Item("n4_csr_to_ell", lambda: spt.spt_to_ell(Ac, W3, ec, ev, el, None), 0,
+                          8 * nnz3 + 4 * (N3 + 1) + 8 * W3 * N3))
+        del c3
+        c2 = wl.config2(N=max(64, int(2_000_000 * s)))
+        cc, cv = oracle_free_coo(c2["csr"])
+        N2 = c2["csr"].dims[0]
+        Ad = spt.DeviceTensor(wl.coo_spec(N2, N2, cc[0], cc[1], cv))
+        offs = i32(64)
+        Kd = torch.zeros(1, dtype=torch.int64, device=dev)
+        dv = torch.empty(7 * N2, dtype=torch.float64, device=dev)
+        wd = Ad.workspace(spt.SPT_OP_DIA_OFFSETS)
+        keep.extend([Ad, offs, Kd, dv, wd])
+        items.append(Item("n4_coo_dia_offsets", lambda: spt.spt_coo_dia_offsets(Ad, offs, 64, Kd, wd), 0,
+                          8 * len(cv) + 16 * 2 * N2))
+        items[-1].run()
+        torch.cuda.synchronize()
+        items.append(Item("n4_coo_to_dia", lambda: spt.spt_coo_to_dia(Ad, 7, offs, dv), 0,
+                          16 * len(cv) + 2 * 8 * 7 * N2, "zero fill + scattered values"))
+        del c2
     return items, cpu_jobs, keep
+
+
+def oracle_free_coo(csr_spec):
+    """(rows, cols), values of a CSR spec, expanded with numpy (input preparation only)."""
+    pos = np.asarray(csr_spec.levels[1].pos)
+    rows = np.repeat(np.arange(len(pos) - 1, dtype=np.int32), np.diff(pos))
+    return (rows, np.asarray(csr_spec.levels[1].crd)), csr_spec.vals
 
 
 def measure_ceilings():

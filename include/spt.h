@@ -71,7 +71,10 @@ typedef enum {
   SPT_OP_TTV = 2,
   SPT_OP_MTTKRP = 3,
   SPT_OP_INNERPROD = 4,
-  SPT_OP_TTM = 5
+  SPT_OP_TTM = 5,
+  SPT_OP_TO_CSF = 6,
+  SPT_OP_TO_ELL = 7,
+  SPT_OP_DIA_OFFSETS = 8
 } spt_op;
 
 /*
@@ -229,6 +232,40 @@ spt_status spt_ttm(const spt_tensor* B, const void* C, int32_t K, int32_t* out_c
  */
 spt_status spt_innerprod(const spt_tensor* B, const spt_tensor* C, void* alpha_out, void* ws,
                          size_t ws_bytes, void* stream);
+
+/*
+ * Packing ordered COO into the other formats (Section 3.4: a tensor is assembled level by
+ * level, by appends where coordinates arrive in order and by inserts otherwise). Index
+ * outputs are exact, values are copied bit for bit. Coordinates are assumed unique.
+ *
+ * spt_coo3_to_csf: B = COO3, every level ordered. Output = the three compressed levels of
+ *   CSF: pos0[2], crd0 (capacity nnz), pos1 (nnz+1), crd1 (nnz), pos2 (nnz+1), crd2 (nnz),
+ *   vals_out (nnz). counts_dev[2] (device int64) receives the number of entries of level 0
+ *   (slices) and level 1 (fibres); pos1 holds slices+1 and pos2 fibres+1 valid entries.
+ *   Workspace: SPT_OP_TO_CSF.
+ *
+ * spt_to_ell: A = COO matrix with both levels ordered, or CSR. W slots per row: cell (k, i)
+ *   at k*N + i of crd_out / vals_out (W*N entries each) receives the k-th entry of row i,
+ *   unused cells column -1 and value 0. *longest_dev (device int32) receives the longest
+ *   row; if it exceeds W the entries beyond slot W-1 were left out. Workspace: SPT_OP_TO_ELL
+ *   (needed for COO only).
+ *
+ * spt_coo_dia_offsets: A = COO matrix (any order). The distinct values of col - row,
+ *   ascending, go to offsets_out (at most cap of them); *K_dev (device int64) receives their
+ *   number. Workspace: SPT_OP_DIA_OFFSETS.
+ * spt_coo_to_dia: vals_out[K*N], cell (d, i) at d*N + i = the entry of row i on diagonal
+ *   offsets[d] (device array, ascending, K entries), zero where none is stored; entries on
+ *   other diagonals are skipped. Needs no workspace.
+ */
+spt_status spt_coo3_to_csf(const spt_tensor* B, int32_t* pos0, int32_t* crd0, int32_t* pos1,
+                           int32_t* crd1, int32_t* pos2, int32_t* crd2, void* vals_out,
+                           int64_t* counts_dev, void* ws, size_t ws_bytes, void* stream);
+spt_status spt_to_ell(const spt_tensor* A, int32_t W, int32_t* crd_out, void* vals_out,
+                      int32_t* longest_dev, void* ws, size_t ws_bytes, void* stream);
+spt_status spt_coo_dia_offsets(const spt_tensor* A, int32_t* offsets_out, int64_t cap,
+                               int64_t* K_dev, void* ws, size_t ws_bytes, void* stream);
+spt_status spt_coo_to_dia(const spt_tensor* A, int32_t K, const int32_t* offsets, void* vals_out,
+                          void* stream);
 
 /*
  * A = B + C with a sparse result: matrix addition on COO or CSR (Section 5.2) and 3rd-order

@@ -18,6 +18,7 @@ _lib = None
 
 SPT_OK, SPT_ERR_INVALID_ARG, SPT_ERR_UNSUPPORTED, SPT_ERR_WORKSPACE, SPT_ERR_DEVICE = range(5)
 SPT_OP_SPMV, SPT_OP_COO_TO_CSR, SPT_OP_TTV, SPT_OP_MTTKRP, SPT_OP_INNERPROD, SPT_OP_TTM = range(6)
+SPT_OP_TO_CSF, SPT_OP_TO_ELL, SPT_OP_DIA_OFFSETS = 6, 7, 8
 SPT_ORDER_ROW_COL, SPT_ORDER_ROW_STABLE = 0, 1
 SPT_ORDERED, SPT_UNIQUE = 1, 2
 SPT_F32, SPT_F64 = 0, 1
@@ -25,7 +26,8 @@ SPT_F32, SPT_F64 = 0, 1
 SYMBOLS = ["spt_spmv", "spt_coo_to_csr", "spt_ttv", "spt_mttkrp", "spt_workspace_bytes",
            "spt_last_error", "spt_version", "spt_probe_read", "spt_probe_gather",
            "spt_spmv_sparse_x", "spt_spdm", "spt_innerprod", "spt_ttm",
-           "spt_add", "spt_add_workspace_bytes"]
+           "spt_add", "spt_add_workspace_bytes", "spt_coo3_to_csf", "spt_to_ell",
+           "spt_coo_dia_offsets", "spt_coo_to_dia"]
 
 
 class SptLevel(C.Structure):
@@ -69,6 +71,14 @@ def lib():
         L.spt_ttv.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.spt_mttkrp.restype = i32
         L.spt_mttkrp.argtypes = [vp, vp, vp, i32, vp, vp, sz, vp]
+        L.spt_coo3_to_csf.restype = i32
+        L.spt_coo3_to_csf.argtypes = [vp] * 10 + [sz, vp]
+        L.spt_to_ell.restype = i32
+        L.spt_to_ell.argtypes = [vp, i32, vp, vp, vp, vp, sz, vp]
+        L.spt_coo_dia_offsets.restype = i32
+        L.spt_coo_dia_offsets.argtypes = [vp, vp, C.c_int64, vp, vp, sz, vp]
+        L.spt_coo_to_dia.restype = i32
+        L.spt_coo_to_dia.argtypes = [vp, i32, vp, vp, vp]
         L.spt_add.restype = i32
         L.spt_add.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.spt_add_workspace_bytes.restype = sz
@@ -186,6 +196,27 @@ def spt_ttm(B, Cm, K, out_crd0, out_crd1, out_vals, out_nfib_dev, ws=None, strea
     p, n = _ws(ws)
     _check(lib().spt_ttm(_desc(B), _p(Cm), K, _p(out_crd0), _p(out_crd1), _p(out_vals),
                          _p(out_nfib_dev), p, n, _stream(stream)))
+
+
+def spt_coo3_to_csf(B, pos0, crd0, pos1, crd1, pos2, crd2, vals_out, counts_dev, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(lib().spt_coo3_to_csf(_desc(B), _p(pos0), _p(crd0), _p(pos1), _p(crd1), _p(pos2), _p(crd2),
+                                 _p(vals_out), _p(counts_dev), p, n, _stream(stream)))
+
+
+def spt_to_ell(A, W, crd_out, vals_out, longest_dev, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(lib().spt_to_ell(_desc(A), W, _p(crd_out), _p(vals_out), _p(longest_dev), p, n,
+                            _stream(stream)))
+
+
+def spt_coo_dia_offsets(A, offsets_out, cap, K_dev, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(lib().spt_coo_dia_offsets(_desc(A), _p(offsets_out), cap, _p(K_dev), p, n, _stream(stream)))
+
+
+def spt_coo_to_dia(A, K, offsets, vals_out, stream=None):
+    _check(lib().spt_coo_to_dia(_desc(A), K, _p(offsets), _p(vals_out), _stream(stream)))
 
 
 def spt_add(B, Ct, out_pos, out_crd0, out_crd1, out_crd2, out_vals, out_nnz_dev, ws=None, stream=None):

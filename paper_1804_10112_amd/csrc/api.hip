@@ -53,6 +53,19 @@ spt_status add_dispatch(Format f, const spt_tensor* B, const spt_tensor* C, int3
                         int64_t* out_nnz, void* ws, size_t ws_bytes, hipStream_t s);
 size_t add_workspace(Format f, const spt_tensor* B, const spt_tensor* C);
 
+spt_status pack_csf_dispatch(const spt_tensor* B, int32_t* pos0, int32_t* crd0, int32_t* pos1,
+                             int32_t* crd1, int32_t* pos2, int32_t* crd2, void* vals_out,
+                             int64_t* counts, void* ws, size_t ws_bytes, hipStream_t s);
+size_t pack_csf_workspace(int64_t nnz);
+spt_status pack_ell_dispatch(Format f, const spt_tensor* A, int32_t W, int32_t* crd_out, void* vals_out,
+                             int32_t* longest, void* ws, size_t ws_bytes, hipStream_t s);
+size_t pack_ell_workspace(Format f, const spt_tensor* A);
+spt_status dia_offsets_dispatch(const spt_tensor* A, int32_t* offsets_out, int64_t cap, int64_t* K_dev,
+                                void* ws, size_t ws_bytes, hipStream_t s);
+size_t dia_offsets_workspace(const spt_tensor* A);
+spt_status pack_dia_dispatch(const spt_tensor* A, int32_t K, const int32_t* offsets, void* vals_out,
+                             hipStream_t s);
+
 static bool is(const spt_level& L, int kind) { return L.kind == kind; }
 static bool unique(const spt_level& L) { return (L.flags & SPT_UNIQUE) != 0; }
 
@@ -334,6 +347,61 @@ spt_status spt_innerprod(const spt_tensor* B, const spt_tensor* C, void* alpha_o
   return innerprod_dispatch(fb, B, C, alpha_out, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
+spt_status spt_coo3_to_csf(const spt_tensor* B, int32_t* pos0, int32_t* crd0, int32_t* pos1,
+                           int32_t* crd1, int32_t* pos2, int32_t* crd2, void* vals_out,
+                           int64_t* counts_dev, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  Format f = recognize(B);
+  if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
+  if (f != Format::COO3) return fail(SPT_ERR_UNSUPPORTED, "coo3_to_csf: B must be COO3");
+  for (int k = 0; k < 3; ++k)
+    if (!(B->level[k].flags & SPT_ORDERED))
+      return fail(SPT_ERR_UNSUPPORTED, "coo3_to_csf: every level of B must be ordered");
+  if (!pos0 || !crd0 || !pos1 || !crd1 || !pos2 || !crd2 || !vals_out || !counts_dev)
+    return fail(SPT_ERR_INVALID_ARG, "coo3_to_csf: null output");
+  return pack_csf_dispatch(B, pos0, crd0, pos1, crd1, pos2, crd2, vals_out, counts_dev, ws, ws_bytes,
+                           static_cast<hipStream_t>(stream));
+}
+
+spt_status spt_to_ell(const spt_tensor* A, int32_t W, int32_t* crd_out, void* vals_out,
+                      int32_t* longest_dev, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  Format f = recognize(A);
+  if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
+  if (f != Format::COO2 && f != Format::CSR)
+    return fail(SPT_ERR_UNSUPPORTED, "to_ell: A must be a COO matrix or CSR");
+  if (f == Format::COO2 && !(A->level[0].flags & A->level[1].flags & SPT_ORDERED))
+    return fail(SPT_ERR_UNSUPPORTED, "to_ell: both levels of a COO source must be ordered");
+  if (W < 0) return fail(SPT_ERR_INVALID_ARG, "to_ell: W = %d is negative", W);
+  if (!longest_dev || (W > 0 && (!crd_out || !vals_out)))
+    return fail(SPT_ERR_INVALID_ARG, "to_ell: null output");
+  return pack_ell_dispatch(f, A, W, crd_out, vals_out, longest_dev, ws, ws_bytes,
+                           static_cast<hipStream_t>(stream));
+}
+
+spt_status spt_coo_dia_offsets(const spt_tensor* A, int32_t* offsets_out, int64_t cap,
+                               int64_t* K_dev, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  Format f = recognize(A);
+  if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
+  if (f != Format::COO2) return fail(SPT_ERR_UNSUPPORTED, "coo_dia_offsets: A must be a COO matrix");
+  if (cap < 0 || !K_dev || (cap > 0 && !offsets_out))
+    return fail(SPT_ERR_INVALID_ARG, "coo_dia_offsets: null output or negative capacity");
+  return dia_offsets_dispatch(A, offsets_out, cap, K_dev, ws, ws_bytes,
+                              static_cast<hipStream_t>(stream));
+}
+
+spt_status spt_coo_to_dia(const spt_tensor* A, int32_t K, const int32_t* offsets, void* vals_out,
+                          void* stream) {
+  clear_error();
+  Format f = recognize(A);
+  if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
+  if (f != Format::COO2) return fail(SPT_ERR_UNSUPPORTED, "coo_to_dia: A must be a COO matrix");
+  if (K < 0 || (K > 0 && (!offsets || !vals_out)))
+    return fail(SPT_ERR_INVALID_ARG, "coo_to_dia: null array or negative K");
+  return pack_dia_dispatch(A, K, offsets, vals_out, static_cast<hipStream_t>(stream));
+}
+
 // Common operand checks of spt_add; returns the shared format or sets the error.
 static spt_status add_operands(const spt_tensor* B, const spt_tensor* C, Format* f_out) {
   Format fb = recognize(B);
@@ -402,6 +470,15 @@ size_t spt_workspace_bytes(int32_t op, const spt_tensor* T, int32_t J) {
       break;
     case SPT_OP_TTM:
       n = (f == Format::COO3 || f == Format::CSF3) ? ttm_workspace(f, T, J) : 0;
+      break;
+    case SPT_OP_TO_CSF:
+      n = f == Format::COO3 ? pack_csf_workspace(T->nvals) : 0;
+      break;
+    case SPT_OP_TO_ELL:
+      n = (f == Format::COO2 || f == Format::CSR) ? pack_ell_workspace(f, T) : 0;
+      break;
+    case SPT_OP_DIA_OFFSETS:
+      n = f == Format::COO2 ? dia_offsets_workspace(T) : 0;
       break;
     case SPT_OP_INNERPROD:
       n = (f == Format::COO3 || f == Format::COO2) ? innerprod_workspace(T->nvals) : 0;

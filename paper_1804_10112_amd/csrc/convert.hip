@@ -12,6 +12,7 @@
 // Everything is integer or bit-copy work: results are exact and deterministic.
 #include "common.hpp"
 #include "radix.hpp"
+#include "rows.hpp"
 #include "scan.hpp"
 
 namespace spt {
@@ -140,51 +141,6 @@ __global__ __launch_bounds__(kBlock) void radix_scatter_kernel(
   }
 }
 
-// pos of the compressed column level from the sorted rows. Table 3 assembles pos as
-// per-parent counts (append_edges) followed by a running sum (append_finalize); on sorted
-// rows that running sum is known directly: pos[r] = position of the first entry whose row
-// is >= r. The thread of entry p, whose predecessor lies in row a and which lies in row b,
-// therefore stores p into pos[a+1 .. b] (nothing if a == b), and the last entry's thread
-// stores n into the rest: every element of pos is written exactly once, without atomics
-// or a scan. Ranges longer than 16 rows (runs of empty rows) are written by the whole wave.
-__device__ __forceinline__ void store_pos_range(int32_t* __restrict__ pos, int lo, int hi, int val) {
-  const bool big = hi - lo > 16;
-  if (!big)
-    for (int r = lo + 1; r <= hi; ++r) pos[r] = val;
-  uint64_t todo = __ballot(big);
-  while (todo) {
-    const int src = __ffsll(static_cast<long long>(todo)) - 1;
-    todo &= todo - 1;
-    const int l = __shfl(lo, src), h = __shfl(hi, src), v = __shfl(val, src);
-    for (int r = l + 1 + lane_id(); r <= h; r += kWave) pos[r] = v;
-  }
-}
-template <bool VEC>
-__global__ __launch_bounds__(kBlock) void pos_from_sorted_rows_kernel(const int32_t* __restrict__ row,
-                                                                      int n, int nrows,
-                                                                      int32_t* __restrict__ pos) {
-  typedef int32_t i4 __attribute__((ext_vector_type(4)));
-  const int p0 = (blockIdx.x * kBlock + threadIdx.x) * 4;  // four consecutive entries per lane
-  int r4[4];
-  if (VEC && p0 + 4 <= n) {
-    const i4 v = __builtin_nontemporal_load(reinterpret_cast<const i4*>(row + p0));
-#pragma unroll
-    for (int k = 0; k < 4; ++k) r4[k] = v[k];
-  } else {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) r4[k] = p0 + k < n ? row[p0 + k] : 0;
-  }
-  int a = (p0 > 0 && p0 < n) ? row[p0 - 1] : -1;
-#pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    const bool live = p0 + k < n;  // every lane of a wave takes part in the long ranges
-    store_pos_range(pos, live ? a : 0, live ? r4[k] : 0, p0 + k);
-    const bool last = live && p0 + k == n - 1;
-    if (__any(last)) store_pos_range(pos, last ? r4[k] : 0, last ? nrows : 0, n);
-    a = r4[k];
-  }
-}
-
 template <typename VT>
 __global__ __launch_bounds__(kBlock) void copy_entries_kernel(int n, const int32_t* __restrict__ col_in,
                                                               const VT* __restrict__ val_in,
@@ -293,14 +249,8 @@ static spt_status convert_typed(const spt_tensor* A, int32_t order, int32_t* pos
     }
     sorted_rows = rin;
   }
-  const unsigned pgrid = (unsigned)((nnz + 4 * kBlock - 1) / (4 * kBlock));
-  if ((reinterpret_cast<uintptr_t>(sorted_rows) & 15) == 0)
-    hipLaunchKernelGGL(pos_from_sorted_rows_kernel<true>, dim3(pgrid), dim3(kBlock), 0, s, sorted_rows,
-                       nnz, (int)N, pos_out);
-  else
-    hipLaunchKernelGGL(pos_from_sorted_rows_kernel<false>, dim3(pgrid), dim3(kBlock), 0, s,
-                       sorted_rows, nnz, (int)N, pos_out);
-  SPT_CHECK_LAUNCH("pos_from_sorted_rows");
+  spt_status ps = launch_pos_from_sorted_rows(sorted_rows, nnz, (int)N, pos_out, s);
+  if (ps != SPT_OK) return ps;
   return SPT_OK;
 }
 
