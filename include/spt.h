@@ -99,9 +99,10 @@ typedef enum {
  *   max_children  optional hint for a compressed level: an upper bound on the
  *          number of children of any one parent (CSR: the longest row), 0 =
  *          unknown. Like the level properties of Section 3.3 it is a declared
- *          invariant that only selects a faster loop: with a bound <= 16 CSR
- *          SpMV runs one row per group of lanes instead of the entry-balanced
- *          kernel. A bound that the data violates gives wrong results.
+ *          invariant that only selects a faster loop: with a bound <= 32 CSR
+ *          SpMV streams the entries of 256 rows at a time through LDS and lets
+ *          one lane add up each row, instead of running the entry-balanced
+ *          kernel. A bound that the data violates costs time, not correctness.
  */
 typedef struct {
   int32_t kind;

@@ -353,91 +353,102 @@ __global__ __launch_bounds__(kBlock) void seg_spmv_kernel(
   }
 }
 
-// ---------------------------------------------------------------- CSR with short rows
-// For a compressed level whose max_children hint promises short rows (<= 16):
-// G lanes per row (G from the mean row length), 4 rows per lane group in flight,
-// the workgroup's window of pos staged in LDS. No LDS round trip for the
-// products, no search, no carries: a lane group owns whole rows. Fixed
-// reduction tree inside the group, so the result is bit-reproducible.
-constexpr int kRowsPerGroup = 4;  // rows a lane group keeps in flight (8 measured slower)
+// ---------------------------------------------------------------- CSR, short rows, streamed
+// A workgroup owns kStreamRows consecutive rows. Their entries are one contiguous range of
+// crd / vals, which the lanes read side by side with 16-byte loads (no lane waits on pos to
+// find its entries), multiply by x and park in LDS; then one lane per row adds its row's
+// products from LDS in order and stores y. The range is taken in pieces of kStreamCap entries,
+// so any row length is handled correctly; the kernel is chosen for short rows because there a
+// piece holds many whole rows. Fixed order of additions: bit-reproducible.
+constexpr int kStreamRPT = 1;                       // rows per lane in the reduction
+constexpr int kStreamRows = kStreamRPT * kBlock;    // rows per workgroup
+constexpr int kStreamCap = 2048;                    // products parked per piece
 
-template <typename T, int G, class XP>
-__global__ __launch_bounds__(kBlock) void csr_rowgroup_kernel(int nrows,
-                                                              const int32_t* __restrict__ pos,
-                                                              const int32_t* __restrict__ crd,
-                                                              const T* __restrict__ vals, const XP x,
-                                                              T* __restrict__ y) {
-  constexpr int GROUPS = kBlock / G;
-  constexpr int RPG = kRowsPerGroup;
-  constexpr int ROWS = GROUPS * RPG;
-  __shared__ int32_t s_pos[ROWS + 1];
-  const int row0 = xcd_contiguous_block_id() * ROWS;
-  for (int q = threadIdx.x; q <= ROWS; q += kBlock) s_pos[q] = pos[min(row0 + q, nrows)];
+template <typename T, bool VEC, class XP>
+__global__ __launch_bounds__(kBlock) void csr_stream_kernel(int nrows, int nnz,
+                                                            const int32_t* __restrict__ pos,
+                                                            const int32_t* __restrict__ crd,
+                                                            const T* __restrict__ vals, const XP x,
+                                                            T* __restrict__ y) {
+  typedef int32_t i4 __attribute__((ext_vector_type(4)));
+  using V = typename VecOf<T>::type;  // 16 bytes of values
+  constexpr int R = VecOf<T>::R;
+  __shared__ int32_t s_pos[kStreamRows + 1];
+  __shared__ T s_prod[kStreamCap + 4];
+  const int row0 = xcd_contiguous_block_id() * kStreamRows;
+  for (int q = threadIdx.x; q <= kStreamRows; q += kBlock) s_pos[q] = pos[min(row0 + q, nrows)];
   __syncthreads();
-  const int g = threadIdx.x / G, l = threadIdx.x % G;
-  int p[RPG], e[RPG];
-  T acc[RPG];
-  bool more = false;
+  const int e0 = s_pos[0], e1 = s_pos[kStreamRows];
+  const int e0a = e0 & ~3;  // pieces start on a multiple of 4 entries: aligned 16-byte loads
+  T acc[kStreamRPT];
+  int ra[kStreamRPT], rb[kStreamRPT];
 #pragma unroll
-  for (int u = 0; u < RPG; ++u) {
-    p[u] = s_pos[u * GROUPS + g] + l;
-    e[u] = s_pos[u * GROUPS + g + 1];
+  for (int u = 0; u < kStreamRPT; ++u) {
     acc[u] = T(0);
-    more |= p[u] < e[u];
+    ra[u] = s_pos[u * kBlock + threadIdx.x];
+    rb[u] = s_pos[u * kBlock + threadIdx.x + 1];
   }
-  while (more) {
-    int32_t c[RPG];
-    T v[RPG];
+  for (int c0 = e0a; c0 < e1; c0 += kStreamCap) {
+    const int c1 = min(c0 + kStreamCap, e1);
+    const int groups = (c1 - c0 + 3) >> 2;
+    for (int g4 = threadIdx.x; g4 < groups; g4 += kBlock) {
+      const int p = c0 + 4 * g4;
+      T pr[4];
+      if (VEC && p + 4 <= nnz) {
+        const i4 c = ld_stream(reinterpret_cast<const i4*>(crd + p));
+        T v[4];
 #pragma unroll
-    for (int u = 0; u < RPG; ++u) {
-      const bool ok = p[u] < e[u];
-      c[u] = ok ? ld_stream(crd + p[u]) : -1;
-      v[u] = ok ? ld_stream(vals + p[u]) : T(0);
-    }
-    more = false;
+        for (int h = 0; h < 4 / R; ++h) {
+          const V w = ld_stream(reinterpret_cast<const V*>(vals + p + R * h));
 #pragma unroll
-    for (int u = 0; u < RPG; ++u) {
-      if (c[u] >= 0) acc[u] += v[u] * x.at(c[u]);
-      p[u] += G;
-      more |= p[u] < e[u];
+          for (int r = 0; r < R; ++r) v[R * h + r] = w[r];
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) pr[r] = v[r] * x.at(c[r]);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          pr[r] = p + r < nnz ? ld_stream(vals + p + r) * x.at(ld_stream(crd + p + r)) : T(0);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) s_prod[4 * g4 + r] = pr[r];
     }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kStreamRPT; ++u) {
+      const int a = max(ra[u], c0), b = min(rb[u], c1);
+      for (int q = a; q < b; ++q) acc[u] += s_prod[q - c0];
+    }
+    __syncthreads();
   }
 #pragma unroll
-  for (int u = 0; u < RPG; ++u) {
-#pragma unroll
-    for (int d = G / 2; d > 0; d >>= 1) acc[u] += __shfl_xor(acc[u], d, G);
-    const int r = row0 + u * GROUPS + g;
-    if (l == 0 && r < nrows) y[r] = acc[u];
+  for (int u = 0; u < kStreamRPT; ++u) {
+    const int r = row0 + u * kBlock + threadIdx.x;
+    if (r < nrows) y[r] = acc[u];
   }
 }
 
-template <typename T, int G, class XP>
-static spt_status launch_rowgroup_g(int64_t nrows, const int32_t* pos, const int32_t* crd,
-                                    const T* vals, const XP x, T* y, hipStream_t s) {
-  constexpr int ROWS = (kBlock / G) * kRowsPerGroup;
-  hipLaunchKernelGGL((csr_rowgroup_kernel<T, G, XP>), dim3((unsigned)((nrows + ROWS - 1) / ROWS)),
-                     dim3(kBlock), 0, s, (int)nrows, pos, crd, vals, x, y);
-  SPT_CHECK_LAUNCH("csr_rowgroup");
+template <typename T, class XP>
+static spt_status launch_csr_stream(int64_t nnz, int64_t nrows, const int32_t* pos,
+                                    const int32_t* crd, const T* vals, const XP x, T* y,
+                                    hipStream_t s) {
+  const unsigned grid = (unsigned)((nrows + kStreamRows - 1) / kStreamRows);
+  const bool vec = ((reinterpret_cast<uintptr_t>(crd) | reinterpret_cast<uintptr_t>(vals)) & 15) == 0;
+  if (vec)
+    hipLaunchKernelGGL((csr_stream_kernel<T, true, XP>), dim3(grid), dim3(kBlock), 0, s, (int)nrows,
+                       (int)nnz, pos, crd, vals, x, y);
+  else
+    hipLaunchKernelGGL((csr_stream_kernel<T, false, XP>), dim3(grid), dim3(kBlock), 0, s, (int)nrows,
+                       (int)nnz, pos, crd, vals, x, y);
+  SPT_CHECK_LAUNCH("csr_stream");
   return SPT_OK;
 }
 
-// Lanes per row from the mean row length (power of two in [4, 32]).
-template <typename T, class XP>
-static spt_status launch_rowgroup(int64_t nnz, int64_t nrows, const int32_t* pos,
-                                  const int32_t* crd, const T* vals, const XP x, T* y,
-                                  hipStream_t s) {
-  // smallest power of two that covers the mean row length: most rows take one step
-  const double mean = nrows > 0 ? (double)nnz / (double)nrows : 0.0;
-  if (mean <= 4.0) return launch_rowgroup_g<T, 4, XP>(nrows, pos, crd, vals, x, y, s);
-  if (mean <= 8.0) return launch_rowgroup_g<T, 8, XP>(nrows, pos, crd, vals, x, y, s);
-  if (mean <= 16.0) return launch_rowgroup_g<T, 16, XP>(nrows, pos, crd, vals, x, y, s);
-  return launch_rowgroup_g<T, 32, XP>(nrows, pos, crd, vals, x, y, s);
-}
-
-// Longest declared row for which the row-per-lane-group kernel is used. Measured on the
-// banded matrix (rows <= 7): 48.6 us vs 64.9 us for the entry-balanced kernel + fix-up; with
-// rows of 8..32 entries the entry-balanced kernel's vector loads win (135 vs 142 us).
-constexpr int kShortRowHint = 16;
+// Longest declared row (max_children of the column level) for which the streamed kernel is
+// used. Measured against the entry-balanced kernel + fix-up: banded matrix, rows <= 7, fp64:
+// 36.9 vs 64.9 us (a row per group of 8 lanes: 48.6 us); rows of 8..32 entries, fp32: 119.6 vs
+// 135 us. Without a declared bound a single long row would be added up by one lane.
+constexpr int kShortRowHint = 32;
 
 // ---------------------------------------------------------------- unsorted COO
 // The fused single loop over all entries of the paper's COO kernel: a scatter
@@ -558,8 +569,8 @@ static spt_status spmv_typed(Format f, const spt_tensor* A, const T* x, T* y, vo
       const int hint = A->level[1].max_children;
       if (hint > 0 && hint <= kShortRowHint && A->nvals > 0 && A->level[0].N + 1 < INT32_MAX &&
           A->nvals < INT32_MAX)
-        return launch_rowgroup<T, DenseX<T>>(A->nvals, A->level[0].N, A->level[1].pos,
-                                             A->level[1].crd, vals, DenseX<T>{x}, y, s);
+        return launch_csr_stream<T, DenseX<T>>(A->nvals, A->level[0].N, A->level[1].pos,
+                                               A->level[1].crd, vals, DenseX<T>{x}, y, s);
       return launch_seg<T, true>(A->nvals, A->level[0].N, A->level[1].pos, A->level[1].crd, vals,
                                  x, y, ws, ws_bytes, s);
     }

@@ -159,9 +159,9 @@ def test_ell_scaled_config3_with_poisoned_padding(dtype, N):
 
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
 @pytest.mark.parametrize("lo,hi", [(0, 3), (1, 7), (0, 12), (9, 16), (8, 32)])
-def test_csr_short_row_hint_selects_the_row_group_kernel(dtype, lo, hi):
-    """max_children <= 16 on the column level: one row per lane group (4/8/16 lanes by mean
-    length); larger bounds and no hint run the entry-balanced kernel; all match the oracle."""
+def test_csr_short_row_hint_selects_the_streamed_kernel(dtype, lo, hi):
+    """max_children <= 32 on the column level: the streamed kernel (256 rows' entries through
+    LDS, one lane per row); no hint runs the entry-balanced kernel; all match the oracle."""
     c3 = wl.config3(N=5003, lo=lo, hi=hi, dtype=dtype)
     hinted = c3["csr"]
     assert hinted.levels[1].max_children == c3["W"] <= 64
@@ -169,10 +169,30 @@ def test_csr_short_row_hint_selects_the_row_group_kernel(dtype, lo, hi):
     plain = wl.csr_spec(5003, 5003, lv.pos, lv.crd, hinted.vals)
     ref, mag = oracle.spmv(hinted, c3["x"])
     a, b = gpu_spmv(hinted, c3["x"], repeat=2)
-    assert_close(a, ref, mag, dtype, f"row-group kernel rows {lo}..{hi}")
+    assert_close(a, ref, mag, dtype, f"streamed kernel rows {lo}..{hi}")
     assert np.array_equal(a, b)
     assert_close(gpu_spmv(plain, c3["x"]), ref, mag, dtype, f"entry-balanced kernel rows {lo}..{hi}")
-    assert_close(gpu_spmv(hinted, c3["x"], misalign=True), ref, mag, dtype, "row-group, unaligned")
+    assert_close(gpu_spmv(hinted, c3["x"], misalign=True), ref, mag, dtype, "streamed kernel, unaligned")
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_csr_hint_that_the_data_violates_stays_correct(dtype):
+    """A declared bound of 8 on a matrix with one row of 9000 entries: the streamed kernel takes
+    the long row in several LDS pieces; slower, never wrong."""
+    N, M = 3000, 10_000
+    r, c, v = wl.random_coo_entries(N, M, 20_000, seed=77, dtype=dtype)
+    rng = np.random.default_rng(78)
+    long_cols = np.sort(rng.choice(M, 9000, replace=False))
+    keep = r != 7
+    r = np.concatenate([r[keep], np.full(9000, 7)])
+    c = np.concatenate([c[keep], long_cols])
+    v = np.concatenate([v[keep], rng.uniform(-1, 1, 9000).astype(dtype)])
+    order = np.lexsort((c, r))
+    lying = wl.csr_from_sorted_coo(N, M, r[order], c[order], v[order])
+    lying.levels[1].max_children = 8
+    x = wl.dense_vector(M, 79, dtype)
+    ref, mag = oracle.spmv(lying, x)
+    assert_close(gpu_spmv(lying, x), ref, mag, dtype, "violated hint")
 
 
 def test_unsupported_and_invalid_descriptors_report_errors():
