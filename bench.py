@@ -66,7 +66,7 @@ def build_items(args):
 
     def on(name):
         if want is None:
-            return name not in ("x16", "n2", "n3", "n4")   # these groups run only on request
+            return name not in ("x16", "n2", "n3", "n4", "n5")   # these groups run only on request
         return name in want or name.split("_")[0] in want
 
     # ---- config 2: banded, 7 diagonals, fp64: DIA and CSR
@@ -313,6 +313,31 @@ def build_items(args):
         items.append(Item("n4_coo_to_dia", lambda: spt.spt_coo_to_dia(Ad, 7, offs, dv), 0,
                           16 * len(cv) + 2 * 8 * 7 * N2, "zero fill + scattered values"))
         del c2
+    # ---- on request (--only n5): compositions without a kernel of their own, read through the
+    #      level functions per stored value: config 3's matrix as CSC and as DCSR (SpMV), and its
+    #      ELL layout unpacked to COO
+    if on("n5"):
+        c3 = wl.config3(N=max(64, int(1_000_000 * s)))
+        N3, nnz3 = c3["csr"].dims[0], c3["nnz"]
+        (rr, cc), vv = oracle_free_coo(c3["csr"])
+        xg = up(c3["x"])
+        yg = torch.empty(N3, dtype=torch.float32, device=dev)
+        for nm, spec in (("csc", wl.csc_from_coo(N3, N3, rr, cc, vv)),
+                         ("dcsr", wl.dcsr_from_sorted_coo(N3, N3, rr, cc, vv))):
+            Ag = spt.DeviceTensor(spec)
+            keep.append(Ag)
+            items.append(Item(f"n5_spmv_{nm}", lambda Ag=Ag: spt.spt_spmv(Ag, xg, yg, None), 2 * nnz3,
+                              8 * nnz3 + 12 * N3, "one atomic per stored value"))
+        Ae = spt.DeviceTensor(c3["ell"])
+        cells = len(c3["ell"].vals)
+        g0, g1 = (torch.empty(cells, dtype=torch.int32, device=dev) for _ in range(2))
+        gv = torch.empty(cells, dtype=torch.float32, device=dev)
+        gcnt = torch.zeros(1, dtype=torch.int64, device=dev)
+        wg = Ae.workspace(spt.SPT_OP_TO_COO)
+        keep.extend([Ae, g0, g1, gv, gcnt, wg, yg])
+        items.append(Item("n5_ell_to_coo", lambda: spt.spt_to_coo(Ae, g0, g1, None, gv, gcnt, wg), 0,
+                          2 * 8 * cells + 12 * nnz3, "cells read twice (count, fill)"))
+        del c3
     return items, cpu_jobs, keep
 
 

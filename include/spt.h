@@ -74,7 +74,8 @@ typedef enum {
   SPT_OP_TTM = 5,
   SPT_OP_TO_CSF = 6,
   SPT_OP_TO_ELL = 7,
-  SPT_OP_DIA_OFFSETS = 8
+  SPT_OP_DIA_OFFSETS = 8,
+  SPT_OP_TO_COO = 9
 } spt_op;
 
 /*
@@ -127,7 +128,14 @@ typedef struct {
  *   ELL   (D slots W, D rows, S cols)             vals[W*N], cell (k,i) at k*N+i
  *   COO3  (C~U, S~U, S)                           vals[nnz]
  *   CSF3  (C, C, C)                               vals[nnz]
- * Everything else returns SPT_ERR_UNSUPPORTED from the four operations.
+ * spt_spmv and spt_to_coo also accept every other legal composition ("any composition"
+ * below); the remaining operations return SPT_ERR_UNSUPPORTED for them.
+ *
+ * Any composition: level 0 is dense, compressed (M = 1) or hashed; a range level needs a level
+ * above it and an offset level two (their coordinates are computed from those levels'
+ * coordinates, Table 2); every tensor dimension is encoded by exactly one level; dense and
+ * range levels have N > 0 and hashed levels M > 0 when values are stored. nvals is the number
+ * of leaf positions (positions of the last level), whether or not each holds a component.
  */
 typedef struct {
   int32_t order;   /* number of tensor dimensions (2 or 3) */
@@ -145,6 +153,9 @@ typedef struct {
  * 0). Every stored entry counts (duplicates add up). COO flagged SPT_ORDERED
  * on its row level runs a deterministic segmented reduction; without the flag
  * the entries are accumulated with floating-point atomics (any order).
+ * Any other composition of levels that stores a matrix (DCSR, CSC, dense, hashed
+ * rows or columns, ...) is evaluated by reading the level functions of Table 2 per
+ * stored value, again with floating-point atomics; it needs no workspace.
  */
 spt_status spt_spmv(const spt_tensor* A, const void* x, void* y, void* ws,
                     size_t ws_bytes, void* stream);
@@ -267,6 +278,16 @@ spt_status spt_coo_dia_offsets(const spt_tensor* A, int32_t* offsets_out, int64_
                                int64_t* K_dev, void* ws, size_t ws_bytes, void* stream);
 spt_status spt_coo_to_dia(const spt_tensor* A, int32_t K, const int32_t* offsets, void* vals_out,
                           void* stream);
+
+/*
+ * Any composition -> COO, in storage order (Section 3.1: every format is a coordinate
+ * hierarchy; its components are the root-to-leaf paths). T: order 1..3, any composition.
+ * out_crd0 .. out_crd[order-1] and out_vals need capacity nvals; components whose position
+ * holds none (padding, empty buckets, cells outside a range level) are left out;
+ * *out_nnz_dev (device int64) receives the number written. Workspace: SPT_OP_TO_COO.
+ */
+spt_status spt_to_coo(const spt_tensor* T, int32_t* out_crd0, int32_t* out_crd1, int32_t* out_crd2,
+                      void* out_vals, int64_t* out_nnz_dev, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * A = B + C with a sparse result: matrix addition on COO or CSR (Section 5.2) and 3rd-order

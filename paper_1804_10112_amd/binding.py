@@ -18,7 +18,7 @@ _lib = None
 
 SPT_OK, SPT_ERR_INVALID_ARG, SPT_ERR_UNSUPPORTED, SPT_ERR_WORKSPACE, SPT_ERR_DEVICE = range(5)
 SPT_OP_SPMV, SPT_OP_COO_TO_CSR, SPT_OP_TTV, SPT_OP_MTTKRP, SPT_OP_INNERPROD, SPT_OP_TTM = range(6)
-SPT_OP_TO_CSF, SPT_OP_TO_ELL, SPT_OP_DIA_OFFSETS = 6, 7, 8
+SPT_OP_TO_CSF, SPT_OP_TO_ELL, SPT_OP_DIA_OFFSETS, SPT_OP_TO_COO = 6, 7, 8, 9
 SPT_ORDER_ROW_COL, SPT_ORDER_ROW_STABLE = 0, 1
 SPT_ORDERED, SPT_UNIQUE = 1, 2
 SPT_F32, SPT_F64 = 0, 1
@@ -27,7 +27,7 @@ SYMBOLS = ["spt_spmv", "spt_coo_to_csr", "spt_ttv", "spt_mttkrp", "spt_workspace
            "spt_last_error", "spt_version", "spt_probe_read", "spt_probe_gather",
            "spt_spmv_sparse_x", "spt_spdm", "spt_innerprod", "spt_ttm",
            "spt_add", "spt_add_workspace_bytes", "spt_coo3_to_csf", "spt_to_ell",
-           "spt_coo_dia_offsets", "spt_coo_to_dia"]
+           "spt_coo_dia_offsets", "spt_coo_to_dia", "spt_to_coo"]
 
 
 class SptLevel(C.Structure):
@@ -79,6 +79,8 @@ def lib():
         L.spt_coo_dia_offsets.argtypes = [vp, vp, C.c_int64, vp, vp, sz, vp]
         L.spt_coo_to_dia.restype = i32
         L.spt_coo_to_dia.argtypes = [vp, i32, vp, vp, vp]
+        L.spt_to_coo.restype = i32
+        L.spt_to_coo.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.spt_add.restype = i32
         L.spt_add.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.spt_add_workspace_bytes.restype = sz
@@ -217,6 +219,12 @@ def spt_coo_dia_offsets(A, offsets_out, cap, K_dev, ws=None, stream=None):
 
 def spt_coo_to_dia(A, K, offsets, vals_out, stream=None):
     _check(lib().spt_coo_to_dia(_desc(A), K, _p(offsets), _p(vals_out), _stream(stream)))
+
+
+def spt_to_coo(T, out_crd0, out_crd1, out_crd2, out_vals, out_nnz_dev, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(lib().spt_to_coo(_desc(T), _p(out_crd0), _p(out_crd1), _p(out_crd2), _p(out_vals),
+                            _p(out_nnz_dev), p, n, _stream(stream)))
 
 
 def spt_add(B, Ct, out_pos, out_crd0, out_crd1, out_crd2, out_vals, out_nnz_dev, ws=None, stream=None):

@@ -66,6 +66,11 @@ size_t dia_offsets_workspace(const spt_tensor* A);
 spt_status pack_dia_dispatch(const spt_tensor* A, int32_t K, const int32_t* offsets, void* vals_out,
                              hipStream_t s);
 
+spt_status generic_spmv_dispatch(const spt_tensor* A, const void* x, void* y, hipStream_t s);
+spt_status to_coo_dispatch(const spt_tensor* T, int32_t* o0, int32_t* o1, int32_t* o2, void* ov,
+                           int64_t* out_nnz, void* ws, size_t ws_bytes, hipStream_t s);
+size_t to_coo_workspace(int64_t nvals);
+
 static bool is(const spt_level& L, int kind) { return L.kind == kind; }
 static bool unique(const spt_level& L) { return (L.flags & SPT_UNIQUE) != 0; }
 
@@ -207,6 +212,42 @@ Format recognize(const spt_tensor* T) {
   return Format::Unsupported;
 }
 
+// Structural rules under which the per-value reading of the level functions is defined for
+// a composition that has no kernel of its own. Call after recognize() returned a format or
+// Unsupported (so every level passed level_ok). Sets the error and returns false otherwise.
+static bool generic_ok(const spt_tensor* T) {
+  const spt_level* L = T->level;
+  if (!(L[0].kind == SPT_DENSE || L[0].kind == SPT_HASHED ||
+        (L[0].kind == SPT_COMPRESSED && L[0].M == 1))) {
+    fail(SPT_ERR_UNSUPPORTED, "level 0 must be dense, hashed or compressed with one parent (M = 1)");
+    return false;
+  }
+  int seen[4] = {0, 0, 0, 0};
+  for (int k = 0; k < T->nlevels; ++k) {
+    if (L[k].kind == SPT_OFFSET && k < 2) {
+      fail(SPT_ERR_UNSUPPORTED, "level %d: an offset level needs two levels above it", k);
+      return false;
+    }
+    if (T->nvals > 0 && (((L[k].kind == SPT_DENSE || L[k].kind == SPT_RANGE) && L[k].N <= 0) ||
+                         (L[k].kind == SPT_HASHED && L[k].M <= 0))) {
+      fail(SPT_ERR_INVALID_ARG, "level %d: empty extent but values are stored", k);
+      return false;
+    }
+    if (L[k].N >= INT32_MAX || L[k].M >= INT32_MAX) {
+      fail(SPT_ERR_UNSUPPORTED, "level %d: extent beyond int32", k);
+      return false;
+    }
+    if (L[k].mode >= 0) ++seen[L[k].mode];
+  }
+  for (int m = 0; m < T->order; ++m)
+    if (seen[m] != 1) {
+      fail(SPT_ERR_UNSUPPORTED, "tensor dimension %d must be encoded by exactly one level", m);
+      return false;
+    }
+  clear_error();
+  return true;
+}
+
 static spt_status status_of(Format f) {
   return f == Format::Invalid ? SPT_ERR_INVALID_ARG : SPT_ERR_UNSUPPORTED;
 }
@@ -224,7 +265,13 @@ spt_status spt_spmv(const spt_tensor* A, const void* x, void* y, void* ws, size_
                     void* stream) {
   clear_error();
   Format f = recognize(A);
-  if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
+  if (f == Format::Invalid) return status_of(f);
+  if (f == Format::Unsupported) {  // no kernel of its own: per-value reading of the level functions
+    if (A->order != 2) return fail(SPT_ERR_UNSUPPORTED, "spmv: A must be a matrix");
+    if (!generic_ok(A)) return SPT_ERR_UNSUPPORTED;
+    if (!x || !y) return fail(SPT_ERR_INVALID_ARG, "spmv: x or y is null");
+    return generic_spmv_dispatch(A, x, y, static_cast<hipStream_t>(stream));
+  }
   if (!x || !y) return fail(SPT_ERR_INVALID_ARG, "spmv: x or y is null");
   return spmv_dispatch(f, A, x, y, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
@@ -402,6 +449,20 @@ spt_status spt_coo_to_dia(const spt_tensor* A, int32_t K, const int32_t* offsets
   return pack_dia_dispatch(A, K, offsets, vals_out, static_cast<hipStream_t>(stream));
 }
 
+spt_status spt_to_coo(const spt_tensor* T, int32_t* out_crd0, int32_t* out_crd1, int32_t* out_crd2,
+                      void* out_vals, int64_t* out_nnz_dev, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  Format f = recognize(T);
+  if (f == Format::Invalid) return status_of(f);
+  if (T->order > 3) return fail(SPT_ERR_UNSUPPORTED, "to_coo: order %d above 3", T->order);
+  if (!generic_ok(T)) return SPT_ERR_UNSUPPORTED;
+  if (!out_nnz_dev || (T->nvals > 0 && (!out_crd0 || !out_vals || (T->order > 1 && !out_crd1) ||
+                                        (T->order > 2 && !out_crd2))))
+    return fail(SPT_ERR_INVALID_ARG, "to_coo: null output");
+  return to_coo_dispatch(T, out_crd0, out_crd1, out_crd2, out_vals, out_nnz_dev, ws, ws_bytes,
+                         static_cast<hipStream_t>(stream));
+}
+
 // Common operand checks of spt_add; returns the shared format or sets the error.
 static spt_status add_operands(const spt_tensor* B, const spt_tensor* C, Format* f_out) {
   Format fb = recognize(B);
@@ -450,7 +511,13 @@ size_t spt_add_workspace_bytes(const spt_tensor* B, const spt_tensor* C) {
 size_t spt_workspace_bytes(int32_t op, const spt_tensor* T, int32_t J) {
   clear_error();
   Format f = recognize(T);
-  if (f == Format::Invalid || f == Format::Unsupported) return 0;
+  if (f == Format::Invalid) return 0;
+  if (f == Format::Unsupported || op == SPT_OP_TO_COO) {  // operations defined for any composition
+    if (op == SPT_OP_SPMV && f == Format::Unsupported && T->order == 2 && generic_ok(T)) return 256;
+    if (op == SPT_OP_TO_COO && T->order <= 3 && generic_ok(T)) return to_coo_workspace(T->nvals);
+    if (g_err[0] == 0) fail(SPT_ERR_UNSUPPORTED, "operation %d is not defined for this composition", op);
+    return 0;
+  }
   size_t n = 0;
   switch (op) {
     case SPT_OP_SPMV:

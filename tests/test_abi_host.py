@@ -78,10 +78,12 @@ def test_invalid_and_unsupported_descriptors():
     t.level[1].kind = wl.HASHED
     st, msg = _status(spt.spt_workspace_bytes, B.SPT_OP_SPMV, t)
     assert st == B.SPT_ERR_INVALID_ARG and "hashed" in msg
-    # hashed, legally flagged: a valid level but no kernel for the composition
+    # hashed, legally flagged: (dense, hashed) has no kernel of its own but SpMV reads any
+    # composition's level functions per value: the workspace query succeeds (nothing is launched)
     t.level[1].flags = B.SPT_UNIQUE
-    st, msg = _status(spt.spt_spmv, t, 0x1000, 0x1000, None, 0)
-    assert st == B.SPT_ERR_UNSUPPORTED
+    t.level[1].M = 8
+    assert spt.spt_workspace_bytes(B.SPT_OP_SPMV, t) >= 256
+    assert _status(spt.spt_workspace_bytes, B.SPT_OP_MTTKRP, t)[0] == B.SPT_ERR_INVALID_ARG   # reported through the query
     # compressed level without pos; CSR whose column level has the wrong parent count
     t = _host_desc(c1["csr"])
     t.level[1].pos = None
@@ -89,11 +91,22 @@ def test_invalid_and_unsupported_descriptors():
     t = _host_desc(c1["csr"])
     t.level[1].M = 7
     assert _status(spt.spt_spmv, t, 0x1000, 0x1000, None, 0)[0] == B.SPT_ERR_INVALID_ARG
-    # (compressed, compressed) = DCSR: valid levels, unsupported composition
+    # (compressed, compressed) = DCSR: valid for SpMV and to_coo (any composition), not for the
+    # operations with format-specific kernels only
     t = _host_desc(c1["coo"])
     t.level[1].kind = wl.COMPRESSED
     t.level[1].pos = 0x1000
+    assert spt.spt_workspace_bytes(B.SPT_OP_SPMV, t) >= 256
+    assert spt.spt_workspace_bytes(B.SPT_OP_TO_COO, t) >= 256
+    assert _status(spt.spt_coo_to_csr, t, 0, 0x1000, 0x1000, 0x1000, None, 0)[0] == B.SPT_ERR_UNSUPPORTED
+    # structurally impossible compositions stay unsupported: an offset level without two levels above
+    t = _host_desc(c1["csr"])
+    t.level[1].kind = wl.OFFSET
+    t.level[1].offset = 0x1000
     assert _status(spt.spt_spmv, t, 0x1000, 0x1000, None, 0)[0] == B.SPT_ERR_UNSUPPORTED
+    # a 3rd-order tensor is no operand of SpMV
+    c5s = wl.config5(dims=(20, 16, 12), nnz=300, rank=4)
+    assert _status(spt.spt_spmv, _host_desc(c5s["coo"]), 0x1000, 0x1000, None, 0)[0] == B.SPT_ERR_UNSUPPORTED
     # null operands, bad order, bad rank, wrong operation for the format
     t = _host_desc(c1["coo"])
     assert _status(spt.spt_spmv, t, None, 0x1000, None, 0)[0] == B.SPT_ERR_INVALID_ARG

@@ -1,0 +1,128 @@
+"""GPU parity: spt_spmv and spt_to_coo on compositions that have no kernel of their own (read
+through the level functions per stored value), and spt_to_coo on the named formats, vs the
+oracle's level walk."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from gpu_util import assert_close, gpu_spmv
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_to_coo(spec):
+    import torch
+    import paper_1804_10112_amd as spt
+    T = spt.DeviceTensor(spec)
+    n = max(len(spec.vals), 1)
+    crd = [torch.full((n,), -7, dtype=torch.int32, device="cuda") for _ in range(3)]
+    vals = torch.full((n,), float("nan"), dtype=T.torch_dtype, device="cuda")
+    cnt = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    order = len(spec.dims)
+    spt.spt_to_coo(T, crd[0], crd[1] if order > 1 else None, crd[2] if order > 2 else None, vals, cnt,
+                   T.workspace(spt.SPT_OP_TO_COO))
+    torch.cuda.synchronize()
+    k = int(cnt.item())
+    return [c.cpu().numpy()[:k] for c in crd[:order]], vals.cpu().numpy()[:k]
+
+
+def _entries(N, M, nnz, seed, dtype):
+    r, c, v = wl.random_coo_entries(N, M, nnz, seed=seed, dtype=dtype)
+    r[(r % 7) == 3] += 1                                      # empty rows
+    r = np.minimum(r, N - 1)
+    order = np.lexsort((c, r))
+    key, first = np.unique(r[order].astype(np.int64) * M + c[order], return_index=True)
+    return r[order][first], c[order][first], v[order][first]
+
+
+def _compositions(N, M, r, c, v, dense=True):
+    out = {
+        "dcsr": wl.dcsr_from_sorted_coo(N, M, r, c, v),
+        "csc": wl.csc_from_coo(N, M, r, c, v),
+        "dhash": wl.hashed_rows_from_coo(N, M, r, c, v, W=1 << int(np.ceil(np.log2(2 * np.bincount(r).max() + 1)))),
+    }
+    if dense:
+        D = np.zeros((N, M), v.dtype)
+        D[r, c] = v
+        out["dense"] = wl.dense_matrix_spec(D)
+    return out
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("nnz", [1, 300, 20_000])
+def test_spmv_any_composition(dtype, nnz):
+    N, M = 700, 900
+    r, c, v = _entries(N, M, nnz, 1500 + nnz, dtype)
+    x = wl.dense_vector(M, 7, dtype)
+    ref, mag = oracle.spmv(wl.coo_spec(N, M, r, c, v), x)
+    for name, spec in _compositions(N, M, r, c, v, dense=nnz <= 20_000).items():
+        oref, _ = oracle.spmv(spec, x)                         # the oracle walks the composition itself
+        assert np.allclose(oref, ref, atol=1e-12 * max(mag.max(), 1)), name
+        assert_close(gpu_spmv(spec, x), ref, mag, dtype, f"spmv {name} nnz={nnz}")
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_to_coo_any_composition_and_named_formats(dtype):
+    N, M = 500, 640
+    r, c, v = _entries(N, M, 9000, 1600, dtype)
+    specs = _compositions(N, M, r, c, v)
+    specs["csr"] = wl.csr_from_sorted_coo(N, M, r, c, v)
+    specs["coo"] = wl.coo_spec(N, M, r, c, v)
+    c2 = wl.config2(N=3000, dtype=dtype)
+    c3 = wl.config3(N=3000, dtype=dtype)
+    specs["dia"], specs["ell"] = c2["dia"], c3["ell"]
+    for name, spec in specs.items():
+        rc, rv = oracle.to_coo(spec)                           # storage order of the level walk
+        gc, gv = gpu_to_coo(spec)
+        assert len(gv) == len(rv), name
+        for m in range(2):
+            assert np.array_equal(gc[m], rc[m]), f"{name}: coordinate {m}"
+        assert np.array_equal(gv.astype(np.float64), rv), name
+
+
+def test_to_coo_third_order_vectors_and_empty():
+    dims = (40, 30, 50)
+    ci, cj, ck, v = wl.random_coo3_entries(dims, 12_000, 1700, dtype=np.float32, skew=1.4)
+    for spec in (wl.coo3_spec(dims, ci, cj, ck, v), wl.csf3_from_sorted_coo(dims, ci, cj, ck, v),
+                 wl.dcc3_from_sorted_coo(dims, ci, cj, ck, v)):
+        gc, gv = gpu_to_coo(spec)
+        assert np.array_equal(gc[0], ci) and np.array_equal(gc[1], cj) and np.array_equal(gc[2], ck)
+        assert np.array_equal(gv, v)
+    xc, xv = wl.random_sparse_vector(5000, 700, seed=9, dtype=np.float64)
+    for spec in (wl.sparse_vector_spec(5000, xc, xv), wl.hash_vector_spec(5000, xc, xv, 2048)):
+        rc, rv = oracle.to_coo(spec)
+        gc, gv = gpu_to_coo(spec)
+        assert np.array_equal(gc[0], rc[0]) and np.array_equal(gv, rv)
+        assert np.array_equal(np.sort(gc[0]), xc)
+    e = np.zeros(0, np.int32)
+    gc, gv = gpu_to_coo(wl.coo_spec(10, 10, e, e, np.zeros(0, np.float32)))
+    assert len(gv) == 0
+
+
+def test_to_coo_then_coo_to_csr_round_trip_from_csc():
+    """CSC -> COO (storage order: column-major, so the row level is not ordered) -> CSR through
+    the sort: the composition of the generic unpacker and the conversion kernel."""
+    from gpu_util import gpu_coo_to_csr
+    N, M = 900, 800
+    r, c, v = _entries(N, M, 30_000, 1800, np.float64)
+    gc, gv = gpu_to_coo(wl.csc_from_coo(N, M, r, c, v))
+    pos, crd, vals = gpu_coo_to_csr(wl.coo_spec(N, M, gc[0], gc[1], gv, ordered=False), 0)
+    want = wl.csr_from_sorted_coo(N, M, r, c, v)
+    assert np.array_equal(pos, want.levels[1].pos) and np.array_equal(crd, c) and np.array_equal(vals, v)
+
+
+def test_generic_errors():
+    import torch
+    import paper_1804_10112_amd as spt
+    ci, cj, ck, v = wl.random_coo3_entries((5, 5, 5), 50, 2, dtype=np.float32)
+    t3 = spt.DeviceTensor(wl.dcc3_from_sorted_coo((5, 5, 5), ci, cj, ck, v))
+    x = torch.zeros(5, device="cuda")
+    with pytest.raises(spt.SptError) as e:
+        spt.spt_spmv(t3, x, x, None)                         # a 3rd-order tensor is no matrix
+    assert e.value.status == 2
+    r, c, w = _entries(20, 20, 50, 3, np.float32)
+    d = spt.DeviceTensor(wl.dcsr_from_sorted_coo(20, 20, r, c, w))
+    with pytest.raises(spt.SptError) as e:
+        spt.spt_to_coo(d, None, None, None, None, None, None)
+    assert e.value.status == 1

@@ -186,3 +186,51 @@ def test_empty_tensors_walk_to_nothing():
     coo = wl.coo_spec(4, 5, z, z, np.zeros(0))
     csr = wl.csr_from_sorted_coo(4, 5, z, z, np.zeros(0))
     assert oracle.to_coo(coo)[1].size == 0 and oracle.to_coo(csr)[1].size == 0
+
+
+# ---------------------------------------------------------------- other compositions
+# DCSR, CSC, a dense matrix, hashed rows and a (dense, compressed, compressed) tensor have no
+# kernel of their own: the oracle's level walk is their reference, pinned here against scipy /
+# the entry list they were built from.
+
+def test_other_matrix_compositions_walk_to_the_same_entries_and_products():
+    import scipy.sparse as sp
+    N, M = 23, 31
+    r, c, v = wl.random_coo_entries(N, M, 120, seed=91, dtype=np.float64)
+    r[r == 5] = 6                                   # leave rows empty so DCSR really compresses rows
+    order = np.lexsort((c, r))
+    key, first = np.unique(r[order].astype(np.int64) * M + c[order], return_index=True)
+    r, c, v = r[order][first], c[order][first], v[order][first]
+    S = sp.coo_matrix((v, (r, c)), shape=(N, M))
+    x = wl.dense_vector(M, 92, np.float64)
+    want = S @ x
+    specs = {
+        "dcsr": wl.dcsr_from_sorted_coo(N, M, r, c, v),
+        "csc": wl.csc_from_coo(N, M, r, c, v),
+        "dense": wl.dense_matrix_spec(S.toarray()),
+        "dhash": wl.hashed_rows_from_coo(N, M, r, c, v, W=16),
+    }
+    assert len(specs["dcsr"].levels[0].crd) < N
+    for name, spec in specs.items():
+        co, w = oracle.to_coo(spec)
+        if name == "dense":                          # every cell is a leaf; the zeros are stored too
+            assert co.shape[1] == N * M
+            keep = w != 0
+            co, w = co[:, keep], w[keep]
+        o = np.lexsort((co[1], co[0]))
+        assert np.array_equal(co[0][o], r) and np.array_equal(co[1][o], c), name
+        assert np.array_equal(w[o], v), name
+        y, _ = oracle.spmv(spec, x)
+        np.testing.assert_allclose(y, want, rtol=0, atol=1e-13, err_msg=name)
+    # CSC is stored column-major: its storage order is by (col, row)
+    co, _ = oracle.to_coo(specs["csc"])
+    assert np.all(np.diff(co[1] * N + co[0]) > 0)
+
+
+def test_dense_compressed_compressed_tensor_walk():
+    dims = (6, 5, 7)
+    ci, cj, ck, v = wl.random_coo3_entries(dims, 90, seed=93, dtype=np.float64, skew=1.5)
+    spec = wl.dcc3_from_sorted_coo(dims, ci, cj, ck, v)
+    co, w = oracle.to_coo(spec)
+    assert np.array_equal(co[0], ci) and np.array_equal(co[1], cj) and np.array_equal(co[2], ck)
+    assert np.array_equal(w, v)

@@ -148,6 +148,70 @@ def hash_vector_spec(M, crd, vals, W, name="hashvec") -> TensorSpec:
     return TensorSpec((M,), [LevelSpec(HASHED, 0, M, M=W, crd=table, ordered=False)], tv, name)
 
 
+# ---- compositions without a kernel of their own (evaluated through the level functions) ----
+
+def dcsr_from_sorted_coo(N, M, row, col, vals, name="dcsr") -> TensorSpec:
+    """DCSR = (compressed rows, compressed cols): only rows that hold entries are stored."""
+    row = np.asarray(row)
+    rows, first = np.unique(row, return_index=True)
+    pos1 = np.concatenate([first, [len(row)]]) if len(row) else np.zeros(1, np.int64)
+    return TensorSpec((N, M), [
+        LevelSpec(COMPRESSED, 0, N, M=1, pos=_i32([0, len(rows)]), crd=_i32(rows)),
+        LevelSpec(COMPRESSED, 1, M, M=len(rows), pos=_i32(pos1), crd=_i32(col)),
+    ], np.ascontiguousarray(vals), name)
+
+
+def csc_from_coo(N, M, row, col, vals, name="csc") -> TensorSpec:
+    """CSC = (dense cols, compressed rows): the levels store the dimensions in the order
+    (1, 0); entries are laid out column-major."""
+    row, col, vals = np.asarray(row), np.asarray(col), np.asarray(vals)
+    order = np.lexsort((row, col))
+    pos = np.searchsorted(col[order], np.arange(M + 1), side="left")
+    return TensorSpec((N, M), [
+        LevelSpec(DENSE, 1, M),
+        LevelSpec(COMPRESSED, 0, N, M=M, pos=_i32(pos), crd=_i32(row[order])),
+    ], np.ascontiguousarray(vals[order]), name)
+
+
+def dense_matrix_spec(A, name="dense") -> TensorSpec:
+    """(dense rows, dense cols): every cell is a leaf, row-major."""
+    A = np.ascontiguousarray(A)
+    N, M = A.shape
+    return TensorSpec((N, M), [LevelSpec(DENSE, 0, N), LevelSpec(DENSE, 1, M)], A.reshape(-1), name)
+
+
+def hashed_rows_from_coo(N, M, row, col, vals, W, name="dhash") -> TensorSpec:
+    """(dense rows, hashed cols): every row owns a W-wide open-addressed table; column j sits
+    at the first free slot at or after j % W of its row's segment (wrapping), -1 = empty."""
+    vals = np.asarray(vals)
+    table = np.full(N * W, -1, np.int32)
+    tv = np.zeros(N * W, vals.dtype)
+    for i, j, v in zip(np.asarray(row).tolist(), np.asarray(col).tolist(), vals.tolist()):
+        q = j % W
+        while table[i * W + q] != -1:
+            q = (q + 1) % W
+        table[i * W + q] = j
+        tv[i * W + q] = v
+    return TensorSpec((N, M), [
+        LevelSpec(DENSE, 0, N),
+        LevelSpec(HASHED, 1, M, M=W, crd=table, ordered=False),
+    ], tv, name)
+
+
+def dcc3_from_sorted_coo(dims, ci, cj, ck, vals, name="dcc3") -> TensorSpec:
+    """3rd-order (dense, compressed, compressed): CSF with a dense first level."""
+    ci, cj = np.asarray(ci, np.int64), np.asarray(cj, np.int64)
+    key = ci * dims[1] + cj
+    fib, first = np.unique(key, return_index=True)
+    pos2 = np.concatenate([first, [len(key)]]) if len(key) else np.zeros(1, np.int64)
+    pos1 = np.searchsorted(fib // dims[1], np.arange(dims[0] + 1), side="left")
+    return TensorSpec(tuple(dims), [
+        LevelSpec(DENSE, 0, dims[0]),
+        LevelSpec(COMPRESSED, 1, dims[1], M=dims[0], pos=_i32(pos1), crd=_i32(fib % dims[1])),
+        LevelSpec(COMPRESSED, 2, dims[2], M=len(fib), pos=_i32(pos2), crd=_i32(ck)),
+    ], np.ascontiguousarray(vals), name)
+
+
 def random_sparse_vector(M, nnz, seed, dtype=np.float64, dist="u11"):
     """(sorted distinct coordinates, values) of a random sparse vector."""
     rng = np.random.default_rng(seed)
