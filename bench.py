@@ -402,6 +402,31 @@ def read_traffic_file():
     return out
 
 
+def config1_warm(reps=200):
+    """Config 1 (4096 x 4096, 40 960 entries, fp64) fits every cache: its SpMV is bound by launch
+    and dependent-load latency, not bandwidth. Warm back-to-back calls, microseconds per call."""
+    import torch
+    import paper_1804_10112_amd as spt
+    import workloads as wl
+    c1 = wl.config1()
+    x = torch.from_numpy(c1["x"]).cuda()
+    out = {}
+    for fmt in ("csr", "coo"):
+        A = spt.DeviceTensor(c1[fmt])
+        y = torch.empty(c1[fmt].dims[0], dtype=torch.float64, device="cuda")
+        ws = A.workspace(spt.SPT_OP_SPMV)
+        for _ in range(10):
+            spt.spt_spmv(A, x, y, ws)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            spt.spt_spmv(A, x, y, ws)
+        b.record()
+        torch.cuda.synchronize()
+        out[f"{fmt}_spmv_us"] = round(a.elapsed_time(b) * 1e3 / reps, 2)
+    return out
+
+
 def cpu_baseline(cpu_jobs, target_s=10.0, max_rounds=20):
     """The oracle's plain per-format loops (single thread, as the paper measured) on the same
     full-size inputs: rounds of one call each until about target_s seconds of CPU work."""
@@ -486,11 +511,18 @@ def main():
     traffic = read_traffic_file()
     kernels = []
     for it in items:
-        ms = float(np.mean([a.elapsed_time(b) for a, b in it.events]))
+        times = [a.elapsed_time(b) for a, b in it.events]
+        ms = float(np.mean(times))
         gbs = it.bytes / (ms * 1e-3) / 1e9
-        kernels.append({"name": it.name, "ms": round(ms, 4), "gflops": round(it.flops / (ms * 1e-3) / 1e9, 2),
+        tr = traffic.get(it.name)
+        kernels.append({"name": it.name, "ms": round(ms, 4), "ms_median": round(float(np.median(times)), 4),
+                        "ms_min": round(float(np.min(times)), 4),
+                        "gflops": round(it.flops / (ms * 1e-3) / 1e9, 2),
                         "alg_gbs": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
-                        "alg_bytes": it.bytes, "traffic": traffic.get(it.name)})
+                        "alg_bytes": it.bytes, "traffic": tr,
+                        # measured HBM-side bytes (rocprofv3 counters, profiles/) over the same time
+                        "hbm_gbs": round(tr / (ms * 1e-3) / 1e9, 1) if tr else None,
+                        "frac_hbm_peak_traffic": round(tr / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if tr else None})
         if it.note:
             kernels[-1]["note"] = it.note
     dom = max(kernels, key=lambda k: k["ms"])
@@ -513,6 +545,7 @@ def main():
     }
     if not args.no_ceilings:
         out["ceilings"] = measure_ceilings()
+        out["c1_warm"] = config1_warm()
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cpu_jobs)
     print(json.dumps(out), flush=True)
