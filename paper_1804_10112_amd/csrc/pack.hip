@@ -215,9 +215,12 @@ __global__ void set_i32_kernel(int32_t* out, int32_t v) {
   if (threadIdx.x == 0 && blockIdx.x == 0) *out = v;
 }
 
-// One lane per row: slot k of row i is the row's k-th entry, or padding. For a fixed k the
-// lanes write neighbouring cells; their reads walk neighbouring rows and stay in cache from
-// one k to the next. The longest row is reduced per workgroup and merged with one atomic.
+// A workgroup packs 256 consecutive rows. Their entries are one contiguous range of col /
+// vals: it is read lanes side by side in pieces of kEllCap entries into LDS, and every lane
+// then writes its row's cells (k, row) from LDS - neighbouring lanes write neighbouring
+// cells of the same slot - and the padding once the row has ended. The longest row is reduced
+// per workgroup and merged with one atomic.
+constexpr int kEllCap = 2048;
 template <typename VT>
 __global__ __launch_bounds__(kBlock) void ell_rows_kernel(int N, int W, const int32_t* __restrict__ pos,
                                                           const int32_t* __restrict__ col,
@@ -225,18 +228,43 @@ __global__ __launch_bounds__(kBlock) void ell_rows_kernel(int N, int W, const in
                                                           int32_t* __restrict__ crd_out,
                                                           VT* __restrict__ vals_out,
                                                           int32_t* __restrict__ longest) {
+  __shared__ int32_t s_col[kEllCap];
+  __shared__ VT s_val[kEllCap];
+  __shared__ int s_range[2];
   __shared__ int s_max[kBlock / kWave];
-  const int i = blockIdx.x * kBlock + threadIdx.x;
-  int a = 0, len = 0;
-  if (i < N) {
-    a = pos[i];
-    len = pos[i + 1] - a;
-    for (int k = 0; k < W; ++k) {
-      const bool in = k < len;
-      crd_out[static_cast<int64_t>(k) * N + i] = in ? col[a + k] : -1;
-      vals_out[static_cast<int64_t>(k) * N + i] = in ? vals[a + k] : VT(0);
-    }
+  const int row0 = blockIdx.x * kBlock;
+  const int i = row0 + threadIdx.x;
+  const bool live = i < N;
+  const int a = live ? pos[i] : 0;
+  const int len = live ? pos[i + 1] - a : 0;
+  if (threadIdx.x == 0) {
+    s_range[0] = a;
+    s_range[1] = pos[min(row0 + kBlock, N)];
   }
+  __syncthreads();
+  const int e0 = s_range[0], e1 = s_range[1];
+  const int stored = min(len, W);  // slots of this row that hold entries
+  for (int c0 = e0; c0 < e1; c0 += kEllCap) {
+    const int c1 = min(c0 + kEllCap, e1);
+    for (int q = c0 + threadIdx.x; q < c1; q += kBlock) {
+      s_col[q - c0] = col[q];
+      s_val[q - c0] = vals[q];
+    }
+    __syncthreads();
+    // slots of this row whose entries lie in the piece: k in [max(c0 - a, 0), min(c1 - a, stored))
+    const int k_lo = max(c0 - a, 0), k_hi = min(c1 - a, stored);
+    if (live)
+      for (int k = k_lo; k < k_hi; ++k) {
+        crd_out[static_cast<int64_t>(k) * N + i] = s_col[a + k - c0];
+        vals_out[static_cast<int64_t>(k) * N + i] = s_val[a + k - c0];
+      }
+    __syncthreads();
+  }
+  if (live)
+    for (int k = stored; k < W; ++k) {
+      crd_out[static_cast<int64_t>(k) * N + i] = -1;
+      vals_out[static_cast<int64_t>(k) * N + i] = VT(0);
+    }
   int m = len;
   for (int d = kWave / 2; d > 0; d >>= 1) m = max(m, __shfl_down(m, d, kWave));
   if (lane_id() == 0) s_max[wave_id()] = m;
