@@ -544,11 +544,19 @@ static spt_status spmv_sparse_x_typed(const spt_tensor* A, const spt_tensor* X, 
   const int64_t nnz = A->nvals, N = A->level[0].N;
   const T* vals = static_cast<const T*>(A->vals);
   if (X->nvals >= INT32_MAX) return fail(SPT_ERR_UNSUPPORTED, "spmv: x too large");
+  const int hint = A->level[1].max_children;  // declared short rows: the streamed kernel
+  const bool stream = hint > 0 && hint <= kShortRowHint && nnz > 0 && N + 1 < INT32_MAX && nnz < INT32_MAX;
   if (L.kind == SPT_HASHED) {
     if (L.M < 1) return fail(SPT_ERR_INVALID_ARG, "spmv: hashed x needs a table width W >= 1");
+    if (stream)
+      return launch_csr_stream<T, HashX<T>>(nnz, N, A->level[1].pos, A->level[1].crd, vals,
+                                            HashX<T>{L.crd, xv, (int)L.M}, y, s);
     return launch_seg_x<T, true, HashX<T>>(nnz, N, A->level[1].pos, A->level[1].crd, vals,
                                            HashX<T>{L.crd, xv, (int)L.M}, y, ws, ws_bytes, s);
   }
+  if (stream)
+    return launch_csr_stream<T, SparseX<T>>(nnz, N, A->level[1].pos, A->level[1].crd, vals,
+                                            SparseX<T>{L.crd, xv, (int)X->nvals}, y, s);
   return launch_seg_x<T, true, SparseX<T>>(nnz, N, A->level[1].pos, A->level[1].crd, vals,
                                            SparseX<T>{L.crd, xv, (int)X->nvals}, y, ws, ws_bytes, s);
 }
