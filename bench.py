@@ -66,7 +66,7 @@ def build_items(args):
 
     def on(name):
         if want is None:
-            return name not in ("x16", "n2", "n3", "n4", "n5")   # these groups run only on request
+            return name not in ("x14", "x16", "n2", "n3", "n4", "n5")   # these groups run only on request
         return name in want or name.split("_")[0] in want
 
     # ---- config 2: banded, 7 diagonals, fp64: DIA and CSR
@@ -162,6 +162,25 @@ def build_items(args):
         cpu_jobs.append(("c5_mttkrp_coo", lambda o, t=c5["coo"], C=c5["C"], D=c5["D"]: o.plain_mttkrp(t, C, D, "coo"),
                          3 * J * nnz))
         del c5
+    # ---- on request (--only x14): the other conversion order of Figure 14's pipeline: rows sorted,
+    #      input order kept inside a row (enough for SpMV), on config 4's unsorted COO
+    if on("x14"):
+        n4 = max(1024, int(4_000_000 * s))
+        c4 = wl.config4(N=n4, nnz_target=int(60_000_000 * s), max_row=max(8, int(200_000 * s)))
+        nnz = c4["nnz"]
+        A = spt.DeviceTensor(c4["coo"])
+        pos = torch.empty(n4 + 1, dtype=torch.int32, device=dev)
+        crd = torch.empty(nnz, dtype=torch.int32, device=dev)
+        vout = torch.empty(nnz, dtype=A.torch_dtype, device=dev)
+        wsc = A.workspace(spt.SPT_OP_COO_TO_CSR)
+        keep.extend([A, pos, crd, vout, wsc])
+        bits = lambda d: max(1, int(np.ceil(np.log2(max(d, 2)))))
+        for tag, order, passes in (("row_stable", spt.SPT_ORDER_ROW_STABLE, (bits(n4) + 7) // 8),
+                                   ("row_col", spt.SPT_ORDER_ROW_COL, 2 * ((bits(n4) + 7) // 8))):
+            items.append(Item(f"x14_coo_to_csr_{tag}",
+                              lambda order=order: spt.spt_coo_to_csr(A, order, pos, crd, vout, wsc), 0,
+                              passes * (4 + 32) * nnz + 4 * nnz + 12 * (n4 + 1), f"{passes} radix passes"))
+        del c4
     # ---- on request (--only x16): CSR SpMV on config 3's matrix with x as dense array,
     #      sparse vector and hash map at three densities (the experiment of Figure 16)
     if on("x16"):
