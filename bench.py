@@ -70,7 +70,7 @@ def build_items(args):
         return name in want or name.split("_")[0] in want
 
     # ---- config 2: banded, 7 diagonals, fp64: DIA and CSR
-    if on("c2"):
+    def group_c2():
         t0 = time.time()
         c2 = wl.config2(N=max(64, int(2_000_000 * s)))
         N, nnz = c2["dia"].dims[0], c2["nnz"]
@@ -80,7 +80,7 @@ def build_items(args):
         spmv_item("c2_csr_spmv", c2["csr"], c2["x"], 12 * nnz + 4 * (N + 1) + 16 * N, 2 * nnz, "csr")
         del c2
     # ---- config 3: row lengths 8..32, fp32: ELL and CSR
-    if on("c3"):
+    def group_c3():
         t0 = time.time()
         c3 = wl.config3(N=max(64, int(1_000_000 * s)))
         N, nnz, W = c3["ell"].dims[0], c3["nnz"], c3["W"]
@@ -89,7 +89,7 @@ def build_items(args):
         spmv_item("c3_csr_spmv", c3["csr"], c3["x"], 8 * nnz + 4 * (N + 1) + 8 * N, 2 * nnz, "csr")
         del c3
     # ---- config 4: power-law rows, fp64, unsorted COO: the three pipelines of Section 5.4
-    if on("c4"):
+    def group_c4():
         t0 = time.time()
         n4 = max(1024, int(4_000_000 * s))
         c4 = wl.config4(N=n4, nnz_target=int(60_000_000 * s), max_row=max(8, int(200_000 * s)))
@@ -131,7 +131,7 @@ def build_items(args):
                           12 * nnz + 4 * (N + 1) + 16 * N))
         del c4
     # ---- config 5: skewed 3rd-order tensor, fp32: TTV and MTTKRP on COO and CSF
-    if on("c5"):
+    def group_c5():
         t0 = time.time()
         dims = tuple(max(16, int(d * s)) for d in (100_000, 80_000, 50_000))
         c5 = wl.config5(dims=dims, nnz=max(1000, int(50_000_000 * s)))
@@ -164,7 +164,7 @@ def build_items(args):
         del c5
     # ---- on request (--only x14): the other conversion order of Figure 14's pipeline: rows sorted,
     #      input order kept inside a row (enough for SpMV), on config 4's unsorted COO
-    if on("x14"):
+    def group_x14():
         n4 = max(1024, int(4_000_000 * s))
         c4 = wl.config4(N=n4, nnz_target=int(60_000_000 * s), max_row=max(8, int(200_000 * s)))
         nnz = c4["nnz"]
@@ -183,7 +183,7 @@ def build_items(args):
         del c4
     # ---- on request (--only x16): CSR SpMV on config 3's matrix with x as dense array,
     #      sparse vector and hash map at three densities (the experiment of Figure 16)
-    if on("x16"):
+    def group_x16():
         c3 = wl.config3(N=max(64, int(1_000_000 * s)))
         N, nnz = c3["csr"].dims[0], c3["nnz"]
         A = spt.DeviceTensor(c3["csr"])
@@ -210,7 +210,7 @@ def build_items(args):
         del c3
     # ---- on request (--only n2): INNERPROD (Section 5.3) on config 5's tensor, with itself
     #      and with a tensor holding every third of its coordinates
-    if on("n2"):
+    def group_n2():
         dims = tuple(max(16, int(d * s)) for d in (100_000, 80_000, 50_000))
         c5 = wl.config5(dims=dims, nnz=max(1000, int(50_000_000 * s)))
         b = c5["coo"]
@@ -248,7 +248,7 @@ def build_items(args):
     # ---- on request (--only n3): sparse addition with sparse result. PLUS on config 5's tensor
     #      and a 10M-entry tensor of the same generator; COO and CSR matrix addition on config 4's
     #      sorted matrix and every second of its entries
-    if on("n3"):
+    def group_n3():
         dims = tuple(max(16, int(d * s)) for d in (100_000, 80_000, 50_000))
         c5 = wl.config5(dims=dims, nnz=max(1000, int(50_000_000 * s)))
         nb = c5["nnz"]
@@ -290,7 +290,7 @@ def build_items(args):
         del c4
     # ---- on request (--only n4): packers. Config 5's COO -> CSF, config 3's CSR -> ELL,
     #      config 2's matrix (as COO) -> DIA offsets + values
-    if on("n4"):
+    def group_n4():
         dims = tuple(max(16, int(d * s)) for d in (100_000, 80_000, 50_000))
         c5 = wl.config5(dims=dims, nnz=max(1000, int(50_000_000 * s)))
         nnz = c5["nnz"]
@@ -335,7 +335,7 @@ def build_items(args):
     # ---- on request (--only n5): compositions without a kernel of their own, read through the
     #      level functions per stored value: config 3's matrix as CSC and as DCSR (SpMV), and its
     #      ELL layout unpacked to COO
-    if on("n5"):
+    def group_n5():
         c3 = wl.config3(N=max(64, int(1_000_000 * s)))
         N3, nnz3 = c3["csr"].dims[0], c3["nnz"]
         (rr, cc), vv = oracle_free_coo(c3["csr"])
@@ -357,6 +357,26 @@ def build_items(args):
         items.append(Item("n5_ell_to_coo", lambda: spt.spt_to_coo(Ae, g0, g1, None, gv, gcnt, wg), 0,
                           2 * 8 * cells + 12 * nnz3, "cells read twice (count, fill)"))
         del c3
+    if on("c2"):
+        group_c2()
+    if on("c3"):
+        group_c3()
+    if on("c4"):
+        group_c4()
+    if on("c5"):
+        group_c5()
+    if on("x14"):
+        group_x14()
+    if on("x16"):
+        group_x16()
+    if on("n2"):
+        group_n2()
+    if on("n3"):
+        group_n3()
+    if on("n4"):
+        group_n4()
+    if on("n5"):
+        group_n5()
     return items, cpu_jobs, keep
 
 
