@@ -66,3 +66,76 @@ def test_kernels_without_atomics_are_bit_reproducible():
     p1 = gpu_coo_to_csr(c4["coo"], 0)
     p2 = gpu_coo_to_csr(c4["coo"], 0)
     assert all(np.array_equal(u, v) for u, v in zip(p1, p2))
+
+
+def test_widening_entry_points_in_a_captured_graph():
+    """Conversion, sparse addition, INNERPROD, TTM and the CSF packer enqueue only kernels (their
+    counts stay on the device), so a graph of them replays to the eager results bit for bit."""
+    import torch
+    import paper_1804_10112_amd as spt
+    dims = (60, 50, 70)
+    bi, bj, bk, bv = wl.random_coo3_entries(dims, 20_000, 1, dtype=np.float32, dist="u11", skew=1.3)
+    ci, cj, ck, cv = wl.random_coo3_entries(dims, 15_000, 2, dtype=np.float32, dist="u11")
+    B = spt.DeviceTensor(wl.coo3_spec(dims, bi, bj, bk, bv))
+    Ct = spt.DeviceTensor(wl.coo3_spec(dims, ci, cj, ck, cv))
+    c4 = wl.config4(N=5000, nnz_target=60_000, max_row=3000)
+    M = spt.DeviceTensor(c4["coo"])
+    nnz_m = len(c4["coo"].vals)
+    i32 = lambda n: torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    cap = 35_000
+    outs = {
+        "add": [i32(cap), i32(cap), i32(cap), torch.zeros(cap, device="cuda"), torch.zeros(1, dtype=torch.int64, device="cuda")],
+        "ip": [torch.zeros(1, device="cuda")],
+        "ttm": [i32(20_000), i32(20_000), torch.zeros(20_000, 8, device="cuda"), torch.zeros(1, dtype=torch.int64, device="cuda")],
+        "csf": [i32(2), i32(20_000), i32(20_001), i32(20_000), i32(20_001), i32(20_000),
+                torch.zeros(20_000, device="cuda"), torch.zeros(2, dtype=torch.int64, device="cuda")],
+        "csr": [i32(5001), i32(nnz_m), torch.zeros(nnz_m, dtype=torch.float64, device="cuda")],
+    }
+    Ck = torch.from_numpy(np.random.default_rng(3).uniform(-1, 1, (8, 70)).astype(np.float32)).cuda()
+    ws = {"add": torch.empty(spt.spt_add_workspace_bytes(B, Ct), dtype=torch.uint8, device="cuda"),
+          "ip": B.workspace(spt.SPT_OP_INNERPROD), "ttm": B.workspace(spt.SPT_OP_TTM, 8),
+          "csf": B.workspace(spt.SPT_OP_TO_CSF), "csr": M.workspace(spt.SPT_OP_COO_TO_CSR)}
+
+    def run_all():
+        a = outs["add"]
+        spt.spt_add(B, Ct, None, a[0], a[1], a[2], a[3], a[4], ws["add"])
+        spt.spt_innerprod(B, Ct, outs["ip"][0], ws["ip"])
+        t = outs["ttm"]
+        spt.spt_ttm(B, Ck, 8, t[0], t[1], t[2], t[3], ws["ttm"])
+        spt.spt_coo3_to_csf(B, *outs["csf"], ws["csf"])
+        r = outs["csr"]
+        spt.spt_coo_to_csr(M, spt.SPT_ORDER_ROW_COL, r[0], r[1], r[2], ws["csr"])
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run_all()
+    side.synchronize()
+    eager = {k: [t.clone() for t in v] for k, v in outs.items()}
+    assert int(eager["add"][4].item()) > 20_000 and int(eager["ttm"][3].item()) > 0
+
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run_all()
+    for rep in range(3):
+        for v in outs.values():
+            for t in v:
+                t.fill_(-3)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        n_add, n_fib = int(outs["add"][4].item()), int(outs["ttm"][3].item())
+        for k, v in outs.items():
+            for j, (t, e) in enumerate(zip(v, eager[k])):
+                n = {"add": n_add, "ttm": n_fib}.get(k)
+                if n is not None and t.shape[0] >= n and t.dim() >= 1 and t.shape[0] > 2:
+                    t, e = t[:n], e[:n]                     # capacity beyond the count is never written
+                if k == "csf" and t.shape[0] > 2:
+                    continue                                 # compared through their counts below
+                assert torch.equal(t, e), f"replay {rep}: {k}[{j}] differs"
+        n0, n1 = (int(z) for z in outs["csf"][7].cpu())
+        e = eager["csf"]
+        assert torch.equal(outs["csf"][1][:n0], e[1][:n0]) and torch.equal(outs["csf"][2][:n0 + 1], e[2][:n0 + 1])
+        assert torch.equal(outs["csf"][3][:n1], e[3][:n1]) and torch.equal(outs["csf"][4][:n1 + 1], e[4][:n1 + 1])
+        nb = len(bv)
+        assert torch.equal(outs["csf"][5][:nb], e[5][:nb]) and torch.equal(outs["csf"][6][:nb], e[6][:nb])
