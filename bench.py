@@ -244,6 +244,17 @@ def build_items(args):
                           2 * K * nnz, 16 * nnz + 8 * nfib + out_b, "output fibres dominate the bytes"))
         items.append(Item("n2_ttm_csf", lambda: spt.spt_ttm(Bf, Ck, K, None, None, tv, tcnt, w4),
                           2 * K * nnz, 8 * nnz + 4 * nfib + out_b, "output fibres dominate the bytes"))
+        # SpDM (Figure 11) with 32 columns: config 3's matrix as ordered COO (fp32) times a dense matrix
+        c3 = wl.config3(N=max(64, int(1_000_000 * s)))
+        N3, nnz3 = c3["csr"].dims[0], c3["nnz"]
+        (r3, q3), v3 = oracle_free_coo(c3["csr"])
+        Am = spt.DeviceTensor(wl.coo_spec(N3, N3, r3, q3, v3))
+        Cd = up(np.random.default_rng(10).uniform(0, 1, (N3, 32)).astype(np.float32))
+        Ad = torch.empty(N3, 32, dtype=torch.float32, device=dev)
+        w5 = Am.workspace(spt.SPT_OP_MTTKRP, 32)
+        keep.extend([Am, Ad, w5])
+        items.append(Item("n2_spdm_coo", lambda: spt.spt_spdm(Am, Cd, 32, Ad, w5), 2 * 32 * nnz3,
+                          12 * nnz3 + 2 * 4 * 32 * N3, "compulsory HBM bytes; rows of C are gathered from cache"))
         del c5
     # ---- on request (--only n3): sparse addition with sparse result. PLUS on config 5's tensor
     #      and a 10M-entry tensor of the same generator; COO and CSR matrix addition on config 4's
