@@ -41,6 +41,7 @@ def _compositions(N, M, r, c, v, dense=True):
         "dcsr": wl.dcsr_from_sorted_coo(N, M, r, c, v),
         "csc": wl.csc_from_coo(N, M, r, c, v),
         "dhash": wl.hashed_rows_from_coo(N, M, r, c, v, W=1 << int(np.ceil(np.log2(2 * np.bincount(r).max() + 1)))),
+        "sdia": wl.sparse_dia_from_coo(N, M, r, c, v),      # (dense, compressed, offset)
     }
     if dense:
         D = np.zeros((N, M), v.dtype)

@@ -209,6 +209,7 @@ def test_other_matrix_compositions_walk_to_the_same_entries_and_products():
         "csc": wl.csc_from_coo(N, M, r, c, v),
         "dense": wl.dense_matrix_spec(S.toarray()),
         "dhash": wl.hashed_rows_from_coo(N, M, r, c, v, W=16),
+        "sdia": wl.sparse_dia_from_coo(N, M, r, c, v),     # (dense, compressed, offset), Section 3.1
     }
     assert len(specs["dcsr"].levels[0].crd) < N
     for name, spec in specs.items():

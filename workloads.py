@@ -198,6 +198,21 @@ def hashed_rows_from_coo(N, M, row, col, vals, W, name="dhash") -> TensorSpec:
     ], tv, name)
 
 
+def sparse_dia_from_coo(N, M, row, col, vals, name="sdia") -> TensorSpec:
+    """(dense diagonals, compressed rows, offset cols): DIA for sparsely filled diagonals; only
+    the rows that hold an entry on a diagonal are stored, the column is row + offset[d]."""
+    row, col, vals = np.asarray(row, np.int64), np.asarray(col, np.int64), np.asarray(vals)
+    off = np.unique(col - row)
+    d = np.searchsorted(off, col - row)
+    order = np.lexsort((row, d))
+    pos = np.searchsorted(d[order], np.arange(len(off) + 1), side="left")
+    return TensorSpec((N, M), [
+        LevelSpec(DENSE, -1, len(off)),
+        LevelSpec(COMPRESSED, 0, N, M=len(off), pos=_i32(pos), crd=_i32(row[order])),
+        LevelSpec(OFFSET, 1, M, offset=_i32(off)),
+    ], np.ascontiguousarray(vals[order]), name)
+
+
 def dcc3_from_sorted_coo(dims, ci, cj, ck, vals, name="dcc3") -> TensorSpec:
     """3rd-order (dense, compressed, compressed): CSF with a dense first level."""
     ci, cj = np.asarray(ci, np.int64), np.asarray(cj, np.int64)
