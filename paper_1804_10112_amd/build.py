@@ -29,5 +29,23 @@ def build(verbose: bool = False) -> str:
     return SO
 
 
+EXAMPLE_SRC = os.path.join(os.path.dirname(HERE), "examples", "c_abi_demo.c")
+EXAMPLE_BIN = os.path.join(os.path.dirname(HERE), "examples", "c_abi_demo")
+
+
+def build_example(verbose: bool = False) -> str:
+    """Compiles examples/c_abi_demo.c with the host C compiler (C99) against include/spt.h,
+    libspt.so and the HIP runtime: the ABI is usable from plain C."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c99", "-O2", "-Wall", "-Wextra", "-D__HIP_PLATFORM_AMD__", f"-I{rocm}/include",
+           EXAMPLE_SRC, "-o", EXAMPLE_BIN, f"-L{HERE}", "-lspt", f"-L{rocm}/lib", "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../paper_1804_10112_amd", f"-Wl,-rpath,{rocm}/lib"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return EXAMPLE_BIN
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_example(verbose=True))
