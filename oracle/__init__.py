@@ -63,6 +63,8 @@ def lib():
         L.orc_ttm.argtypes = [vp, vp, C.c_int32, C.c_int64, C.c_int64, vp, vp, vp, vp]
         L.orc_pack_csf.restype = C.c_int64
         L.orc_pack_csf.argtypes = [vp] * 10
+        L.orc_pack_hashed_rows.restype = C.c_int64
+        L.orc_pack_hashed_rows.argtypes = [vp, vp, C.c_int64, vp, vp]
         L.orc_pack_ell.restype = C.c_int64
         L.orc_pack_ell.argtypes = [vp, vp, C.c_int64, vp, vp]
         L.orc_dia_offsets.restype = C.c_int64
@@ -277,6 +279,17 @@ def pack_csf(spec):
         raise ValueError("orc_pack_csf: unsupported tensor")
     n0, n1 = int(counts[0]), int(counts[1])
     return pos0, crd0[:n0], pos1[:n0 + 1], crd1[:n1], pos2[:n1 + 1], crd2[:nnz], vals[:nnz]
+
+
+def pack_hashed_rows(spec, W):
+    """(crd[N, W], vals[N, W], dropped) of the matrix packed as (dense rows, hashed columns)."""
+    T = OTensor(spec)
+    N = spec.dims[0]
+    dims = np.asarray(spec.dims, np.int64)
+    crd = np.zeros((N, W), np.int32)
+    vals = np.zeros((N, W), np.float64)
+    dropped = lib().orc_pack_hashed_rows(T.ref, _ptr(dims), W, _ptr(crd), _ptr(vals))
+    return crd, vals, int(dropped)
 
 
 def pack_ell(spec, W):

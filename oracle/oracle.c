@@ -438,6 +438,34 @@ int64_t orc_pack_csf(const orc_tensor* B, const int64_t* dims, int32_t* pos0, in
   return n;
 }
 
+int64_t orc_pack_hashed_rows(const orc_tensor* A, const int64_t* dims, int64_t W, int32_t* crd,
+                             double* vals) {
+  int64_t N = dims[0], M = dims[1], n, dropped = 0;
+  for (int64_t q = 0; q < N * W; ++q) { /* insert_init */
+    crd[q] = -1;
+    vals[q] = 0.0;
+  }
+  orc_level H = {0};
+  H.kind = ORC_HASHED;
+  H.N = M;
+  H.M = W;
+  H.crd = crd;
+  kv_pair* e = linearise(A, dims, &n);
+  for (int64_t p = 0; p < n; ++p) {
+    int64_t i = e[p].key / M, j = e[p].key % M;
+    int32_t found;
+    int64_t slot = orc_hashed_locate(&H, i, j, &found); /* locate, then insert_coord */
+    if (found || crd[slot] == -1) {
+      crd[slot] = (int32_t)j;
+      vals[slot] = e[p].val;
+    } else {
+      ++dropped;
+    }
+  }
+  free(e);
+  return dropped;
+}
+
 int64_t orc_pack_ell(const orc_tensor* A, const int64_t* dims, int64_t W, int32_t* crd,
                      double* vals) {
   int64_t N = dims[0], M = dims[1], n;

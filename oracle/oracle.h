@@ -114,6 +114,14 @@ int64_t orc_add(const orc_tensor* B, const orc_tensor* C, const int64_t* dims, i
  * orc_dia_offsets: the distinct values of col - row, ascending (at most cap are written);
  * returns their number K. orc_pack_dia: cell (d, i) at d*N + i = the entry of row i on
  * diagonal offsets[d], zero where none is stored (coordinates unique). */
+/* orc_pack_hashed_rows: the matrix as (dense rows, hashed columns of width W), assembled with
+ * Table 3's insert functions: insert_init fills crd with -1; every entry (walked in order of
+ * linearised coordinate) is inserted at the position the hashed level's locate returns (first
+ * slot at or after j % W, wrapping, that holds j or is empty). Returns the number of entries
+ * that found their row's table full. */
+int64_t orc_pack_hashed_rows(const orc_tensor* A, const int64_t* dims, int64_t W, int32_t* crd,
+                             double* vals);
+
 int64_t orc_pack_csf(const orc_tensor* B, const int64_t* dims, int32_t* pos0, int32_t* crd0,
                      int32_t* pos1, int32_t* crd1, int32_t* pos2, int32_t* crd2, double* vals,
                      int64_t* counts);

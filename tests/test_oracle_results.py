@@ -543,3 +543,28 @@ def test_pack_dia_vs_scipy():
     dense = np.zeros((N, M))
     dense[c2[0], c2[1]] = w2
     assert np.array_equal(dense, sp.coo_matrix((v, (r, c)), shape=(N, M)).toarray())
+
+
+def test_pack_hashed_rows_against_the_generators_tables_and_locate():
+    """Table 3's hashed insert: the generator's independent Python insertion (same visiting order)
+    builds the same tables; every stored coordinate is found by the hashed level's locate; the
+    level walk returns exactly the entries; a full table reports what it had to drop."""
+    N, M, W = 17, 40, 16
+    r, c, v = wl.random_coo_entries(N, M, 120, seed=95, dtype=np.float64)
+    coo = wl.coo_spec(N, M, r, c, v)
+    crd, vals, dropped = oracle.pack_hashed_rows(coo, W)
+    assert dropped == 0
+    ref = wl.hashed_rows_from_coo(N, M, r, c, v, W)
+    assert np.array_equal(crd.reshape(-1), ref.levels[1].crd) and np.array_equal(vals.reshape(-1), ref.vals)
+    packed = wl.TensorSpec((N, M), ref.levels, vals.reshape(-1).copy())
+    for i, j in zip(r, c):                                       # locate finds every inserted coordinate
+        p, found = oracle.hashed_locate(packed.levels[1], int(i), int(j))
+        assert found and crd.reshape(-1)[p] == j
+    co, w = oracle.to_coo(packed)
+    o = np.lexsort((co[1], co[0]))
+    assert np.array_equal(co[0][o], r) and np.array_equal(co[1][o], c) and np.array_equal(w[o], v)
+    # a row with more entries than slots: the surplus is reported, the table stays consistent
+    rows = np.zeros(6, int)
+    cols = np.array([0, 4, 8, 12, 16, 20])
+    crd2, vals2, dropped2 = oracle.pack_hashed_rows(wl.coo_spec(2, 40, rows, cols, np.arange(6.0)), 4)
+    assert dropped2 == 2 and np.count_nonzero(crd2 >= 0) == 4 and np.all(crd2[1] == -1)
