@@ -262,6 +262,14 @@ spt_status spt_innerprod(const spt_tensor* B, const spt_tensor* C, void* alpha_o
  *   row; if it exceeds W the entries beyond slot W-1 were left out. Workspace: SPT_OP_TO_ELL
  *   (needed for COO only).
  *
+ * spt_to_hashed_rows: A = COO matrix (any order, entries with W > 0 and rows non-empty of
+ *   slots). Output = (dense rows, hashed columns of width W): crd_out / vals_out with N*W
+ *   entries each; Table 3's hashed insert: crd is filled with -1, then every entry takes the
+ *   first slot at or after col % W (wrapping, inside its row's segment) that is empty or already
+ *   holds its column. When two columns of a row collide, which gets the earlier slot is not
+ *   fixed (any result is a table in which locate finds every stored column). *dropped_dev
+ *   (device int32) receives the number of entries whose row segment was full. No workspace.
+ *
  * spt_coo_dia_offsets: A = COO matrix (any order). The distinct values of col - row,
  *   ascending, go to offsets_out (at most cap of them); *K_dev (device int64) receives their
  *   number. Workspace: SPT_OP_DIA_OFFSETS.
@@ -274,6 +282,8 @@ spt_status spt_coo3_to_csf(const spt_tensor* B, int32_t* pos0, int32_t* crd0, in
                            int64_t* counts_dev, void* ws, size_t ws_bytes, void* stream);
 spt_status spt_to_ell(const spt_tensor* A, int32_t W, int32_t* crd_out, void* vals_out,
                       int32_t* longest_dev, void* ws, size_t ws_bytes, void* stream);
+spt_status spt_to_hashed_rows(const spt_tensor* A, int32_t W, int32_t* crd_out, void* vals_out,
+                              int32_t* dropped_dev, void* stream);
 spt_status spt_coo_dia_offsets(const spt_tensor* A, int32_t* offsets_out, int64_t cap,
                                int64_t* K_dev, void* ws, size_t ws_bytes, void* stream);
 spt_status spt_coo_to_dia(const spt_tensor* A, int32_t K, const int32_t* offsets, void* vals_out,

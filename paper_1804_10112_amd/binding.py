@@ -27,7 +27,7 @@ SYMBOLS = ["spt_spmv", "spt_coo_to_csr", "spt_ttv", "spt_mttkrp", "spt_workspace
            "spt_last_error", "spt_version", "spt_probe_read", "spt_probe_gather",
            "spt_spmv_sparse_x", "spt_spdm", "spt_innerprod", "spt_ttm",
            "spt_add", "spt_add_workspace_bytes", "spt_coo3_to_csf", "spt_to_ell",
-           "spt_coo_dia_offsets", "spt_coo_to_dia", "spt_to_coo"]
+           "spt_coo_dia_offsets", "spt_coo_to_dia", "spt_to_coo", "spt_to_hashed_rows"]
 
 
 class SptLevel(C.Structure):
@@ -79,6 +79,8 @@ def lib():
         L.spt_coo_dia_offsets.argtypes = [vp, vp, C.c_int64, vp, vp, sz, vp]
         L.spt_coo_to_dia.restype = i32
         L.spt_coo_to_dia.argtypes = [vp, i32, vp, vp, vp]
+        L.spt_to_hashed_rows.restype = i32
+        L.spt_to_hashed_rows.argtypes = [vp, i32, vp, vp, vp, vp]
         L.spt_to_coo.restype = i32
         L.spt_to_coo.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.spt_add.restype = i32
@@ -219,6 +221,11 @@ def spt_coo_dia_offsets(A, offsets_out, cap, K_dev, ws=None, stream=None):
 
 def spt_coo_to_dia(A, K, offsets, vals_out, stream=None):
     _check(lib().spt_coo_to_dia(_desc(A), K, _p(offsets), _p(vals_out), _stream(stream)))
+
+
+def spt_to_hashed_rows(A, W, crd_out, vals_out, dropped_dev, stream=None):
+    _check(lib().spt_to_hashed_rows(_desc(A), W, _p(crd_out), _p(vals_out), _p(dropped_dev),
+                                    _stream(stream)))
 
 
 def spt_to_coo(T, out_crd0, out_crd1, out_crd2, out_vals, out_nnz_dev, ws=None, stream=None):

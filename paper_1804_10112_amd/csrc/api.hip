@@ -60,6 +60,8 @@ size_t pack_csf_workspace(int64_t nnz);
 spt_status pack_ell_dispatch(Format f, const spt_tensor* A, int32_t W, int32_t* crd_out, void* vals_out,
                              int32_t* longest, void* ws, size_t ws_bytes, hipStream_t s);
 size_t pack_ell_workspace(Format f, const spt_tensor* A);
+spt_status pack_hashed_dispatch(const spt_tensor* A, int32_t W, int32_t* crd_out, void* vals_out,
+                                int32_t* dropped, hipStream_t s);
 spt_status dia_offsets_dispatch(const spt_tensor* A, int32_t* offsets_out, int64_t cap, int64_t* K_dev,
                                 void* ws, size_t ws_bytes, hipStream_t s);
 size_t dia_offsets_workspace(const spt_tensor* A);
@@ -424,6 +426,17 @@ spt_status spt_to_ell(const spt_tensor* A, int32_t W, int32_t* crd_out, void* va
     return fail(SPT_ERR_INVALID_ARG, "to_ell: null output");
   return pack_ell_dispatch(f, A, W, crd_out, vals_out, longest_dev, ws, ws_bytes,
                            static_cast<hipStream_t>(stream));
+}
+
+spt_status spt_to_hashed_rows(const spt_tensor* A, int32_t W, int32_t* crd_out, void* vals_out,
+                              int32_t* dropped_dev, void* stream) {
+  clear_error();
+  Format f = recognize(A);
+  if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
+  if (f != Format::COO2) return fail(SPT_ERR_UNSUPPORTED, "to_hashed_rows: A must be a COO matrix");
+  if (W < 1) return fail(SPT_ERR_INVALID_ARG, "to_hashed_rows: W = %d, at least one slot per row needed", W);
+  if (!crd_out || !vals_out || !dropped_dev) return fail(SPT_ERR_INVALID_ARG, "to_hashed_rows: null output");
+  return pack_hashed_dispatch(A, W, crd_out, vals_out, dropped_dev, static_cast<hipStream_t>(stream));
 }
 
 spt_status spt_coo_dia_offsets(const spt_tensor* A, int32_t* offsets_out, int64_t cap,

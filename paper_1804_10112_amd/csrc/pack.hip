@@ -420,6 +420,66 @@ spt_status pack_dia_dispatch(const spt_tensor* A, int32_t K, const int32_t* offs
   return pack_dia_typed<uint32_t>(A, K, offsets, static_cast<uint32_t*>(vals_out), s);
 }
 
+// ================================================================ COO -> (dense rows, hashed cols)
+
+// Table 3's hashed insert on the device: insert_init is the fill with -1; an entry (i, j) then
+// walks the probe sequence of locate (Table 2: from j % W, +1 with wrap) inside row i's segment
+// and claims the first empty slot with a compare-and-swap, or finds j already there. Which of
+// two colliding coordinates gets the earlier slot depends on the order the lanes arrive: the
+// table is one of the valid ones, not a fixed one. Entries of a full segment are counted.
+template <typename VT>
+__global__ __launch_bounds__(kBlock) void hashed_insert_kernel(int nnz, int W,
+                                                               const int32_t* __restrict__ row,
+                                                               const int32_t* __restrict__ col,
+                                                               const VT* __restrict__ vals,
+                                                               int32_t* __restrict__ crd,
+                                                               VT* __restrict__ out,
+                                                               int32_t* __restrict__ dropped) {
+  const int p = blockIdx.x * kBlock + threadIdx.x;
+  if (p >= nnz) return;
+  const int j = col[p];
+  const int64_t base = static_cast<int64_t>(row[p]) * W;
+  int q = j % W;
+  for (int t = 0; t < W; ++t) {  // at most one full cycle
+    const int32_t seen = atomicCAS(crd + base + q, -1, j);
+    if (seen == -1 || seen == j) {
+      out[base + q] = vals[p];
+      return;
+    }
+    q = q + 1 == W ? 0 : q + 1;
+  }
+  atomicAdd(dropped, 1);
+}
+
+template <typename VT>
+static spt_status pack_hashed_typed(const spt_tensor* A, int W, int32_t* crd_out, VT* vals_out,
+                                    int32_t* dropped, hipStream_t s) {
+  const int64_t N = A->level[0].N, nnz = A->nvals, cells = N * W;
+  if (nnz >= INT32_MAX || N >= INT32_MAX) return fail(SPT_ERR_UNSUPPORTED, "to_hashed_rows: matrix too large");
+  hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(kWave), 0, s, dropped, 0);
+  SPT_CHECK_LAUNCH("hashed set dropped");
+  if (cells > 0) {
+    const unsigned g = static_cast<unsigned>((cells + kBlock - 1) / kBlock);
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(g), dim3(kBlock), 0, s, crd_out, cells, -1);
+    hipLaunchKernelGGL(fill_vt_kernel<VT>, dim3(g), dim3(kBlock), 0, s, vals_out, cells);
+    SPT_CHECK_LAUNCH("hashed insert_init");
+  }
+  if (nnz > 0) {
+    hipLaunchKernelGGL(hashed_insert_kernel<VT>, dim3(static_cast<unsigned>((nnz + kBlock - 1) / kBlock)),
+                       dim3(kBlock), 0, s, static_cast<int>(nnz), W, A->level[0].crd, A->level[1].crd,
+                       static_cast<const VT*>(A->vals), crd_out, vals_out, dropped);
+    SPT_CHECK_LAUNCH("hashed insert");
+  }
+  return SPT_OK;
+}
+
+spt_status pack_hashed_dispatch(const spt_tensor* A, int32_t W, int32_t* crd_out, void* vals_out,
+                                int32_t* dropped, hipStream_t s) {
+  if (A->dtype == SPT_F64)
+    return pack_hashed_typed<uint64_t>(A, W, crd_out, static_cast<uint64_t*>(vals_out), dropped, s);
+  return pack_hashed_typed<uint32_t>(A, W, crd_out, static_cast<uint32_t*>(vals_out), dropped, s);
+}
+
 spt_status pack_ell_dispatch(Format f, const spt_tensor* A, int32_t W, int32_t* crd_out, void* vals_out,
                              int32_t* longest, void* ws, size_t ws_bytes, hipStream_t s) {
   if (A->dtype == SPT_F64)

@@ -210,3 +210,68 @@ def test_packers_full_size():
         i = np.arange(N)
         want[d, (i + o < 0) | (i + o >= N)] = 0
     assert np.array_equal(gv, want)
+
+
+def gpu_to_hashed_rows(spec, W):
+    import torch
+    import paper_1804_10112_amd as spt
+    A = spt.DeviceTensor(spec)
+    N = spec.dims[0]
+    crd = torch.full((N * W,), 77, dtype=torch.int32, device="cuda")
+    vals = torch.full((N * W,), float("nan"), dtype=A.torch_dtype, device="cuda")
+    dropped = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    spt.spt_to_hashed_rows(A, W, crd, vals, dropped)
+    torch.cuda.synchronize()
+    return crd.cpu().numpy().reshape(N, W), vals.cpu().numpy().reshape(N, W), int(dropped.item())
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("ordered", [True, False])
+def test_to_hashed_rows_is_a_valid_table(dtype, ordered):
+    """Table 3's hashed insert with concurrent lanes: which colliding column takes the earlier
+    slot is not fixed, so the table is checked for what is unique (the stored set, the values,
+    emptiness elsewhere) and for validity (locate's probe sequence reaches every stored column
+    before an empty slot); the packed matrix then multiplies like the original."""
+    N, M, W = 3000, 5000, 64
+    r, c, v = wl.random_coo_entries(N, M, 60_000, seed=1900, dtype=dtype, sort=ordered)
+    coo = wl.coo_spec(N, M, r, c, v, ordered=ordered)
+    crd, vals, dropped = gpu_to_hashed_rows(coo, W)
+    assert dropped == 0
+    rr, qq = np.nonzero(crd >= 0)
+    got = np.lexsort((crd[rr, qq], rr))
+    want = np.lexsort((c, r))
+    assert np.array_equal(rr[got], r[want]) and np.array_equal(crd[rr, qq][got], c[want])
+    assert np.array_equal(vals[rr, qq][got], v[want])
+    assert np.all(crd[crd < 0] == -1) and np.all(vals[crd < 0] == 0)
+    # probe sequence: every slot between col % W and the column's slot (cyclically) is occupied
+    start = crd[rr, qq] % W
+    dist = (qq - start) % W
+    for d in range(1, int(dist.max()) + 1):
+        m = dist >= d
+        assert np.all(crd[rr[m], (start[m] + d - 1) % W] >= 0)
+    ocrd, ovals, odropped = oracle.pack_hashed_rows(coo, W)
+    assert odropped == 0 and np.array_equal(np.sort(ocrd, axis=1), np.sort(crd, axis=1))
+    packed = wl.TensorSpec((N, M), wl.hashed_rows_from_coo(2, 2, [], [], np.zeros(0, dtype), W).levels, vals.reshape(-1))
+    packed.levels[0].N, packed.levels[1].N = N, M
+    packed.levels[1].crd = crd.reshape(-1)
+    x = wl.dense_vector(M, 3, dtype)
+    ref, mag = oracle.spmv(coo, x)
+    assert_close(gpu_spmv(packed, x), ref, mag, dtype, "spmv on the packed (dense, hashed) matrix")
+
+
+def test_to_hashed_rows_collision_free_layout_and_full_rows():
+    # distinct residues per row: no collisions, the layout is the oracle's bit for bit
+    N, M, W = 50, 64, 64
+    r = np.repeat(np.arange(N), 10)
+    c = np.tile(np.arange(0, 60, 6), N) + (np.arange(N * 10) // 10) % 4
+    v = np.arange(N * 10, dtype=np.float64)
+    coo = wl.coo_spec(N, M, r, c, v)
+    crd, vals, dropped = gpu_to_hashed_rows(coo, W)
+    ocrd, ovals, _ = oracle.pack_hashed_rows(coo, W)
+    assert dropped == 0 and np.array_equal(crd, ocrd) and np.array_equal(vals, ovals)
+    # six columns for four slots in row 0: two are dropped, the table stays consistent
+    rows = np.zeros(6, int)
+    cols = np.array([0, 4, 8, 12, 16, 20])
+    crd, vals, dropped = gpu_to_hashed_rows(wl.coo_spec(2, 40, rows, cols, np.arange(6.0)), 4)
+    assert dropped == 2 and np.count_nonzero(crd[0] >= 0) == 4 and np.all(crd[1] == -1)
+    assert set(crd[0]) <= set(cols) and all(vals[0][q] == list(cols).index(crd[0][q]) for q in range(4))
