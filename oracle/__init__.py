@@ -73,6 +73,8 @@ def lib():
         L.orc_pack_dia.argtypes = [vp, vp, C.c_int64, vp, vp]
         L.orc_add.restype = C.c_int64
         L.orc_add.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp]
+        L.orc_mul.restype = C.c_int64
+        L.orc_mul.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp]
         L.orc_innerprod.restype = C.c_double
         L.orc_innerprod.argtypes = [vp, vp, vp, vp]
         L.orc_coo_to_csr.restype = None
@@ -261,6 +263,24 @@ def add(bspec, cspec):
     n = lib().orc_add(TB.ref, TC.ref, _ptr(dims), cap, ptrs, _ptr(v), _ptr(mag))
     if n < 0:
         raise ValueError("orc_add: unsupported operands")
+    return [c[:n] for c in crd], v[:n], mag[:n]
+
+
+def mul(bspec, cspec):
+    """Reference A = B .* C: (list of coordinate arrays, values, magnitudes), ordered, intersection."""
+    if tuple(bspec.dims) != tuple(cspec.dims):
+        raise ValueError("operands differ in shape")
+    TB, TC = OTensor(bspec), OTensor(cspec)
+    order = len(bspec.dims)
+    dims = np.asarray(bspec.dims, np.int64)
+    cap = max(min(lib().orc_count(TB.ref), lib().orc_count(TC.ref)), 1)
+    crd = [np.zeros(cap, np.int32) for _ in range(order)]
+    ptrs = (C.c_void_p * order)(*[c.ctypes.data for c in crd])
+    v = np.zeros(cap, np.float64)
+    mag = np.zeros(cap, np.float64)
+    n = lib().orc_mul(TB.ref, TC.ref, _ptr(dims), cap, ptrs, _ptr(v), _ptr(mag))
+    if n < 0:
+        raise ValueError("orc_mul: unsupported operands")
     return [c[:n] for c in crd], v[:n], mag[:n]
 
 

@@ -400,6 +400,30 @@ int64_t orc_add(const orc_tensor* B, const orc_tensor* C, const int64_t* dims, i
   return n;
 }
 
+int64_t orc_mul(const orc_tensor* B, const orc_tensor* C, const int64_t* dims, int64_t cap,
+                int32_t* const* out_crd, double* out_v, double* out_mag) {
+  long double space = 1.0L;
+  for (int m = 0; m < B->order; ++m) space *= (long double)dims[m];
+  if (B->order != C->order || space >= 9.0e18L) return -1;
+  int64_t nb, nc;
+  kv_pair* b = linearise(B, dims, &nb);
+  kv_pair* c = linearise(C, dims, &nc);
+  int64_t pb = 0, pc = 0, n = 0;
+  while (pb < nb && pc < nc) { /* intersection: the loop ends with the first exhausted operand */
+    int64_t ib = b[pb].key, ic = c[pc].key;
+    int64_t i = ib < ic ? ib : ic; /* the coordinate visited in this step */
+    if (ib == i && ic == i) {
+      double v = b[pb].val * c[pc].val;
+      emit_sum(B->order, dims, i, v, fabs(v), n++, cap, out_crd, out_v, out_mag);
+    }
+    if (ib == i) ++pb; /* each operand that holds the coordinate moves on */
+    if (ic == i) ++pc;
+  }
+  free(b);
+  free(c);
+  return n;
+}
+
 int64_t orc_pack_csf(const orc_tensor* B, const int64_t* dims, int32_t* pos0, int32_t* crd0,
                      int32_t* pos1, int32_t* crd1, int32_t* pos2, int32_t* crd2, double* vals,
                      int64_t* counts) {

@@ -97,6 +97,14 @@ double orc_innerprod(const orc_tensor* B, const orc_tensor* C, const int64_t* di
 int64_t orc_add(const orc_tensor* B, const orc_tensor* C, const int64_t* dims, int64_t cap,
                 int32_t* const* out_crd, double* out_v, double* out_mag);
 
+/* A = B .* C (element-wise product) with a sparse result: the intersection merge of Section 4.4
+ * (the running example of Sections 1 and 4, Figure 1): both operands are walked in order of
+ * linearised coordinate, the one with the smaller coordinate advances, and only a coordinate
+ * stored in both produces an entry (the product; products that are zero stay stored).
+ * Arguments and return as orc_add; out_mag = |b * c|. */
+int64_t orc_mul(const orc_tensor* B, const orc_tensor* C, const int64_t* dims, int64_t cap,
+                int32_t* const* out_crd, double* out_v, double* out_mag);
+
 /* Packing a tensor (any format) into CSF, ELL or DIA, Section 3.4: the entries are walked,
  * ordered by linearised coordinate, and appended (CSF, ELL) or inserted (DIA) into the
  * target's levels. Values are returned as double (exact for fp32 and fp64 sources).

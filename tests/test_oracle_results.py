@@ -459,6 +459,66 @@ def test_add_third_order_vs_dense_and_closed_forms():
     assert np.array_equal(fi, oi) and np.array_equal(fk, ok) and np.array_equal(fv, v)
 
 
+# ------------------------------------------------------------------ sparse multiply (intersection merge)
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_mul_matrices_vs_scipy(dtype):
+    N, M = 40, 53
+    r1, c1, v1 = wl.random_coo_entries(N, M, 500, seed=75, dtype=dtype)
+    r2, c2, v2 = wl.random_coo_entries(N, M, 700, seed=76, dtype=dtype)
+    B = sp.coo_matrix((v1.astype(np.float64), (r1, c1)), shape=(N, M)).tocsr()
+    Cm = sp.coo_matrix((v2.astype(np.float64), (r2, c2)), shape=(N, M)).tocsr()
+    S = B.multiply(Cm).tocsr()
+    S.sort_indices()
+    S = S.tocoo()
+    assert 0 < S.nnz < min(len(r1), len(r2))          # a proper partial overlap
+    bcoo, ccoo = wl.coo_spec(N, M, r1, c1, v1), wl.coo_spec(N, M, r2, c2, v2)
+    bcsr, ccsr = wl.csr_from_sorted_coo(N, M, r1, c1, v1), wl.csr_from_sorted_coo(N, M, r2, c2, v2)
+    for b, c in ((bcoo, ccoo), (bcsr, ccsr), (bcsr, ccoo), (bcoo, ccsr)):   # CSR x COO: the running example
+        (ri, ci), v, mag = oracle.mul(b, c)
+        assert np.array_equal(ri, S.row) and np.array_equal(ci, S.col)
+        np.testing.assert_allclose(v, S.data, rtol=0, atol=1e-15)
+        np.testing.assert_allclose(mag, np.abs(S.data), rtol=0, atol=1e-15)
+
+
+def test_mul_third_order_vs_dense_and_closed_forms():
+    dims = (6, 5, 7)
+    bi, bj, bk, bv = wl.random_coo3_entries(dims, 90, seed=77, dtype=np.float64, skew=1.5)
+    ci, cj, ck, cv = wl.random_coo3_entries(dims, 120, seed=78, dtype=np.float64)
+    b, c = wl.coo3_spec(dims, bi, bj, bk, bv), wl.coo3_spec(dims, ci, cj, ck, cv)
+    D = _dense3(dims, bi, bj, bk, bv) * _dense3(dims, ci, cj, ck, cv)
+    both = (_dense3(dims, bi, bj, bk, np.ones(len(bv))) * _dense3(dims, ci, cj, ck, np.ones(len(cv)))) > 0
+    (oi, oj, ok), v, _ = oracle.mul(b, c)
+    lin = (oi.astype(np.int64) * 5 + oj) * 7 + ok
+    assert 0 < len(lin) < min(len(bv), len(cv))
+    assert np.all(np.diff(lin) > 0)                                   # ordered, unique
+    assert np.array_equal(lin, np.flatnonzero(both.ravel()))          # exactly the intersection
+    np.testing.assert_allclose(v, D[oi, oj, ok], rtol=0, atol=1e-15)
+    # commutative
+    (pi, pj, pk), pv, _ = oracle.mul(c, b)
+    assert np.array_equal(pi, oi) and np.array_equal(pj, oj) and np.array_equal(pk, ok) and np.array_equal(pv, v)
+    # B .* B squares the values on B's structure
+    (qi, qj, qk), qv, _ = oracle.mul(b, b)
+    assert np.array_equal(qi, bi) and np.array_equal(qj, bj) and np.array_equal(qk, bk) and np.array_equal(qv, bv * bv)
+    # an explicit zero in one operand stays stored in the result
+    z = bv.copy()
+    z[::2] = 0.0
+    (zi, _, _), zv, _ = oracle.mul(b, wl.coo3_spec(dims, bi, bj, bk, z))
+    assert len(zi) == len(bv) and np.array_equal(zv, bv * z)
+    # an empty operand, and operands with disjoint supports, give an empty result
+    e = np.zeros(0, int)
+    (ei, _, _), ev, _ = oracle.mul(b, wl.coo3_spec(dims, e, e, e, np.zeros(0)))
+    assert len(ei) == 0 and len(ev) == 0
+    even = wl.coo3_spec(dims, bi[bk % 2 == 0], bj[bk % 2 == 0], bk[bk % 2 == 0], bv[bk % 2 == 0])
+    odd = wl.coo3_spec(dims, bi[bk % 2 == 1], bj[bk % 2 == 1], bk[bk % 2 == 1], bv[bk % 2 == 1])
+    assert len(oracle.mul(even, odd)[1]) == 0
+    # the sum over the product's entries is the inner product
+    assert abs(v.sum() - oracle.innerprod(b, c)[0]) <= 1e-12 * np.abs(v).sum()
+    # CSF operand walks to the same result
+    (fi, fj, fk), fv, _ = oracle.mul(wl.csf3_from_sorted_coo(dims, bi, bj, bk, bv), c)
+    assert np.array_equal(fi, oi) and np.array_equal(fk, ok) and np.array_equal(fv, v)
+
+
 # ------------------------------------------------------------------ packing into CSF / ELL / DIA
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
