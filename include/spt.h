@@ -301,20 +301,30 @@ spt_status spt_to_coo(const spt_tensor* T, int32_t* out_crd0, int32_t* out_crd1,
 
 /*
  * A = B + C with a sparse result: matrix addition on COO or CSR (Section 5.2) and 3rd-order
- * PLUS on COO (Section 5.3). B and C: the same format (both COO matrices, both CSR, or both
- * COO3), dimensions and dtype, every level ordered, each coordinate stored at most once per
- * operand. The result has one entry per coordinate stored in B or C (the union merge of
- * Section 4.4), ordered, holding b, c or the rounded sum b + c; sums that cancel stay stored.
+ * PLUS on COO (Section 5.3). B and C: two matrices, each COO or CSR (the formats may differ;
+ * the result takes B's), or two COO3 tensors; same dimensions and dtype, every level ordered,
+ * each coordinate stored at most once per operand. The result has one entry per coordinate
+ * stored in B or C (the union merge of Section 4.4), ordered, holding b, c or the rounded sum
+ * b + c; sums that cancel stay stored.
  * Outputs need capacity nnz(B) + nnz(C) entries; *out_nnz_dev (device int64, required)
  * receives the entry count.
- *   COO matrices: out_crd0 (rows), out_crd1 (cols), out_vals; out_pos, out_crd2 ignored.
- *   COO3:         out_crd0, out_crd1, out_crd2, out_vals; out_pos ignored.
- *   CSR:          out_pos[N+1] (Table 3: counts, then running sum), out_crd1 (cols), out_vals;
+ *   B COO matrix: out_crd0 (rows), out_crd1 (cols), out_vals; out_pos, out_crd2 ignored.
+ *   B COO3:       out_crd0, out_crd1, out_crd2, out_vals; out_pos ignored.
+ *   B CSR:        out_pos[N+1] (Table 3: counts, then running sum), out_crd1 (cols), out_vals;
  *                 out_crd0, out_crd2 ignored.
  * Workspace: spt_add_workspace_bytes(B, C), about 4 bytes per stored entry of both operands
- * (CSR: 12).
+ * (CSR operands: up to 12).
+ *
+ * spt_mul: A = B .* C, the element-wise product with a sparse result (the running example of
+ * Sections 1 and 4: a CSR matrix times a COO matrix, element by element). Operands, outputs,
+ * capacities and workspace exactly as spt_add (min(nnz(B), nnz(C)) entries of capacity are
+ * enough); the result has one entry per coordinate stored in BOTH operands (the intersection
+ * merge of Section 4.4), holding the rounded product b * c; products that are zero stay stored.
  */
 spt_status spt_add(const spt_tensor* B, const spt_tensor* C, int32_t* out_pos, int32_t* out_crd0,
+                   int32_t* out_crd1, int32_t* out_crd2, void* out_vals, int64_t* out_nnz_dev,
+                   void* ws, size_t ws_bytes, void* stream);
+spt_status spt_mul(const spt_tensor* B, const spt_tensor* C, int32_t* out_pos, int32_t* out_crd0,
                    int32_t* out_crd1, int32_t* out_crd2, void* out_vals, int64_t* out_nnz_dev,
                    void* ws, size_t ws_bytes, void* stream);
 size_t spt_add_workspace_bytes(const spt_tensor* B, const spt_tensor* C);

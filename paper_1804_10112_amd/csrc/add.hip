@@ -30,7 +30,9 @@ constexpr uint32_t kNoSrc = 0xFFFF;
 
 // rec = (index into the tile's C list or kNoSrc) << 16 | (1 + index into the tile's B list,
 // 0 being the B entry just before the tile, or kNoSrc)
-template <typename KL>
+// UNION: every coordinate of B or C produces a result entry (addition); otherwise only the
+// coordinates stored in both do (element-wise multiplication, the intersection merge).
+template <typename KL, bool UNION>
 __global__ __launch_bounds__(kBlock) void add_merge_kernel(const KL kb, const KL kc, int nb, int nc,
                                                            const int* __restrict__ xs,
                                                            uint32_t* __restrict__ rec,
@@ -76,12 +78,12 @@ __global__ __launch_bounds__(kBlock) void add_merge_kernel(const KL kb, const KL
       const bool take_b = y >= ncl || (x < nbl && key_le(head_b, head_c));
       if (take_b) {
         // head_c is the next C entry, also past the tile's end: an equal one is this entry's twin
-        if (!key_eq(head_b, head_c)) mine[k] = (kNoSrc << 16) | static_cast<uint32_t>(x + 1);
+        if (UNION && !key_eq(head_b, head_c)) mine[k] = (kNoSrc << 16) | static_cast<uint32_t>(x + 1);
         prev_b = head_b;
         head_b = sB[++x];
       } else {
         const uint32_t bsrc = key_eq(prev_b, head_c) ? static_cast<uint32_t>(x) : kNoSrc;
-        mine[k] = (static_cast<uint32_t>(y) << 16) | bsrc;
+        if (UNION || bsrc != kNoSrc) mine[k] = (static_cast<uint32_t>(y) << 16) | bsrc;
         head_c = sC[++y];
       }
       cnt += mine[k] != kNothing ? 1 : 0;
@@ -111,7 +113,7 @@ struct CoordOut {
   int32_t *a0, *a1, *a2;
 };
 
-template <typename T>
+template <typename T, bool UNION>
 __global__ __launch_bounds__(kBlock) void add_fill_kernel(
     const int* __restrict__ xs, const uint32_t* __restrict__ rec, const int32_t* __restrict__ counts,
     const int32_t* __restrict__ offs, const CoordArrays B, const T* __restrict__ bv,
@@ -135,7 +137,8 @@ __global__ __launch_bounds__(kBlock) void add_fill_kernel(
     }
     if (cs != kNoSrc) {
       const int p = y0 + static_cast<int>(cs);
-      v += cv[p];
+      if (UNION) v += cv[p];
+      else v *= cv[p];  // intersection: both sources are present
       c0 = C.a0[p];
       c1 = C.a1[p];
       if (C.a2) c2 = C.a2[p];
@@ -230,27 +233,30 @@ __global__ __launch_bounds__(kBlock) void add_zero_i32_kernel(int32_t* __restric
 
 static int64_t add_tiles(int64_t nb, int64_t nc) { return (nb + nc + kAddTile - 1) / kAddTile; }
 
-size_t add_workspace(Format f, const spt_tensor* B, const spt_tensor* C) {
+// fb / fc: formats of the operands (matrices may mix CSR and COO; the result takes B's format)
+size_t add_workspace(Format fb, Format fc, const spt_tensor* B, const spt_tensor* C) {
   const int64_t nb = B->nvals, nc = C->nvals, nt = add_tiles(nb, nc);
   size_t n = 3 * align_up(static_cast<size_t>(nt + 1) * 4, 256) +
              align_up(static_cast<size_t>(nt) * kAddTile * 4, 256) + scan_workspace(nt) + 256;
-  if (f == Format::CSR)
-    n += align_up(static_cast<size_t>(nb) * 4, 256) + align_up(static_cast<size_t>(nc) * 4, 256) +
-         align_up(static_cast<size_t>(nb + nc) * 4, 256) + scan_workspace(B->level[0].N + 1);
+  if (fb == Format::CSR)
+    n += align_up(static_cast<size_t>(nb) * 4, 256) + align_up(static_cast<size_t>(nb + nc) * 4, 256) +
+         scan_workspace(B->level[0].N + 1);
+  if (fc == Format::CSR) n += align_up(static_cast<size_t>(nc) * 4, 256);
   return n;
 }
 
-template <typename T>
-static spt_status add_typed(Format f, const spt_tensor* B, const spt_tensor* C, int32_t* out_pos,
-                            int32_t* out_crd0, int32_t* out_crd1, int32_t* out_crd2, T* out_vals,
-                            int64_t* out_nnz, void* ws, size_t ws_bytes, hipStream_t s) {
+template <typename T, bool UNION>
+static spt_status add_typed(Format fb, Format fc, const spt_tensor* B, const spt_tensor* C,
+                            int32_t* out_pos, int32_t* out_crd0, int32_t* out_crd1, int32_t* out_crd2,
+                            T* out_vals, int64_t* out_nnz, void* ws, size_t ws_bytes, hipStream_t s) {
   const int64_t nb64 = B->nvals, nc64 = C->nvals;
   if (nb64 + nc64 + kAddTile >= INT32_MAX)
     return fail(SPT_ERR_UNSUPPORTED, "add: more than 2^31 entries in both operands together");
   const int nb = static_cast<int>(nb64), nc = static_cast<int>(nc64);
-  const int ntiles = static_cast<int>(add_tiles(nb, nc));
+  // an intersection with an empty operand is empty: no tile to walk
+  const int ntiles = (!UNION && (nb == 0 || nc == 0)) ? 0 : static_cast<int>(add_tiles(nb, nc));
   const int64_t N = B->level[0].N;
-  if (f == Format::CSR) {
+  if (fb == Format::CSR) {
     if (N + 1 >= INT32_MAX) return fail(SPT_ERR_UNSUPPORTED, "add: too many rows");
     hipLaunchKernelGGL(add_zero_i32_kernel, dim3(static_cast<unsigned>((N + 1 + kBlock - 1) / kBlock)),
                        dim3(kBlock), 0, s, out_pos, N + 1);
@@ -261,7 +267,7 @@ static spt_status add_typed(Format f, const spt_tensor* B, const spt_tensor* C, 
     SPT_CHECK_LAUNCH("add total");
     return SPT_OK;
   }
-  const size_t need = add_workspace(f, B, C);
+  const size_t need = add_workspace(fb, fc, B, C);
   if (!ws || ws_bytes < need)
     return fail(SPT_ERR_WORKSPACE, "add: workspace of %zu bytes needed, %zu given", need, ws_bytes);
   Workspace W(ws, ws_bytes);
@@ -271,31 +277,29 @@ static spt_status add_typed(Format f, const spt_tensor* B, const spt_tensor* C, 
   uint32_t* rec = W.take<uint32_t>(static_cast<size_t>(ntiles) * kAddTile);
   int32_t* scan_tmp = reinterpret_cast<int32_t*>(W.take<char>(scan_workspace(ntiles)));
 
+  // coordinate lists of the operands: CSR rows are expanded, COO levels are used as they are
+  auto coords_of = [&](Format f, const spt_tensor* X, int n, CoordArrays* out) -> spt_status {
+    if (f == Format::CSR) {
+      int32_t* rows = W.take<int32_t>(n);
+      if (n > 0) {
+        hipLaunchKernelGGL(expand_rows_kernel, dim3((n + kExpChunk - 1) / kExpChunk), dim3(kBlock), 0, s,
+                           n, static_cast<int>(N), X->level[1].pos, rows);
+        SPT_CHECK_LAUNCH("add expand rows");
+      }
+      *out = CoordArrays{rows, X->level[1].crd, nullptr};
+    } else {
+      *out = CoordArrays{X->level[0].crd, X->level[1].crd, f == Format::COO3 ? X->level[2].crd : nullptr};
+    }
+    return SPT_OK;
+  };
   CoordArrays cb, cc;
+  spt_status st = coords_of(fb, B, nb, &cb);
+  if (st != SPT_OK) return st;
+  st = coords_of(fc, C, nc, &cc);
+  if (st != SPT_OK) return st;
   CoordOut co;
-  if (f == Format::CSR) {
-    int32_t* rows_b = W.take<int32_t>(nb);
-    int32_t* rows_c = W.take<int32_t>(nc);
-    int32_t* rows_o = W.take<int32_t>(static_cast<size_t>(nb) + nc);
-    if (nb > 0) {
-      hipLaunchKernelGGL(expand_rows_kernel, dim3((nb + kExpChunk - 1) / kExpChunk), dim3(kBlock), 0,
-                         s, nb, static_cast<int>(N), B->level[1].pos, rows_b);
-      SPT_CHECK_LAUNCH("add expand rows of B");
-    }
-    if (nc > 0) {
-      hipLaunchKernelGGL(expand_rows_kernel, dim3((nc + kExpChunk - 1) / kExpChunk), dim3(kBlock), 0,
-                         s, nc, static_cast<int>(N), C->level[1].pos, rows_c);
-      SPT_CHECK_LAUNCH("add expand rows of C");
-    }
-    cb = CoordArrays{rows_b, B->level[1].crd, nullptr};
-    cc = CoordArrays{rows_c, C->level[1].crd, nullptr};
-    co = CoordOut{rows_o, out_crd1, nullptr};
-  } else {
-    const bool third = f == Format::COO3;
-    cb = CoordArrays{B->level[0].crd, B->level[1].crd, third ? B->level[2].crd : nullptr};
-    cc = CoordArrays{C->level[0].crd, C->level[1].crd, third ? C->level[2].crd : nullptr};
-    co = CoordOut{out_crd0, out_crd1, third ? out_crd2 : nullptr};
-  }
+  if (fb == Format::CSR) co = CoordOut{W.take<int32_t>(static_cast<size_t>(nb) + nc), out_crd1, nullptr};
+  else co = CoordOut{out_crd0, out_crd1, fb == Format::COO3 ? out_crd2 : nullptr};
 
   const int pgrid = (ntiles + 1 + kBlock - 1) / kBlock;
   const bool third = cb.a2 != nullptr;
@@ -305,25 +309,26 @@ static spt_status add_typed(Format f, const spt_tensor* B, const spt_tensor* C, 
     PackedLoader kc{cc.a0, cc.a1, cc.a2, w1 + w2, w2};
     hipLaunchKernelGGL(merge_partition_kernel<PackedLoader>, dim3(pgrid), dim3(kBlock), 0, s, kb, kc,
                        nb, nc, ntiles, kAddTile, xs);
-    hipLaunchKernelGGL(add_merge_kernel<PackedLoader>, dim3(ntiles), dim3(kBlock), 0, s, kb, kc, nb,
-                       nc, xs, rec, counts);
+    hipLaunchKernelGGL((add_merge_kernel<PackedLoader, UNION>), dim3(ntiles), dim3(kBlock), 0, s, kb,
+                       kc, nb, nc, xs, rec, counts);
   } else {
     TripleLoader kb{cb.a0, cb.a1, cb.a2};
     TripleLoader kc{cc.a0, cc.a1, cc.a2};
     hipLaunchKernelGGL(merge_partition_kernel<TripleLoader>, dim3(pgrid), dim3(kBlock), 0, s, kb, kc,
                        nb, nc, ntiles, kAddTile, xs);
-    hipLaunchKernelGGL(add_merge_kernel<TripleLoader>, dim3(ntiles), dim3(kBlock), 0, s, kb, kc, nb,
-                       nc, xs, rec, counts);
+    hipLaunchKernelGGL((add_merge_kernel<TripleLoader, UNION>), dim3(ntiles), dim3(kBlock), 0, s, kb,
+                       kc, nb, nc, xs, rec, counts);
   }
   SPT_CHECK_LAUNCH("add merge");
-  spt_status st = device_scan_i32<false>(counts, offs, ntiles, scan_tmp, s);
+  st = device_scan_i32<false>(counts, offs, ntiles, scan_tmp, s);
   if (st != SPT_OK) return st;
   hipLaunchKernelGGL(add_total_kernel, dim3(1), dim3(kWave), 0, s, ntiles, counts, offs, out_nnz);
   SPT_CHECK_LAUNCH("add total");
-  hipLaunchKernelGGL(add_fill_kernel<T>, dim3(ntiles), dim3(kBlock), 0, s, xs, rec, counts, offs, cb,
-                     static_cast<const T*>(B->vals), cc, static_cast<const T*>(C->vals), co, out_vals);
+  hipLaunchKernelGGL((add_fill_kernel<T, UNION>), dim3(ntiles), dim3(kBlock), 0, s, xs, rec, counts,
+                     offs, cb, static_cast<const T*>(B->vals), cc, static_cast<const T*>(C->vals), co,
+                     out_vals);
   SPT_CHECK_LAUNCH("add fill");
-  if (f == Format::CSR) {
+  if (fb == Format::CSR) {
     const unsigned egrid = static_cast<unsigned>((static_cast<int64_t>(nb) + nc + kBlock - 1) / kBlock);
     hipLaunchKernelGGL(result_row_count_kernel, dim3(egrid), dim3(kBlock), 0, s, co.a0, out_nnz,
                        out_pos);
@@ -334,14 +339,22 @@ static spt_status add_typed(Format f, const spt_tensor* B, const spt_tensor* C, 
   return SPT_OK;
 }
 
-spt_status add_dispatch(Format f, const spt_tensor* B, const spt_tensor* C, int32_t* out_pos,
-                        int32_t* out_crd0, int32_t* out_crd1, int32_t* out_crd2, void* out_vals,
-                        int64_t* out_nnz, void* ws, size_t ws_bytes, hipStream_t s) {
-  if (B->dtype == SPT_F64)
-    return add_typed<double>(f, B, C, out_pos, out_crd0, out_crd1, out_crd2,
-                             static_cast<double*>(out_vals), out_nnz, ws, ws_bytes, s);
-  return add_typed<float>(f, B, C, out_pos, out_crd0, out_crd1, out_crd2,
-                          static_cast<float*>(out_vals), out_nnz, ws, ws_bytes, s);
+// op: 0 = addition (union merge), 1 = element-wise multiplication (intersection merge)
+spt_status add_dispatch(int op, Format fb, Format fc, const spt_tensor* B, const spt_tensor* C,
+                        int32_t* out_pos, int32_t* out_crd0, int32_t* out_crd1, int32_t* out_crd2,
+                        void* out_vals, int64_t* out_nnz, void* ws, size_t ws_bytes, hipStream_t s) {
+  if (B->dtype == SPT_F64) {
+    double* ov = static_cast<double*>(out_vals);
+    return op == 0 ? add_typed<double, true>(fb, fc, B, C, out_pos, out_crd0, out_crd1, out_crd2, ov,
+                                             out_nnz, ws, ws_bytes, s)
+                   : add_typed<double, false>(fb, fc, B, C, out_pos, out_crd0, out_crd1, out_crd2, ov,
+                                              out_nnz, ws, ws_bytes, s);
+  }
+  float* ov = static_cast<float*>(out_vals);
+  return op == 0 ? add_typed<float, true>(fb, fc, B, C, out_pos, out_crd0, out_crd1, out_crd2, ov,
+                                          out_nnz, ws, ws_bytes, s)
+                 : add_typed<float, false>(fb, fc, B, C, out_pos, out_crd0, out_crd1, out_crd2, ov,
+                                           out_nnz, ws, ws_bytes, s);
 }
 
 }  // namespace spt

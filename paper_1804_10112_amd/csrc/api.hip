@@ -48,10 +48,10 @@ spt_status innerprod_dispatch(Format f, const spt_tensor* B, const spt_tensor* C
                               void* ws, size_t ws_bytes, hipStream_t s);
 size_t innerprod_workspace(int64_t nb);
 
-spt_status add_dispatch(Format f, const spt_tensor* B, const spt_tensor* C, int32_t* out_pos,
-                        int32_t* out_crd0, int32_t* out_crd1, int32_t* out_crd2, void* out_vals,
-                        int64_t* out_nnz, void* ws, size_t ws_bytes, hipStream_t s);
-size_t add_workspace(Format f, const spt_tensor* B, const spt_tensor* C);
+spt_status add_dispatch(int op, Format fb, Format fc, const spt_tensor* B, const spt_tensor* C,
+                        int32_t* out_pos, int32_t* out_crd0, int32_t* out_crd1, int32_t* out_crd2,
+                        void* out_vals, int64_t* out_nnz, void* ws, size_t ws_bytes, hipStream_t s);
+size_t add_workspace(Format fb, Format fc, const spt_tensor* B, const spt_tensor* C);
 
 spt_status pack_csf_dispatch(const spt_tensor* B, int32_t* pos0, int32_t* crd0, int32_t* pos1,
                              int32_t* crd1, int32_t* pos2, int32_t* crd2, void* vals_out,
@@ -476,48 +476,68 @@ spt_status spt_to_coo(const spt_tensor* T, int32_t* out_crd0, int32_t* out_crd1,
                          static_cast<hipStream_t>(stream));
 }
 
-// Common operand checks of spt_add; returns the shared format or sets the error.
-static spt_status add_operands(const spt_tensor* B, const spt_tensor* C, Format* f_out) {
+// Common operand checks of spt_add and spt_mul; returns both formats or sets the error.
+// Matrices may mix CSR and COO (the result takes B's format); 3rd-order operands are both COO.
+static spt_status add_operands(const spt_tensor* B, const spt_tensor* C, Format* fb_out,
+                               Format* fc_out) {
   Format fb = recognize(B);
   if (fb == Format::Invalid || fb == Format::Unsupported) return status_of(fb);
   Format fc = recognize(C);
   if (fc == Format::Invalid || fc == Format::Unsupported) return status_of(fc);
-  if (fb != fc || (fb != Format::COO2 && fb != Format::COO3 && fb != Format::CSR))
-    return fail(SPT_ERR_UNSUPPORTED, "add: B and C must both be COO matrices, both CSR or both COO3");
-  if (B->dtype != C->dtype) return fail(SPT_ERR_INVALID_ARG, "add: B and C differ in dtype");
+  const bool mat_b = fb == Format::COO2 || fb == Format::CSR, mat_c = fc == Format::COO2 || fc == Format::CSR;
+  if (!((mat_b && mat_c) || (fb == Format::COO3 && fc == Format::COO3)))
+    return fail(SPT_ERR_UNSUPPORTED, "add/mul: B and C must be COO or CSR matrices, or both COO3");
+  if (B->dtype != C->dtype) return fail(SPT_ERR_INVALID_ARG, "add/mul: B and C differ in dtype");
   for (int k = 0; k < B->nlevels; ++k) {
     if (B->level[k].N != C->level[k].N)
-      return fail(SPT_ERR_INVALID_ARG, "add: dimension %d differs (%lld vs %lld)", k,
+      return fail(SPT_ERR_INVALID_ARG, "add/mul: dimension %d differs (%lld vs %lld)", k,
                   (long long)B->level[k].N, (long long)C->level[k].N);
-    if (fb == Format::CSR && k == 0) continue;  // the dense row level is ordered by construction
-    if (!(B->level[k].flags & C->level[k].flags & SPT_ORDERED))
-      return fail(SPT_ERR_UNSUPPORTED, "add: every level of B and C must be ordered");
+    // a dense row level is ordered by construction
+    if (!(fb == Format::CSR && k == 0) && !(B->level[k].flags & SPT_ORDERED))
+      return fail(SPT_ERR_UNSUPPORTED, "add/mul: every level of B must be ordered");
+    if (!(fc == Format::CSR && k == 0) && !(C->level[k].flags & SPT_ORDERED))
+      return fail(SPT_ERR_UNSUPPORTED, "add/mul: every level of C must be ordered");
   }
-  *f_out = fb;
+  *fb_out = fb;
+  *fc_out = fc;
   return SPT_OK;
+}
+
+static spt_status add_or_mul(int op, const spt_tensor* B, const spt_tensor* C, int32_t* out_pos,
+                             int32_t* out_crd0, int32_t* out_crd1, int32_t* out_crd2, void* out_vals,
+                             int64_t* out_nnz_dev, void* ws, size_t ws_bytes, void* stream) {
+  clear_error();
+  Format fb, fc;
+  spt_status st = add_operands(B, C, &fb, &fc);
+  if (st != SPT_OK) return st;
+  if (!out_crd1 || !out_vals || !out_nnz_dev)
+    return fail(SPT_ERR_INVALID_ARG, "add/mul: out_crd1, out_vals and out_nnz_dev are required");
+  if (fb == Format::CSR && !out_pos) return fail(SPT_ERR_INVALID_ARG, "add/mul: CSR result needs out_pos");
+  if (fb != Format::CSR && !out_crd0) return fail(SPT_ERR_INVALID_ARG, "add/mul: COO result needs out_crd0");
+  if (fb == Format::COO3 && !out_crd2) return fail(SPT_ERR_INVALID_ARG, "add/mul: COO3 result needs out_crd2");
+  return add_dispatch(op, fb, fc, B, C, out_pos, out_crd0, out_crd1, out_crd2, out_vals, out_nnz_dev,
+                      ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 spt_status spt_add(const spt_tensor* B, const spt_tensor* C, int32_t* out_pos, int32_t* out_crd0,
                    int32_t* out_crd1, int32_t* out_crd2, void* out_vals, int64_t* out_nnz_dev,
                    void* ws, size_t ws_bytes, void* stream) {
-  clear_error();
-  Format f;
-  spt_status st = add_operands(B, C, &f);
-  if (st != SPT_OK) return st;
-  if (!out_crd1 || !out_vals || !out_nnz_dev)
-    return fail(SPT_ERR_INVALID_ARG, "add: out_crd1, out_vals and out_nnz_dev are required");
-  if (f == Format::CSR && !out_pos) return fail(SPT_ERR_INVALID_ARG, "add: CSR result needs out_pos");
-  if (f != Format::CSR && !out_crd0) return fail(SPT_ERR_INVALID_ARG, "add: COO result needs out_crd0");
-  if (f == Format::COO3 && !out_crd2) return fail(SPT_ERR_INVALID_ARG, "add: COO3 result needs out_crd2");
-  return add_dispatch(f, B, C, out_pos, out_crd0, out_crd1, out_crd2, out_vals, out_nnz_dev, ws,
-                      ws_bytes, static_cast<hipStream_t>(stream));
+  return add_or_mul(0, B, C, out_pos, out_crd0, out_crd1, out_crd2, out_vals, out_nnz_dev, ws,
+                    ws_bytes, stream);
+}
+
+spt_status spt_mul(const spt_tensor* B, const spt_tensor* C, int32_t* out_pos, int32_t* out_crd0,
+                   int32_t* out_crd1, int32_t* out_crd2, void* out_vals, int64_t* out_nnz_dev,
+                   void* ws, size_t ws_bytes, void* stream) {
+  return add_or_mul(1, B, C, out_pos, out_crd0, out_crd1, out_crd2, out_vals, out_nnz_dev, ws,
+                    ws_bytes, stream);
 }
 
 size_t spt_add_workspace_bytes(const spt_tensor* B, const spt_tensor* C) {
   clear_error();
-  Format f;
-  if (add_operands(B, C, &f) != SPT_OK) return 0;
-  const size_t n = add_workspace(f, B, C);
+  Format fb, fc;
+  if (add_operands(B, C, &fb, &fc) != SPT_OK) return 0;
+  const size_t n = add_workspace(fb, fc, B, C);
   return n < 256 ? 256 : n;
 }
 

@@ -140,9 +140,9 @@ def gpu_ttm(spec, Cm, is_csf=False, fiber_capacity=None, misalign=False):
     return oi.cpu().numpy()[:n], oj.cpu().numpy()[:n], ov.cpu().numpy()[:n]
 
 
-def gpu_add(bspec, cspec, fmt, misalign=False):
-    """fmt 'coo', 'coo3' or 'csr'. Returns (list of index arrays, values): for 'csr' the index
-    arrays are [pos, cols], else the coordinate arrays."""
+def gpu_add(bspec, cspec, fmt, misalign=False, op="add"):
+    """fmt (B's, hence the result's) 'coo', 'coo3' or 'csr'; op 'add' or 'mul'. Returns (list of
+    index arrays, values): for 'csr' the index arrays are [pos, cols], else the coordinate arrays."""
     import torch
     import paper_1804_10112_amd as spt
     B, Ct = spt.DeviceTensor(bspec, misalign=misalign), spt.DeviceTensor(cspec, misalign=misalign)
@@ -153,8 +153,9 @@ def gpu_add(bspec, cspec, fmt, misalign=False):
     ov = torch.full((cap,), float("nan"), dtype=B.torch_dtype, device="cuda")
     cnt = torch.full((1,), -1, dtype=torch.int64, device="cuda")
     ws = torch.empty(spt.spt_add_workspace_bytes(B, Ct), dtype=torch.uint8, device="cuda")
-    spt.spt_add(B, Ct, pos if fmt == "csr" else None, None if fmt == "csr" else c0, c1,
-                c2 if fmt == "coo3" else None, ov, cnt, ws)
+    fn = spt.spt_add if op == "add" else spt.spt_mul
+    fn(B, Ct, pos if fmt == "csr" else None, None if fmt == "csr" else c0, c1,
+       c2 if fmt == "coo3" else None, ov, cnt, ws)
     torch.cuda.synchronize()
     n = int(cnt.item())
     v = ov.cpu().numpy()[:n]

@@ -123,9 +123,9 @@ def test_add_errors():
     with pytest.raises(spt.SptError) as e:
         spt.spt_add(B, Ct, None, i, i, None, v, cnt, None)
     assert "workspace" in str(e.value)
-    csr = spt.DeviceTensor(_matrices(30, 30, 100, 100, seed=1, dtype=np.float32, fmt="csr")[1])
+    t3 = spt.DeviceTensor(wl.coo3_spec((30, 30, 4), *wl.random_coo3_entries((30, 30, 4), 50, 2, dtype=np.float32)))
     with pytest.raises(spt.SptError):
-        spt.spt_add(B, csr, None, i, i, None, v, cnt, ws)                # mixed formats
+        spt.spt_add(B, t3, None, i, i, i, v, cnt, ws)                    # a matrix and a 3rd-order tensor
     other = spt.DeviceTensor(_matrices(30, 31, 100, 100, seed=1, dtype=np.float32, fmt="coo")[1])
     with pytest.raises(spt.SptError):
         spt.spt_add(B, other, None, i, i, None, v, cnt, ws)
