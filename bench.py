@@ -297,6 +297,13 @@ def build_items(args):
                 run = lambda Bm=Bm, Cm2=Cm2, wsm=wsm: spt.spt_add(Bm, Cm2, qpos, None, q1, None, qv, ocnt, wsm)
                 byt = 12 * (nb + nc) + 12 * nb + 12 * (n4 + 1)
             items.append(Item(f"n3_add_{fmt}", run, nc, byt))
+        # the running example: a CSR matrix times a COO matrix, element by element (result CSR)
+        Cm3 = spt.DeviceTensor(wl.coo_spec(n4, n4, rs[half], cs[half], 0.5 * vs[half]))
+        wsx = torch.empty(spt.spt_add_workspace_bytes(Bm, Cm3), dtype=torch.uint8, device=dev)
+        keep.extend([Cm3, wsx])
+        items.append(Item("n3_mul_csr_coo", lambda: spt.spt_mul(Bm, Cm3, qpos, None, q1, None, qv, ocnt, wsx),
+                          nc, 12 * nb + 16 * nc + 12 * nc + 8 * (n4 + 1),
+                          "read B (pos, cols, values) and C (16 B), write the common entries (12 B) and pos"))
         keep.extend([q0, q1, qpos, qv])
         del c4
     # ---- on request (--only n4): packers. Config 5's COO -> CSF, config 3's CSR -> ELL,

@@ -140,7 +140,8 @@ def test_mul_full_size():
     values against the definition through searchsorted."""
     c4 = wl.config4(with_sorted=True)
     rs, cs, vs = c4["sorted"]
-    N = c4["csr"].dims[0]
+    N = c4["coo"].dims[0]
+    b = wl.csr_from_sorted_coo(N, N, rs, cs, vs)
     rng = np.random.default_rng(wl.SEED_BASE + 66)
     r2, c2, v2 = wl.random_coo_entries(N, N, 10_000_000, seed=wl.SEED_BASE + 67, dtype=np.float64)
     third = slice(0, len(vs), 3)
@@ -149,7 +150,7 @@ def test_mul_full_size():
     key, first = np.unique(key, return_index=True)
     vals = vals[first]
     c = wl.coo_spec(N, N, (key // N).astype(np.int32), (key % N).astype(np.int32), vals)
-    (pos, cols), gv = gpu_add(c4["csr"], c, "csr", op="mul")
+    (pos, cols), gv = gpu_add(b, c, "csr", op="mul")
     kb = rs.astype(np.int64) * N + cs
     want = np.intersect1d(kb, key, assume_unique=True)
     assert len(gv) == len(want) and len(want) >= len(vs[third])
