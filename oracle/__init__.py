@@ -73,6 +73,8 @@ def lib():
         L.orc_pack_dia.argtypes = [vp, vp, C.c_int64, vp, vp]
         L.orc_add.restype = C.c_int64
         L.orc_add.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp]
+        L.orc_spmv_blocked.restype = None
+        L.orc_spmv_blocked.argtypes = [vp, vp, C.c_int64, C.c_int64, C.c_int64, vp, vp]
         L.orc_mul.restype = C.c_int64
         L.orc_mul.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp]
         L.orc_innerprod.restype = C.c_double
@@ -201,6 +203,23 @@ def spmv(spec, x):
     y = np.zeros(rows, np.float64)
     mag = np.zeros(rows, np.float64)
     lib().orc_spmv(T.ref, _ptr(x), rows, _ptr(y), _ptr(mag))
+    return y, mag
+
+
+def spmv_blocked(spec, x):
+    """Reference y = A x for a blocked matrix stored as a 4th-order tensor with dims
+    (block rows, block cols, b1, b2): float64 y of length block rows * b1, plus magnitudes."""
+    if spec.order != 4:
+        raise ValueError("a blocked matrix is a 4th-order tensor")
+    T = OTensor(spec)
+    x = _same_dtype(spec, x)
+    b1, b2 = spec.dims[2], spec.dims[3]
+    if len(x) != spec.dims[1] * b2:
+        raise ValueError("x must have block cols * b2 entries")
+    rows = spec.dims[0] * b1
+    y = np.zeros(rows, np.float64)
+    mag = np.zeros(rows, np.float64)
+    lib().orc_spmv_blocked(T.ref, _ptr(x), b1, b2, rows, _ptr(y), _ptr(mag))
     return y, mag
 
 

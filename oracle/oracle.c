@@ -241,6 +241,31 @@ void orc_spmv(const orc_tensor* T, const void* x, int64_t rows, double* y,
 
 typedef struct {
   const orc_tensor* T;
+  const void* x;
+  long double* acc;
+  double* mag;
+  int64_t b1, b2;
+} spmv_blk_ctx;
+static void spmv_blk_visit(void* vctx, const int64_t* c, int64_t p) {
+  spmv_blk_ctx* S = (spmv_blk_ctx*)vctx;
+  /* component (i1, j1, i2, j2) of the 4th-order tensor is element (i1*b1 + i2, j1*b2 + j2) of the matrix */
+  int64_t row = c[0] * S->b1 + c[2], col = c[1] * S->b2 + c[3];
+  long double t = (long double)val_at(S->T, p) * (long double)dense_at(S->x, S->T->is_f64, col);
+  S->acc[row] += t;
+  S->mag[row] += fabs((double)t);
+}
+void orc_spmv_blocked(const orc_tensor* T, const void* x, int64_t b1, int64_t b2, int64_t rows,
+                      double* y, double* mag) {
+  long double* acc = (long double*)calloc((size_t)(rows > 0 ? rows : 1), sizeof(long double));
+  for (int64_t i = 0; i < rows; ++i) mag[i] = 0.0;
+  spmv_blk_ctx S = {T, x, acc, mag, b1, b2};
+  orc_enumerate(T, spmv_blk_visit, &S);
+  for (int64_t i = 0; i < rows; ++i) y[i] = (double)acc[i];
+  free(acc);
+}
+
+typedef struct {
+  const orc_tensor* T;
   const orc_tensor* X;
   long double* acc;
   double* mag;

@@ -67,6 +67,14 @@ void orc_to_coo(const orc_tensor* T, int64_t* coords_out, double* vals_out);
 void orc_spmv(const orc_tensor* T, const void* x, int64_t rows, double* y,
               double* mag);
 
+/* SpMV on a blocked matrix format cast as a 4th-order tensor (Section 3.2: BCSR, CSB): T has
+ * dimensions (block rows, block columns, b1 rows per block, b2 columns per block) in any legal
+ * composition of levels, and component (i1, j1, i2, j2) is matrix element (i1*b1 + i2,
+ * j1*b2 + j2): y(i1, i2) = sum over stored components of A(i1, j1, i2, j2) x(j1, j2), with y and
+ * x stored flat. rows = len(y) = block rows * b1. y and mag are overwritten. */
+void orc_spmv_blocked(const orc_tensor* T, const void* x, int64_t b1, int64_t b2, int64_t rows,
+                      double* y, double* mag);
+
 /* y = A x with x stored as a 1st-order tensor X (Section 5.4, Figure 16):
  * one compressed level (sparse vector) or one hashed level (hash map). Every
  * stored (i,j) of A looks x_j up in X: by the hashed level's locate function

@@ -150,6 +150,50 @@ def test_plain_spmv_loops_agree_with_definition(dtype, tol):
         assert np.all(np.abs(got - y) <= tol * np.maximum(mag, 1e-30) + 1e-300), fmt
 
 
+# ------------------------------------------------------------------ blocked matrices as 4th-order tensors
+
+@pytest.mark.parametrize("dtype,tol", [(np.float64, 1e-15), (np.float32, 1e-15)])
+@pytest.mark.parametrize("b1,b2", [(2, 3), (4, 4), (3, 1), (1, 5)])
+def test_spmv_bcsr_vs_scipy_bsr_and_csr_twin(dtype, tol, b1, b2):
+    Nb, Mb = 37, 29
+    w = wl.random_bcsr(Nb, Mb, b1, b2, 0, 7, seed=91, dtype=dtype, with_csr=True)
+    b, x = w["bcsr"], w["x"]
+    lv = b.levels[1]
+    y, mag = oracle.spmv_blocked(b, x)
+    S = sp.bsr_matrix((b.vals.astype(np.float64).reshape(-1, b1, b2), lv.crd, lv.pos),
+                      shape=(Nb * b1, Mb * b2))
+    np.testing.assert_allclose(y, S @ x.astype(np.float64), rtol=0, atol=1e-13 * max(mag.max(), 1))
+    np.testing.assert_allclose(y, S.toarray() @ x.astype(np.float64), rtol=0, atol=1e-13 * max(mag.max(), 1))
+    np.testing.assert_allclose(mag, abs(S) @ np.abs(x.astype(np.float64)), rtol=0, atol=1e-13 * max(mag.max(), 1))
+    y2, _ = oracle.spmv(w["csr"], x)                       # the same matrix entry by entry
+    np.testing.assert_allclose(y, y2, rtol=0, atol=tol * max(mag.max(), 1))
+    # x = e_c picks matrix column c, block structure and all
+    c = 2 * b2 + (b2 - 1)
+    e = np.zeros(Mb * b2, dtype)
+    e[c] = 1
+    np.testing.assert_array_equal(oracle.spmv_blocked(b, e)[0], S.toarray()[:, c])
+
+
+def test_spmv_blocked_formats_of_one_matrix_agree():
+    # BCSR (padded with explicit zeros) and CSB (sparse blocks) of a matrix whose size is no
+    # multiple of the block size, against scipy on the plain entries
+    N, M, b1, b2 = 50, 41, 4, 3
+    r, c, v = wl.random_coo_entries(N, M, 400, seed=92, dtype=np.float64)
+    x = wl.dense_vector(-(-M // b2) * b2, 93)
+    want = sp.coo_matrix((v, (r, c)), shape=(N, -(-M // b2) * b2)).tocsr() @ x
+    for spec in (wl.bcsr_from_coo(N, M, r, c, v, b1, b2), wl.csb_from_coo(N, M, r, c, v, b1, b2)):
+        y, mag = oracle.spmv_blocked(spec, x)
+        assert len(y) == -(-N // b1) * b1
+        np.testing.assert_allclose(y[:N], want, rtol=0, atol=1e-13 * max(mag.max(), 1))
+        assert not y[N:].any()
+    # CSB stores exactly the entries; BCSR stores whole blocks
+    assert len(wl.csb_from_coo(N, M, r, c, v, b1, b2).vals) == len(v)
+    coords, vals = oracle.to_coo(wl.csb_from_coo(N, M, r, c, v, b1, b2))
+    rows, cols = coords[0] * b1 + coords[2], coords[1] * b2 + coords[3]
+    o = np.lexsort((cols, rows))
+    assert np.array_equal(rows[o], r) and np.array_equal(cols[o], c) and np.array_equal(vals[o], v)
+
+
 # ------------------------------------------------------------------ COO -> CSR
 
 @pytest.mark.parametrize("order", [0, 1])

@@ -227,6 +227,88 @@ def dcc3_from_sorted_coo(dims, ci, cj, ck, vals, name="dcc3") -> TensorSpec:
     ], np.ascontiguousarray(vals), name)
 
 
+def bcsr_spec(Nb, Mb, b1, b2, pos, crd, blocks, name="bcsr") -> TensorSpec:
+    """BCSR cast as a 4th-order tensor (block row, block col, row in block, col in block) =
+    (dense, compressed, dense, dense): one dense b1 x b2 block of values, row-major, per stored
+    block coordinate (Section 3.2)."""
+    return TensorSpec((Nb, Mb, b1, b2), [
+        LevelSpec(DENSE, 0, Nb),
+        LevelSpec(COMPRESSED, 1, Mb, M=Nb, pos=_i32(pos), crd=_i32(crd)),
+        LevelSpec(DENSE, 2, b1),
+        LevelSpec(DENSE, 3, b2),
+    ], np.ascontiguousarray(blocks).reshape(-1), name)
+
+
+def _block_keys(N, M, row, col, b1, b2):
+    Nb, Mb = -(-N // b1), -(-M // b2)
+    row, col = np.asarray(row, np.int64), np.asarray(col, np.int64)
+    return Nb, Mb, (row // b1) * Mb + col // b2, row % b1, col % b2
+
+
+def bcsr_from_coo(N, M, row, col, vals, b1, b2, name="bcsr") -> TensorSpec:
+    """The matrix's entries (distinct coordinates, any order) laid out as BCSR: every b1 x b2
+    block that holds an entry is stored whole, cells without an entry hold 0."""
+    Nb, Mb, bkey, ii, jj = _block_keys(N, M, row, col, b1, b2)
+    ub, inv = np.unique(bkey, return_inverse=True)
+    blocks = np.zeros((len(ub), b1, b2), np.asarray(vals).dtype)
+    blocks[inv, ii, jj] = vals
+    pos = np.concatenate([[0], np.cumsum(np.bincount(ub // Mb, minlength=Nb))])
+    return bcsr_spec(Nb, Mb, b1, b2, pos, ub % Mb, blocks, name)
+
+
+def csb_from_coo(N, M, row, col, vals, b1, b2, name="csb") -> TensorSpec:
+    """CSB cast as a 4th-order tensor = (dense block rows, dense block columns, compressed
+    non-unique rows in the block, singleton columns in the block): a dense grid of sparse blocks,
+    each stored as a COO list (Section 3.2)."""
+    Nb, Mb, bkey, ii, jj = _block_keys(N, M, row, col, b1, b2)
+    o = np.lexsort((jj, ii, bkey))
+    pos = np.concatenate([[0], np.cumsum(np.bincount(bkey, minlength=Nb * Mb))])
+    return TensorSpec((Nb, Mb, b1, b2), [
+        LevelSpec(DENSE, 0, Nb),
+        LevelSpec(DENSE, 1, Mb),
+        LevelSpec(COMPRESSED, 2, b1, M=Nb * Mb, pos=_i32(pos), crd=_i32(ii[o]), unique=False),
+        LevelSpec(SINGLETON, 3, b2, crd=_i32(jj[o])),
+    ], np.ascontiguousarray(np.asarray(vals)[o]), name)
+
+
+def random_bcsr(Nb, Mb, b1, b2, lo, hi, seed, dtype=np.float64, dist="u11", band=0, with_csr=False):
+    """Blocked matrix with lo..hi stored blocks per block row (FEM-like: `band` > 0 draws the
+    block columns within +-band of the diagonal, else uniformly), full dense blocks.
+    Returns {"bcsr", "x", "nblocks"} and, with_csr, the same matrix as CSR ("csr")."""
+    rng = np.random.default_rng(seed)
+    L = rng.integers(lo, hi + 1, Nb)
+    brow = np.repeat(np.arange(Nb, dtype=np.int64), L)
+    if band:
+        bcol = np.clip(brow + rng.integers(-band, band + 1, len(brow)), 0, Mb - 1)
+    else:
+        bcol = rng.integers(0, Mb, len(brow))
+    key = np.unique(brow * Mb + bcol)
+    brow, bcol = key // Mb, key % Mb
+    nb = len(key)
+    L = np.bincount(brow, minlength=Nb)
+    pos = np.concatenate([[0], np.cumsum(L)])
+    blocks = _values(rng, nb * b1 * b2, dtype, dist).reshape(nb, b1, b2)
+    out = {"bcsr": bcsr_spec(Nb, Mb, b1, b2, pos, bcol, blocks), "nblocks": nb,
+           "x": dense_vector(Mb * b2, seed + 1000, dtype, dist)}
+    if with_csr:
+        # row (ib, ii) of the CSR twin lists the blocks of block row ib in order, each giving
+        # its b2 cells of in-block row ii: a transposition (block, ii) -> (ii, block) per block row
+        first = np.repeat(pos[:-1], L)                       # first block of each block's block row
+        k = np.arange(nb, dtype=np.int64) - first            # rank of the block inside its block row
+        Lb = np.repeat(L, L)                                 # blocks in that block row
+        base = first * b1 * b2                               # CSR entries before the block row
+        dst = (base[:, None, None] + np.arange(b1)[None, :, None] * (Lb * b2)[:, None, None]
+               + (k * b2)[:, None, None] + np.arange(b2)[None, None, :])
+        cvals = np.empty(nb * b1 * b2, dtype)
+        ccol = np.empty(nb * b1 * b2, np.int32)
+        cvals[dst.reshape(-1)] = blocks.reshape(-1)
+        ccol[dst.reshape(-1)] = (bcol[:, None, None] * b2 + np.arange(b2)[None, None, :]
+                                 + np.zeros((1, b1, 1), np.int64)).reshape(-1)
+        cpos = np.concatenate([[0], np.cumsum(np.repeat(L * b2, b1))])
+        out["csr"] = csr_spec(Nb * b1, Mb * b2, cpos, ccol, cvals, max_row=int(L.max()) * b2)
+    return out
+
+
 def random_sparse_vector(M, nnz, seed, dtype=np.float64, dist="u11"):
     """(sorted distinct coordinates, values) of a random sparse vector."""
     rng = np.random.default_rng(seed)
