@@ -66,7 +66,7 @@ def build_items(args):
 
     def on(name):
         if want is None:
-            return name not in ("x14", "x16", "n2", "n3", "n4", "n5")   # these groups run only on request
+            return name not in ("x14", "x16", "n2", "n3", "n4", "n5", "n6")   # these groups run only on request
         return name in want or name.split("_")[0] in want
 
     # ---- config 2: banded, 7 diagonals, fp64: DIA and CSR
@@ -375,6 +375,24 @@ def build_items(args):
         items.append(Item("n5_ell_to_coo", lambda: spt.spt_to_coo(Ae, g0, g1, None, gv, gcnt, wg), 0,
                           2 * 8 * cells + 12 * nnz3, "cells read twice (count, fill)"))
         del c3
+    # ---- on request (--only n6): a 4x4-blocked fp64 matrix (FEM-like band, 8..24 blocks per
+    #      block row) as BCSR and as its CSR twin
+    def group_n6():
+        nbr = max(64, int(500_000 * s))
+        w = wl.random_bcsr(nbr, nbr, 4, 4, 8, 24, seed=wl.SEED_BASE + 77, dtype=np.float64,
+                           band=max(32, int(5000 * s)), with_csr=True)
+        nblk = w["nblocks"]
+        xb = up(w["x"])
+        yb = torch.empty(nbr * 4, dtype=torch.float64, device=dev)
+        for nm, spec, byt in (("bcsr", w["bcsr"], (128 + 4) * nblk + 4 * (nbr + 1) + 16 * 4 * nbr),
+                              ("csr_twin", w["csr"], 12 * 16 * nblk + 4 * (4 * nbr + 1) + 16 * 4 * nbr)):
+            Ab = spt.DeviceTensor(spec)
+            wb = Ab.workspace(spt.SPT_OP_SPMV)
+            keep.extend([Ab, wb])
+            items.append(Item(f"n6_spmv_{nm}", lambda Ab=Ab, wb=wb: spt.spt_spmv(Ab, xb, yb, wb),
+                              2 * 16 * nblk, byt))
+        keep.append(yb)
+        del w
     if on("c2"):
         group_c2()
     if on("c3"):
@@ -393,6 +411,8 @@ def build_items(args):
         group_n3()
     if on("n4"):
         group_n4()
+    if on("n6"):
+        group_n6()
     if on("n5"):
         group_n5()
     return items, cpu_jobs, keep

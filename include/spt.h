@@ -128,6 +128,10 @@ typedef struct {
  *   ELL   (D slots W, D rows, S cols)             vals[W*N], cell (k,i) at k*N+i
  *   COO3  (C~U, S~U, S)                           vals[nnz]
  *   CSF3  (C, C, C)                               vals[nnz]
+ *   BCSR  (D block rows, C block cols, D b1, D b2) vals[nblocks*b1*b2], blocks row-major;
+ *         a blocked matrix cast as a 4th-order tensor (Section 3.2): order = 4, modes
+ *         0..3 = (block row, block column, row in block, column in block), and component
+ *         (i1, j1, i2, j2) is matrix element (i1*b1 + i2, j1*b2 + j2). spt_spmv only.
  * spt_spmv and spt_to_coo also accept every other legal composition ("any composition"
  * below); the remaining operations return SPT_ERR_UNSUPPORTED for them.
  *
@@ -138,7 +142,7 @@ typedef struct {
  * of leaf positions (positions of the last level), whether or not each holds a component.
  */
 typedef struct {
-  int32_t order;   /* number of tensor dimensions (2 or 3) */
+  int32_t order;   /* number of tensor dimensions (1..3; 4 for a blocked matrix) */
   int32_t nlevels; /* number of levels (2..4) */
   int32_t dtype;   /* spt_dtype of vals and of every dense operand */
   int32_t reserved;
@@ -156,6 +160,11 @@ typedef struct {
  * Any other composition of levels that stores a matrix (DCSR, CSC, dense, hashed
  * rows or columns, ...) is evaluated by reading the level functions of Table 2 per
  * stored value, again with floating-point atomics; it needs no workspace.
+ * A blocked matrix (order 4, Section 3.2): x has (block columns * b2) entries, y has
+ * (block rows * b1). BCSR with block edges up to 64 has a kernel of its own
+ * (deterministic, workspace from spt_workspace_bytes(SPT_OP_SPMV, ...)); BCSR with larger
+ * blocks and every other 4-level composition of a blocked matrix (e.g. CSB = dense, dense,
+ * compressed non-unique, singleton) are read per stored value like any other composition.
  */
 spt_status spt_spmv(const spt_tensor* A, const void* x, void* y, void* ws,
                     size_t ws_bytes, void* stream);

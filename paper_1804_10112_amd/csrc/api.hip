@@ -69,6 +69,10 @@ spt_status pack_dia_dispatch(const spt_tensor* A, int32_t K, const int32_t* offs
                              hipStream_t s);
 
 spt_status generic_spmv_dispatch(const spt_tensor* A, const void* x, void* y, hipStream_t s);
+spt_status bcsr_spmv_dispatch(const spt_tensor* A, const void* x, void* y, void* ws, size_t ws_bytes,
+                              hipStream_t s);
+size_t bcsr_workspace(const spt_tensor* A);
+bool bcsr_fast_ok(const spt_tensor* A);
 spt_status to_coo_dispatch(const spt_tensor* T, int32_t* o0, int32_t* o1, int32_t* o2, void* ov,
                            int64_t* out_nnz, void* ws, size_t ws_bytes, hipStream_t s);
 size_t to_coo_workspace(int64_t nvals);
@@ -209,8 +213,16 @@ Format recognize(const spt_tensor* T) {
       return Format::CSF3;
     }
   }
+  if (T->order == 4 && T->nlevels == 4 && modes(0, 1, 2, 3) && is(L[0], SPT_DENSE) &&
+      is(L[1], SPT_COMPRESSED) && is(L[2], SPT_DENSE) && is(L[3], SPT_DENSE)) {
+    if (L[1].M != L[0].N) {
+      fail(SPT_ERR_INVALID_ARG, "BCSR: block column level must have one parent per block row");
+      return Format::Invalid;
+    }
+    return Format::BCSR;
+  }
   fail(SPT_ERR_UNSUPPORTED,
-       "level composition not supported (supported: CSR, COO, DIA, ELL, 3rd-order COO, CSF)");
+       "level composition not supported (supported: CSR, COO, DIA, ELL, BCSR, 3rd-order COO, CSF)");
   return Format::Unsupported;
 }
 
@@ -268,13 +280,17 @@ spt_status spt_spmv(const spt_tensor* A, const void* x, void* y, void* ws, size_
   clear_error();
   Format f = recognize(A);
   if (f == Format::Invalid) return status_of(f);
-  if (f == Format::Unsupported) {  // no kernel of its own: per-value reading of the level functions
-    if (A->order != 2) return fail(SPT_ERR_UNSUPPORTED, "spmv: A must be a matrix");
+  if (f == Format::Unsupported || (f == Format::BCSR && !bcsr_fast_ok(A))) {
+    // no kernel of its own: per-value reading of the level functions
+    if (A->order != 2 && A->order != 4)
+      return fail(SPT_ERR_UNSUPPORTED, "spmv: A must be a matrix or a blocked matrix of order 4");
     if (!generic_ok(A)) return SPT_ERR_UNSUPPORTED;
     if (!x || !y) return fail(SPT_ERR_INVALID_ARG, "spmv: x or y is null");
     return generic_spmv_dispatch(A, x, y, static_cast<hipStream_t>(stream));
   }
   if (!x || !y) return fail(SPT_ERR_INVALID_ARG, "spmv: x or y is null");
+  if (f == Format::BCSR)
+    return bcsr_spmv_dispatch(A, x, y, ws, ws_bytes, static_cast<hipStream_t>(stream));
   return spmv_dispatch(f, A, x, y, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
@@ -546,7 +562,9 @@ size_t spt_workspace_bytes(int32_t op, const spt_tensor* T, int32_t J) {
   Format f = recognize(T);
   if (f == Format::Invalid) return 0;
   if (f == Format::Unsupported || op == SPT_OP_TO_COO) {  // operations defined for any composition
-    if (op == SPT_OP_SPMV && f == Format::Unsupported && T->order == 2 && generic_ok(T)) return 256;
+    if (op == SPT_OP_SPMV && f == Format::Unsupported && (T->order == 2 || T->order == 4) &&
+        generic_ok(T))
+      return 256;
     if (op == SPT_OP_TO_COO && T->order <= 3 && generic_ok(T)) return to_coo_workspace(T->nvals);
     if (g_err[0] == 0) fail(SPT_ERR_UNSUPPORTED, "operation %d is not defined for this composition", op);
     return 0;
@@ -558,6 +576,8 @@ size_t spt_workspace_bytes(int32_t op, const spt_tensor* T, int32_t J) {
         n = seg_spmv_workspace(T->nvals);
       else if (f == Format::COO2)
         n = coo_unordered_workspace(T->dtype, T->nvals, T->level[0].N);
+      else if (f == Format::BCSR && bcsr_fast_ok(T))
+        n = bcsr_workspace(T);
       break;
     case SPT_OP_COO_TO_CSR:
       n = f == Format::COO2 ? coo_to_csr_workspace(T) : 0;

@@ -101,15 +101,20 @@ __device__ __forceinline__ bool leaf_coordinates(const GTensor& G, int64_t p, in
 
 // ---- SpMV: one lane per stored value, one floating-point atomic per component ----
 
+// A matrix has b1 = b2 = 1. A blocked matrix cast as a 4th-order tensor (Section 3.2) has
+// dimensions (block rows, block columns, b1, b2), and component (i1, j1, i2, j2) is matrix
+// element (i1 * b1 + i2, j1 * b2 + j2).
 template <typename T>
 __global__ __launch_bounds__(kBlock) void generic_spmv_kernel(const GTensor G, int64_t nvals,
+                                                              int64_t b1, int64_t b2,
                                                               const T* __restrict__ vals,
                                                               const T* __restrict__ x,
                                                               T* __restrict__ y) {
   const int64_t p = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
   if (p >= nvals) return;
-  int64_t c[4];
-  if (leaf_coordinates(G, p, c)) unsafeAtomicAdd(y + c[0], vals[p] * x[c[1]]);
+  int64_t c[4] = {0, 0, 0, 0};
+  if (leaf_coordinates(G, p, c))
+    unsafeAtomicAdd(y + (c[0] * b1 + c[2]), vals[p] * x[c[1] * b2 + c[3]]);
 }
 
 template <typename T>
@@ -119,8 +124,8 @@ __global__ __launch_bounds__(kBlock) void generic_zero_kernel(T* __restrict__ ou
 }
 
 template <typename T>
-static spt_status generic_spmv_typed(const spt_tensor* A, int64_t rows, const T* x, T* y,
-                                     hipStream_t s) {
+static spt_status generic_spmv_typed(const spt_tensor* A, int64_t rows, int64_t b1, int64_t b2,
+                                     const T* x, T* y, hipStream_t s) {
   if (rows > 0) {
     hipLaunchKernelGGL(generic_zero_kernel<T>, dim3(static_cast<unsigned>((rows + kBlock - 1) / kBlock)),
                        dim3(kBlock), 0, s, y, rows);
@@ -129,7 +134,7 @@ static spt_status generic_spmv_typed(const spt_tensor* A, int64_t rows, const T*
   if (A->nvals > 0) {
     hipLaunchKernelGGL(generic_spmv_kernel<T>,
                        dim3(static_cast<unsigned>((A->nvals + kBlock - 1) / kBlock)), dim3(kBlock), 0,
-                       s, make_gtensor(A), A->nvals, static_cast<const T*>(A->vals), x, y);
+                       s, make_gtensor(A), A->nvals, b1, b2, static_cast<const T*>(A->vals), x, y);
     SPT_CHECK_LAUNCH("generic spmv");
   }
   return SPT_OK;
@@ -144,10 +149,16 @@ static int64_t mode_size(const spt_tensor* T, int mode) {
 
 spt_status generic_spmv_dispatch(const spt_tensor* A, const void* x, void* y, hipStream_t s) {
   if (A->nvals >= (int64_t{1} << 40)) return fail(SPT_ERR_UNSUPPORTED, "spmv: tensor too large");
-  const int64_t rows = mode_size(A, 0);
+  const bool blocked = A->order == 4;
+  const int64_t b1 = blocked ? mode_size(A, 2) : 1, b2 = blocked ? mode_size(A, 3) : 1;
+  const int64_t rows = mode_size(A, 0) * b1;
+  if (rows >= INT32_MAX || mode_size(A, 1) * b2 >= INT32_MAX)
+    return fail(SPT_ERR_UNSUPPORTED, "spmv: matrix beyond 2^31 rows or columns");
   if (A->dtype == SPT_F64)
-    return generic_spmv_typed<double>(A, rows, static_cast<const double*>(x), static_cast<double*>(y), s);
-  return generic_spmv_typed<float>(A, rows, static_cast<const float*>(x), static_cast<float*>(y), s);
+    return generic_spmv_typed<double>(A, rows, b1, b2, static_cast<const double*>(x),
+                                      static_cast<double*>(y), s);
+  return generic_spmv_typed<float>(A, rows, b1, b2, static_cast<const float*>(x),
+                                   static_cast<float*>(y), s);
 }
 
 // ---- any format -> COO, in storage order (count per chunk, scan, fill) ----

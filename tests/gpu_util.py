@@ -26,7 +26,8 @@ def gpu_spmv(spec, x, repeat=1, misalign=False):
     ws = A.workspace(spt.SPT_OP_SPMV)
     outs = []
     for _ in range(repeat):
-        y = torch.full((spec.dims[0],), float("nan"), dtype=A.torch_dtype, device="cuda")
+        rows = spec.dims[0] * (spec.dims[2] if len(spec.dims) == 4 else 1)   # order 4: a blocked matrix
+        y = torch.full((rows,), float("nan"), dtype=A.torch_dtype, device="cuda")
         spt.spt_spmv(A, xd, y, ws)
         torch.cuda.synchronize()
         outs.append(y.cpu().numpy())

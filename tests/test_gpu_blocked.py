@@ -1,0 +1,108 @@
+"""GPU parity: spt_spmv on blocked matrices cast as 4th-order tensors: BCSR (its own kernel, and
+the per-value path for block edges beyond the kernel's) and CSB (per-value path), vs the oracle's
+level walk. The BCSR kernel adds in a fixed order, so repeated runs are bit-identical."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from gpu_util import assert_close, gpu_spmv
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("b1,b2", [(1, 1), (2, 2), (3, 3), (4, 4), (2, 3), (5, 2), (6, 6), (8, 8),
+                                   (7, 5), (4, 16), (64, 1), (1, 64)])
+def test_bcsr_block_shapes(dtype, b1, b2):
+    # 900 block rows of 0..40 blocks: several chunks of 2048 (block, row) pairs, rows that
+    # straddle chunk boundaries, empty block rows
+    w = wl.random_bcsr(900, 700, b1, b2, 0, 40, seed=3000 + 10 * b1 + b2, dtype=dtype)
+    ref, mag = oracle.spmv_blocked(w["bcsr"], w["x"])
+    got = gpu_spmv(w["bcsr"], w["x"], repeat=2)
+    assert_close(got[0], ref, mag, dtype, f"bcsr {b1}x{b2}")
+    assert np.array_equal(got[0], got[1])
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_bcsr_row_length_extremes(dtype):
+    b1, b2 = 4, 4
+    Nb, Mb = 3000, 5000
+    rng = np.random.default_rng(31)
+    # one block row of 4000 blocks (spans 8 chunks), a run of empty block rows at the start, in
+    # the middle and at the end, single-block rows elsewhere
+    L = np.ones(Nb, np.int64)
+    L[:70] = 0
+    L[1000] = 4000
+    L[1001:1600] = 0
+    L[-300:] = 0
+    brow = np.repeat(np.arange(Nb), L)
+    bcol = np.concatenate([np.sort(rng.choice(Mb, n, replace=False)) for n in L if n])
+    pos = np.concatenate([[0], np.cumsum(L)])
+    blocks = rng.uniform(-1, 1, (len(brow), b1, b2)).astype(dtype)
+    spec = wl.bcsr_spec(Nb, Mb, b1, b2, pos, bcol, blocks)
+    x = wl.dense_vector(Mb * b2, 32, dtype)
+    ref, mag = oracle.spmv_blocked(spec, x)
+    got = gpu_spmv(spec, x, repeat=2)
+    assert_close(got[0], ref, mag, dtype, "bcsr extremes")
+    assert np.array_equal(got[0], got[1])
+    assert not got[0][:70 * b1].any() and not got[0][-300 * b1:].any()
+    assert_close(gpu_spmv(spec, x, misalign=True), ref, mag, dtype, "bcsr extremes misaligned")
+
+
+def test_bcsr_degenerate_sizes():
+    for Nb, Mb, lo, hi in ((1, 1, 1, 1), (5, 3, 0, 0), (1, 4000, 3000, 3000), (2049, 1, 1, 1)):
+        w = wl.random_bcsr(Nb, Mb, 3, 2, lo, hi, seed=40 + Nb, dtype=np.float64)
+        ref, mag = oracle.spmv_blocked(w["bcsr"], w["x"])
+        assert_close(gpu_spmv(w["bcsr"], w["x"]), ref, mag, np.float64, f"bcsr {Nb}x{Mb}")
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_blocked_formats_through_the_level_functions(dtype):
+    # CSB (dense grid of sparse COO blocks) and a BCSR with 80-wide blocks, which the BCSR kernel
+    # does not take: both run one lane per stored value
+    N, M, b1, b2 = 900, 1100, 16, 32
+    r, c, v = wl.random_coo_entries(N, M, 20_000, seed=50, dtype=dtype)
+    x = wl.dense_vector(-(-M // b2) * b2, 51, dtype)
+    spec = wl.csb_from_coo(N, M, r, c, v, b1, b2)
+    ref, mag = oracle.spmv_blocked(spec, x)
+    assert_close(gpu_spmv(spec, x), ref, mag, dtype, "csb")
+    wide = wl.random_bcsr(40, 30, 2, 80, 0, 9, seed=52, dtype=dtype)
+    ref, mag = oracle.spmv_blocked(wide["bcsr"], wide["x"])
+    assert_close(gpu_spmv(wide["bcsr"], wide["x"]), ref, mag, dtype, "bcsr 2x80")
+
+
+def test_bcsr_matches_csr_twin_at_size():
+    """A 4x4-blocked matrix of 200k block rows (3.2M blocks, 51M values) against the oracle on a
+    sample of rows and against the library's own CSR path on the same matrix."""
+    w = wl.random_bcsr(200_000, 200_000, 4, 4, 8, 24, seed=60, dtype=np.float64, band=2000, with_csr=True)
+    got = gpu_spmv(w["bcsr"], w["x"])
+    twin = gpu_spmv(w["csr"], w["x"])
+    lv = w["csr"].levels[1]
+    rows = np.random.default_rng(61).choice(800_000, 4000, replace=False)
+    xs = w["x"]
+    for i in rows:
+        seg = slice(lv.pos[i], lv.pos[i + 1])
+        terms = w["csr"].vals[seg] * xs[lv.crd[seg]]
+        assert abs(got[i] - terms.sum()) <= 1e-12 * np.abs(terms).sum()
+    scale = np.abs(twin).max()
+    assert np.abs(got - twin).max() <= 1e-12 * scale * 50
+
+
+def test_blocked_errors():
+    import torch
+    import paper_1804_10112_amd as spt
+    w = wl.random_bcsr(50, 40, 2, 2, 1, 5, seed=70, dtype=np.float32)
+    A = spt.DeviceTensor(w["bcsr"])
+    x = torch.zeros(80, device="cuda")
+    y = torch.zeros(100, device="cuda")
+    with pytest.raises(spt.SptError) as e:
+        spt.spt_spmv(A, x, y, None)
+    assert "workspace" in str(e.value)
+    A.c.nvals -= 1                                           # no whole number of blocks
+    with pytest.raises(spt.SptError):
+        spt.spt_spmv(A, x, y, torch.empty(1 << 16, dtype=torch.uint8, device="cuda"))
+    A.c.nvals += 1
+    A.c.level[1].M = 49                                      # one parent per block row
+    with pytest.raises(spt.SptError):
+        spt.spt_spmv(A, x, y, torch.empty(1 << 16, dtype=torch.uint8, device="cuda"))
