@@ -64,6 +64,24 @@ def test_matrix_kernels(seed):
     assert np.array_equal(cols, ci)
     a, m = oracle.innerprod(coo, other)
     assert_close(gpu_innerprod(coo, other), a, m, dtype, f"seed {seed} innerprod matrices")
+    # element-wise product, CSR x COO (result CSR) and COO x CSR (result COO)
+    (ri, ci), rv, rm = oracle.mul(csr, other)
+    (pos, cols), gv = gpu_add(csr, other, "csr", op="mul")
+    assert np.array_equal(pos, np.concatenate([[0], np.cumsum(np.bincount(ri, minlength=N))]))
+    assert np.array_equal(cols, ci)
+    assert_close(gv, rv, rm, dtype, f"seed {seed} mul csr x coo")
+    idx, gv = gpu_add(other, csr, "coo", op="mul")
+    assert np.array_equal(idx[0], ri) and np.array_equal(idx[1], ci)
+    assert_close(gv, rv, rm, dtype, f"seed {seed} mul coo x csr")
+    # the same matrix blocked: BCSR (own kernel) and CSB (per-value path), block shape per seed
+    b1, b2 = int(rng.integers(1, 9)), int(rng.integers(1, 9))
+    xb = wl.dense_vector(-(-M // b2) * b2, seed + 100, dtype)
+    for name, spec in (("bcsr", wl.bcsr_from_coo(N, M, r, c, v, b1, b2)),
+                       ("csb", wl.csb_from_coo(N, M, r, c, v, b1, b2))):
+        if name == "csb" and (-(-N // b1)) * (-(-M // b2)) > 4_000_000:
+            continue                                        # CSB keeps one pos entry per block of the grid
+        bref, bmag = oracle.spmv_blocked(spec, xb)
+        assert_close(gpu_spmv(spec, xb), bref, bmag, dtype, f"seed {seed} spmv {name} {b1}x{b2}")
 
 
 @pytest.mark.parametrize("seed", SEEDS)
@@ -105,3 +123,7 @@ def test_tensor_kernels(seed):
     idx, pv = gpu_add(coo, other, "coo3")
     assert np.array_equal(idx[0], ri) and np.array_equal(idx[1], rj) and np.array_equal(idx[2], rk)
     assert_close(pv, rv, rm, dtype, f"seed {seed} plus")
+    (ri, rj, rk), rv, rm = oracle.mul(coo, other)
+    idx, pv = gpu_add(coo, other, "coo3", op="mul")
+    assert np.array_equal(idx[0], ri) and np.array_equal(idx[1], rj) and np.array_equal(idx[2], rk)
+    assert_close(pv, rv, rm, dtype, f"seed {seed} element-wise product")
