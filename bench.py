@@ -362,9 +362,11 @@ def build_items(args):
         for nm, spec in (("csc", wl.csc_from_coo(N3, N3, rr, cc, vv)),
                          ("dcsr", wl.dcsr_from_sorted_coo(N3, N3, rr, cc, vv))):
             Ag = spt.DeviceTensor(spec)
-            keep.append(Ag)
-            items.append(Item(f"n5_spmv_{nm}", lambda Ag=Ag: spt.spt_spmv(Ag, xg, yg, None), 2 * nnz3,
-                              8 * nnz3 + 12 * N3, "one atomic per stored value"))
+            wg5 = Ag.workspace(spt.SPT_OP_SPMV)
+            keep.extend([Ag, wg5])
+            items.append(Item(f"n5_spmv_{nm}", lambda Ag=Ag, wg5=wg5: spt.spt_spmv(Ag, xg, yg, wg5), 2 * nnz3,
+                              8 * nnz3 + 12 * N3,
+                              "one atomic per stored value" if nm == "csc" else "CSR kernel over the stored rows"))
         Ae = spt.DeviceTensor(c3["ell"])
         cells = len(c3["ell"].vals)
         g0, g1 = (torch.empty(cells, dtype=torch.int32, device=dev) for _ in range(2))

@@ -128,6 +128,8 @@ typedef struct {
  *   ELL   (D slots W, D rows, S cols)             vals[W*N], cell (k,i) at k*N+i
  *   COO3  (C~U, S~U, S)                           vals[nnz]
  *   CSF3  (C, C, C)                               vals[nnz]
+ *   DCSR  (C rows with pos=[0,stored rows], C cols) vals[nnz]; spt_spmv only (a fast path
+ *         when the row level is flagged unique), otherwise any composition
  *   BCSR  (D block rows, C block cols, D b1, D b2) vals[nblocks*b1*b2], blocks row-major;
  *         a blocked matrix cast as a 4th-order tensor (Section 3.2): order = 4, modes
  *         0..3 = (block row, block column, row in block, column in block), and component
@@ -157,9 +159,12 @@ typedef struct {
  * 0). Every stored entry counts (duplicates add up). COO flagged SPT_ORDERED
  * on its row level runs a deterministic segmented reduction; without the flag
  * the entries are accumulated with floating-point atomics (any order).
- * Any other composition of levels that stores a matrix (DCSR, CSC, dense, hashed
- * rows or columns, ...) is evaluated by reading the level functions of Table 2 per
- * stored value, again with floating-point atomics; it needs no workspace.
+ * DCSR (compressed rows flagged SPT_UNIQUE, compressed cols) runs the CSR kernels over the
+ * stored rows and places each sum at its row coordinate (deterministic; workspace from
+ * spt_workspace_bytes(SPT_OP_SPMV, ...)). Any other composition of levels that stores a
+ * matrix (CSC, dense, hashed rows or columns, DCSR with repeated row coordinates, ...) is
+ * evaluated by reading the level functions of Table 2 per stored value, again with
+ * floating-point atomics; it needs no workspace.
  * A blocked matrix (order 4, Section 3.2): x has (block columns * b2) entries, y has
  * (block rows * b1). BCSR with block edges up to 64 has a kernel of its own
  * (deterministic, workspace from spt_workspace_bytes(SPT_OP_SPMV, ...)); BCSR with larger

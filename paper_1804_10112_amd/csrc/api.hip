@@ -23,6 +23,7 @@ spt_status fail(spt_status code, const char* fmt, ...) {
 spt_status spmv_dispatch(Format f, const spt_tensor* A, const void* x, void* y, void* ws,
                          size_t ws_bytes, hipStream_t s);
 size_t seg_spmv_workspace(int64_t nnz);
+size_t dcsr_spmv_workspace(const spt_tensor* A);
 spt_status spmv_sparse_x_dispatch(const spt_tensor* A, const spt_tensor* X, void* y, void* ws,
                                   size_t ws_bytes, hipStream_t s);
 size_t coo_unordered_workspace(int dtype, int64_t nnz, int64_t nrows);
@@ -164,6 +165,11 @@ Format recognize(const spt_tensor* T) {
       }
       return Format::CSR;
     }
+    // DCSR with unique rows has a fast path for SpMV; every other operation and DCSR with
+    // repeated row coordinates take it as "any composition"
+    if (is(L[0], SPT_COMPRESSED) && is(L[1], SPT_COMPRESSED) && modes(0, 1, 0, 0) && L[0].M == 1 &&
+        unique(L[0]) && L[1].pos && (L[0].crd || L[1].M == 0))
+      return Format::DCSR;
     if (is(L[0], SPT_COMPRESSED) && is(L[1], SPT_SINGLETON) && modes(0, 1, 0, 0)) {
       if (L[0].M != 1) {
         fail(SPT_ERR_INVALID_ARG, "COO: the row level has one root parent (M = 1)");
@@ -578,6 +584,8 @@ size_t spt_workspace_bytes(int32_t op, const spt_tensor* T, int32_t J) {
         n = coo_unordered_workspace(T->dtype, T->nvals, T->level[0].N);
       else if (f == Format::BCSR && bcsr_fast_ok(T))
         n = bcsr_workspace(T);
+      else if (f == Format::DCSR)
+        n = dcsr_spmv_workspace(T);
       break;
     case SPT_OP_COO_TO_CSR:
       n = f == Format::COO2 ? coo_to_csr_workspace(T) : 0;

@@ -568,11 +568,51 @@ spt_status spmv_sparse_x_dispatch(const spt_tensor* A, const spt_tensor* X, void
   return spmv_sparse_x_typed<float>(A, X, static_cast<float*>(y), ws, ws_bytes, s);
 }
 
+// y[row[r]] = t[r] for the stored rows of a doubly compressed matrix
+template <typename T>
+__global__ __launch_bounds__(kBlock) void scatter_rows_kernel(int n, const int32_t* __restrict__ row,
+                                                              const T* __restrict__ t,
+                                                              T* __restrict__ y) {
+  const int r = blockIdx.x * kBlock + threadIdx.x;
+  if (r < n) y[row[r]] = t[r];
+}
+
+size_t dcsr_spmv_workspace(const spt_tensor* A) {
+  return align_up(static_cast<size_t>(A->level[1].M) * 8, 256) + seg_spmv_workspace(A->nvals);
+}
+
 template <typename T>
 static spt_status spmv_typed(Format f, const spt_tensor* A, const T* x, T* y, void* ws,
                              size_t ws_bytes, hipStream_t s) {
   const T* vals = static_cast<const T*>(A->vals);
   switch (f) {
+    case Format::DCSR: {
+      // (compressed, compressed): the column level is a CSR over the stored rows only, so
+      // the CSR kernels produce one sum per stored row, which is then placed at the row's
+      // coordinate in the zero-filled y (row coordinates are unique: no two sums collide)
+      const int64_t N = A->level[0].N, stored = A->level[1].M;
+      spt_status st = launch_fill<T>(y, N, T(0), s);
+      if (st != SPT_OK || stored == 0) return st;
+      if (stored >= INT32_MAX) return fail(SPT_ERR_UNSUPPORTED, "spmv: more than 2^31 stored rows");
+      if (!ws || ws_bytes < dcsr_spmv_workspace(A))
+        return fail(SPT_ERR_WORKSPACE, "spmv: workspace of %zu bytes needed, %zu given",
+                    dcsr_spmv_workspace(A), ws_bytes);
+      Workspace W(ws, ws_bytes);
+      T* t = reinterpret_cast<T*>(W.take<double>(stored));
+      char* rest = static_cast<char*>(ws) + W.used;
+      const int hint = A->level[1].max_children;
+      if (hint > 0 && hint <= kShortRowHint && A->nvals > 0 && A->nvals < INT32_MAX)
+        st = launch_csr_stream<T, DenseX<T>>(A->nvals, stored, A->level[1].pos, A->level[1].crd, vals,
+                                             DenseX<T>{x}, t, s);
+      else
+        st = launch_seg<T, true>(A->nvals, stored, A->level[1].pos, A->level[1].crd, vals, x, t, rest,
+                                 ws_bytes - W.used, s);
+      if (st != SPT_OK) return st;
+      hipLaunchKernelGGL(scatter_rows_kernel<T>, dim3(static_cast<unsigned>((stored + kBlock - 1) / kBlock)),
+                         dim3(kBlock), 0, s, static_cast<int>(stored), A->level[0].crd, t, y);
+      SPT_CHECK_LAUNCH("scatter rows");
+      return SPT_OK;
+    }
     case Format::CSR: {
       const int hint = A->level[1].max_children;
       if (hint > 0 && hint <= kShortRowHint && A->nvals > 0 && A->level[0].N + 1 < INT32_MAX &&

@@ -127,3 +127,59 @@ def test_generic_errors():
     with pytest.raises(spt.SptError) as e:
         spt.spt_to_coo(d, None, None, None, None, None, None)
     assert e.value.status == 1
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_dcsr_fast_path_and_its_fallbacks(dtype):
+    """DCSR with unique row coordinates runs the CSR kernels over the stored rows; with a declared
+    short-row bound the streamed kernel; with repeated row coordinates the per-value path."""
+    N, M = 5000, 3000
+    r, c, v = _entries(N, M, 40_000, 1700, dtype)
+    r = (r // 7) * 7                                          # 6 of 7 rows empty: DCSR really compresses
+    o = np.lexsort((c, r))
+    key, first = np.unique(r[o].astype(np.int64) * M + c[o], return_index=True)
+    r, c, v = r[o][first], c[o][first], v[o][first]
+    x = wl.dense_vector(M, 8, dtype)
+    ref, mag = oracle.spmv(wl.coo_spec(N, M, r, c, v), x)
+    d = wl.dcsr_from_sorted_coo(N, M, r, c, v)
+    assert len(d.levels[0].crd) < N // 6
+    assert_close(gpu_spmv(d, x), ref, mag, dtype, "dcsr")
+    assert_close(gpu_spmv(d, x, misalign=True), ref, mag, dtype, "dcsr misaligned")
+    two = gpu_spmv(d, x, repeat=2)
+    assert np.array_equal(two[0], two[1])                     # segmented sums: run-to-run identical
+    hinted = wl.dcsr_from_sorted_coo(N, M, r, c, v)
+    hinted.levels[1].max_children = int(np.bincount(r).max())
+    assert hinted.levels[1].max_children > 0
+    if hinted.levels[1].max_children > 32:
+        hinted.levels[1].max_children = 32                    # a bound the data may violate: still correct
+    assert_close(gpu_spmv(hinted, x), ref, mag, dtype, "dcsr hinted")
+    # stored rows in another order (the row level not ordered)
+    rows, first = np.unique(r, return_index=True)
+    perm = np.random.default_rng(3).permutation(len(rows))
+    seg = np.concatenate([first, [len(r)]])
+    idx = np.concatenate([np.arange(seg[k], seg[k + 1]) for k in perm])
+    lens = (seg[1:] - seg[:-1])[perm]
+    sh = wl.TensorSpec((N, M), [
+        wl.LevelSpec(wl.COMPRESSED, 0, N, M=1, pos=np.array([0, len(rows)], np.int32), crd=rows[perm].astype(np.int32),
+                     ordered=False),
+        wl.LevelSpec(wl.COMPRESSED, 1, M, M=len(rows), pos=np.concatenate([[0], np.cumsum(lens)]).astype(np.int32),
+                     crd=c[idx].astype(np.int32)),
+    ], v[idx])
+    assert_close(gpu_spmv(sh, x), ref, mag, dtype, "dcsr shuffled rows")
+    # a row coordinate stored twice (level 0 not unique): sums must add up, per-value path
+    half = len(rows) // 2
+    dup_rows = np.concatenate([rows, rows[:half]])
+    cut = seg[half]
+    dup = wl.TensorSpec((N, M), [
+        wl.LevelSpec(wl.COMPRESSED, 0, N, M=1, pos=np.array([0, len(dup_rows)], np.int32),
+                     crd=dup_rows.astype(np.int32), ordered=False, unique=False),
+        wl.LevelSpec(wl.COMPRESSED, 1, M, M=len(dup_rows),
+                     pos=np.concatenate([seg, len(r) + seg[1:half + 1]]).astype(np.int32),
+                     crd=np.concatenate([c, c[:cut]]).astype(np.int32)),
+    ], np.concatenate([v, v[:cut]]))
+    dref, dmag = oracle.spmv(dup, x)
+    assert_close(gpu_spmv(dup, x), dref, dmag, dtype, "dcsr repeated rows")
+    # no stored row at all
+    e = np.zeros(0, np.int32)
+    empty = wl.dcsr_from_sorted_coo(N, M, e, e, np.zeros(0, dtype))
+    assert not gpu_spmv(empty, x).any()
