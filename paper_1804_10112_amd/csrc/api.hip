@@ -268,6 +268,15 @@ static bool generic_ok(const spt_tensor* T) {
   return true;
 }
 
+// The kernels carve typed arrays out of the workspace at 256-byte steps.
+static bool ws_misaligned(const void* ws) {
+  if (ws && reinterpret_cast<uintptr_t>(ws) % 256 != 0) {
+    fail(SPT_ERR_INVALID_ARG, "workspace pointer is not 256-byte aligned");
+    return true;
+  }
+  return false;
+}
+
 static spt_status status_of(Format f) {
   return f == Format::Invalid ? SPT_ERR_INVALID_ARG : SPT_ERR_UNSUPPORTED;
 }
@@ -284,6 +293,7 @@ const char* spt_version(void) { return "spt 0.1 gfx950"; }
 spt_status spt_spmv(const spt_tensor* A, const void* x, void* y, void* ws, size_t ws_bytes,
                     void* stream) {
   clear_error();
+  if (ws_misaligned(ws)) return SPT_ERR_INVALID_ARG;
   Format f = recognize(A);
   if (f == Format::Invalid) return status_of(f);
   if (f == Format::Unsupported || (f == Format::BCSR && !bcsr_fast_ok(A))) {
@@ -303,6 +313,7 @@ spt_status spt_spmv(const spt_tensor* A, const void* x, void* y, void* ws, size_
 spt_status spt_spmv_sparse_x(const spt_tensor* A, const spt_tensor* x, void* y, void* ws,
                              size_t ws_bytes, void* stream) {
   clear_error();
+  if (ws_misaligned(ws)) return SPT_ERR_INVALID_ARG;
   Format f = recognize(A);
   if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
   if (f != Format::CSR) return fail(SPT_ERR_UNSUPPORTED, "spmv_sparse_x: A must be CSR");
@@ -333,6 +344,7 @@ spt_status spt_spmv_sparse_x(const spt_tensor* A, const spt_tensor* x, void* y, 
 spt_status spt_coo_to_csr(const spt_tensor* A, int32_t order, int32_t* pos_out, int32_t* crd_out,
                           void* vals_out, void* ws, size_t ws_bytes, void* stream) {
   clear_error();
+  if (ws_misaligned(ws)) return SPT_ERR_INVALID_ARG;
   Format f = recognize(A);
   if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
   if (f != Format::COO2) return fail(SPT_ERR_UNSUPPORTED, "coo_to_csr: input is not a COO matrix");
@@ -347,6 +359,7 @@ spt_status spt_coo_to_csr(const spt_tensor* A, int32_t order, int32_t* pos_out, 
 spt_status spt_ttv(const spt_tensor* B, const void* c, int32_t* out_crd0, int32_t* out_crd1,
                    void* out_vals, int64_t* out_nnz_dev, void* ws, size_t ws_bytes, void* stream) {
   clear_error();
+  if (ws_misaligned(ws)) return SPT_ERR_INVALID_ARG;
   Format f = recognize(B);
   if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
   if (f != Format::COO3 && f != Format::CSF3)
@@ -361,6 +374,7 @@ spt_status spt_ttv(const spt_tensor* B, const void* c, int32_t* out_crd0, int32_
 spt_status spt_mttkrp(const spt_tensor* B, const void* C, const void* D, int32_t J, void* A_out,
                       void* ws, size_t ws_bytes, void* stream) {
   clear_error();
+  if (ws_misaligned(ws)) return SPT_ERR_INVALID_ARG;
   Format f = recognize(B);
   if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
   if (f != Format::COO3 && f != Format::CSF3)
@@ -373,6 +387,7 @@ spt_status spt_mttkrp(const spt_tensor* B, const void* C, const void* D, int32_t
 spt_status spt_spdm(const spt_tensor* B, const void* C, int32_t J, void* A_out, void* ws,
                     size_t ws_bytes, void* stream) {
   clear_error();
+  if (ws_misaligned(ws)) return SPT_ERR_INVALID_ARG;
   Format f = recognize(B);
   if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
   if (f != Format::COO2) return fail(SPT_ERR_UNSUPPORTED, "spdm: B must be a COO matrix");
@@ -385,6 +400,7 @@ spt_status spt_ttm(const spt_tensor* B, const void* C, int32_t K, int32_t* out_c
                    int32_t* out_crd1, void* out_vals, int64_t* out_nfib_dev, void* ws,
                    size_t ws_bytes, void* stream) {
   clear_error();
+  if (ws_misaligned(ws)) return SPT_ERR_INVALID_ARG;
   Format f = recognize(B);
   if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
   if (f != Format::COO3 && f != Format::CSF3)
@@ -400,6 +416,7 @@ spt_status spt_ttm(const spt_tensor* B, const void* C, int32_t K, int32_t* out_c
 spt_status spt_innerprod(const spt_tensor* B, const spt_tensor* C, void* alpha_out, void* ws,
                          size_t ws_bytes, void* stream) {
   clear_error();
+  if (ws_misaligned(ws)) return SPT_ERR_INVALID_ARG;
   Format fb = recognize(B);
   if (fb == Format::Invalid || fb == Format::Unsupported) return status_of(fb);
   Format fc = recognize(C);
@@ -422,6 +439,7 @@ spt_status spt_coo3_to_csf(const spt_tensor* B, int32_t* pos0, int32_t* crd0, in
                            int32_t* crd1, int32_t* pos2, int32_t* crd2, void* vals_out,
                            int64_t* counts_dev, void* ws, size_t ws_bytes, void* stream) {
   clear_error();
+  if (ws_misaligned(ws)) return SPT_ERR_INVALID_ARG;
   Format f = recognize(B);
   if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
   if (f != Format::COO3) return fail(SPT_ERR_UNSUPPORTED, "coo3_to_csf: B must be COO3");
@@ -437,6 +455,7 @@ spt_status spt_coo3_to_csf(const spt_tensor* B, int32_t* pos0, int32_t* crd0, in
 spt_status spt_to_ell(const spt_tensor* A, int32_t W, int32_t* crd_out, void* vals_out,
                       int32_t* longest_dev, void* ws, size_t ws_bytes, void* stream) {
   clear_error();
+  if (ws_misaligned(ws)) return SPT_ERR_INVALID_ARG;
   Format f = recognize(A);
   if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
   if (f != Format::COO2 && f != Format::CSR)
@@ -464,6 +483,7 @@ spt_status spt_to_hashed_rows(const spt_tensor* A, int32_t W, int32_t* crd_out, 
 spt_status spt_coo_dia_offsets(const spt_tensor* A, int32_t* offsets_out, int64_t cap,
                                int64_t* K_dev, void* ws, size_t ws_bytes, void* stream) {
   clear_error();
+  if (ws_misaligned(ws)) return SPT_ERR_INVALID_ARG;
   Format f = recognize(A);
   if (f == Format::Invalid || f == Format::Unsupported) return status_of(f);
   if (f != Format::COO2) return fail(SPT_ERR_UNSUPPORTED, "coo_dia_offsets: A must be a COO matrix");
@@ -487,6 +507,7 @@ spt_status spt_coo_to_dia(const spt_tensor* A, int32_t K, const int32_t* offsets
 spt_status spt_to_coo(const spt_tensor* T, int32_t* out_crd0, int32_t* out_crd1, int32_t* out_crd2,
                       void* out_vals, int64_t* out_nnz_dev, void* ws, size_t ws_bytes, void* stream) {
   clear_error();
+  if (ws_misaligned(ws)) return SPT_ERR_INVALID_ARG;
   Format f = recognize(T);
   if (f == Format::Invalid) return status_of(f);
   if (T->order > 3) return fail(SPT_ERR_UNSUPPORTED, "to_coo: order %d above 3", T->order);
@@ -529,6 +550,7 @@ static spt_status add_or_mul(int op, const spt_tensor* B, const spt_tensor* C, i
                              int32_t* out_crd0, int32_t* out_crd1, int32_t* out_crd2, void* out_vals,
                              int64_t* out_nnz_dev, void* ws, size_t ws_bytes, void* stream) {
   clear_error();
+  if (ws_misaligned(ws)) return SPT_ERR_INVALID_ARG;
   Format fb, fc;
   spt_status st = add_operands(B, C, &fb, &fc);
   if (st != SPT_OK) return st;

@@ -107,6 +107,11 @@ def test_invalid_and_unsupported_descriptors():
     # a 3rd-order tensor is no operand of SpMV
     c5s = wl.config5(dims=(20, 16, 12), nnz=300, rank=4)
     assert _status(spt.spt_spmv, _host_desc(c5s["coo"]), 0x1000, 0x1000, None, 0)[0] == B.SPT_ERR_UNSUPPORTED
+    # a workspace that is not 256-byte aligned is refused before anything is launched
+    import ctypes
+    t = _host_desc(c1["csr"])
+    st = B.lib().spt_spmv(ctypes.byref(t), 0x1000, 0x1000, 0x10010, 1 << 20, None)
+    assert st == B.SPT_ERR_INVALID_ARG and "aligned" in B.spt_last_error()
     # null operands, bad order, bad rank, wrong operation for the format
     t = _host_desc(c1["coo"])
     assert _status(spt.spt_spmv, t, None, 0x1000, None, 0)[0] == B.SPT_ERR_INVALID_ARG
