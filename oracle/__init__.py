@@ -75,6 +75,10 @@ def lib():
         L.orc_add.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp]
         L.orc_spmv_blocked.restype = None
         L.orc_spmv_blocked.argtypes = [vp, vp, C.c_int64, C.c_int64, C.c_int64, vp, vp]
+        L.orc_mul_dense.restype = None
+        L.orc_mul_dense.argtypes = [vp, vp, C.c_int64, C.c_int64, vp]
+        L.orc_add_to_dense.restype = None
+        L.orc_add_to_dense.argtypes = [vp, vp, C.c_int64, C.c_int64, vp, vp]
         L.orc_mul.restype = C.c_int64
         L.orc_mul.argtypes = [vp, vp, vp, C.c_int64, vp, vp, vp]
         L.orc_innerprod.restype = C.c_double
@@ -283,6 +287,30 @@ def add(bspec, cspec):
     if n < 0:
         raise ValueError("orc_add: unsupported operands")
     return [c[:n] for c in crd], v[:n], mag[:n]
+
+
+def mul_dense(bspec, D):
+    """Reference values of B .* D on B's structure: float64[nvals] (0 where a leaf position holds
+    no component). D: dense (N, M) array of B's dtype."""
+    T = OTensor(bspec)
+    D = np.ascontiguousarray(D)
+    if D.dtype != bspec.vals.dtype or D.shape != tuple(bspec.dims):
+        raise TypeError("D must be a dense matrix of B's shape and dtype")
+    out = np.zeros(max(len(bspec.vals), 1), np.float64)
+    lib().orc_mul_dense(T.ref, _ptr(D), D.shape[1], len(bspec.vals), _ptr(out))
+    return out[:len(bspec.vals)]
+
+
+def add_to_dense(bspec, cspec):
+    """Reference dense A = B + C: (A[N, M] float64, magnitudes)."""
+    if tuple(bspec.dims) != tuple(cspec.dims):
+        raise ValueError("operands differ in shape")
+    TB, TC = OTensor(bspec), OTensor(cspec)
+    N, M = bspec.dims
+    A = np.zeros((N, M), np.float64)
+    mag = np.zeros((N, M), np.float64)
+    lib().orc_add_to_dense(TB.ref, TC.ref, N, M, _ptr(A), _ptr(mag))
+    return A, mag
 
 
 def mul(bspec, cspec):

@@ -425,6 +425,43 @@ int64_t orc_add(const orc_tensor* B, const orc_tensor* C, const int64_t* dims, i
   return n;
 }
 
+typedef struct {
+  const orc_tensor* T;
+  const void* D;
+  int64_t ld;
+  double* out;
+} muld_ctx;
+static void muld_visit(void* vctx, const int64_t* c, int64_t p) {
+  muld_ctx* S = (muld_ctx*)vctx;
+  S->out[p] = val_at(S->T, p) * dense_at(S->D, S->T->is_f64, c[0] * S->ld + c[1]);
+}
+void orc_mul_dense(const orc_tensor* B, const void* D, int64_t ld, int64_t nvals, double* out) {
+  for (int64_t p = 0; p < nvals; ++p) out[p] = 0.0; /* positions that hold no component */
+  muld_ctx S = {B, D, ld, out};
+  orc_enumerate(B, muld_visit, &S);
+}
+
+typedef struct {
+  const orc_tensor* T;
+  int64_t ld;
+  double* A;
+  double* mag;
+} addd_ctx;
+static void addd_visit(void* vctx, const int64_t* c, int64_t p) {
+  addd_ctx* S = (addd_ctx*)vctx;
+  double v = val_at(S->T, p);
+  S->A[c[0] * S->ld + c[1]] += v; /* insert into the dense result: locate is i*ld + j */
+  S->mag[c[0] * S->ld + c[1]] += fabs(v);
+}
+void orc_add_to_dense(const orc_tensor* B, const orc_tensor* C, int64_t rows, int64_t ld, double* A,
+                      double* mag) {
+  for (int64_t q = 0; q < rows * ld; ++q) A[q] = mag[q] = 0.0;
+  addd_ctx S = {B, ld, A, mag};
+  orc_enumerate(B, addd_visit, &S);
+  S.T = C;
+  orc_enumerate(C, addd_visit, &S);
+}
+
 int64_t orc_mul(const orc_tensor* B, const orc_tensor* C, const int64_t* dims, int64_t cap,
                 int32_t* const* out_crd, double* out_v, double* out_mag) {
   long double space = 1.0L;

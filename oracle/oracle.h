@@ -105,6 +105,20 @@ double orc_innerprod(const orc_tensor* B, const orc_tensor* C, const int64_t* di
 int64_t orc_add(const orc_tensor* B, const orc_tensor* C, const int64_t* dims, int64_t cap,
                 int32_t* const* out_crd, double* out_v, double* out_mag);
 
+/* A = B .* D with D a dense N x M matrix (row-major, leading dimension ld), the first of the
+ * element-wise products of Figure 1: the result has B's structure, so only its values are
+ * produced, out[p] = B.vals[p] * D(i, j) for the component (i, j) at leaf position p, 0 at
+ * positions that hold no component (ELL padding, cells outside a range level). D has B's dtype.
+ * out: nvals doubles. B: any composition that stores a matrix. */
+void orc_mul_dense(const orc_tensor* B, const void* D, int64_t ld, int64_t nvals, double* out);
+
+/* A = B + C with a dense result (the CSR + COO example of Section 4.4, Figure 9): a dense
+ * output supports insert (Table 3), so no merge is needed: each operand is walked on its own
+ * and every component is added at A[i*ld + j]. A and mag (sum of |terms|): rows*ld doubles,
+ * overwritten. B, C: any compositions that store matrices of equal dimensions. */
+void orc_add_to_dense(const orc_tensor* B, const orc_tensor* C, int64_t rows, int64_t ld, double* A,
+                      double* mag);
+
 /* A = B .* C (element-wise product) with a sparse result: the intersection merge of Section 4.4
  * (the running example of Sections 1 and 4, Figure 1): both operands are walked in order of
  * linearised coordinate, the one with the smaller coordinate advances, and only a coordinate

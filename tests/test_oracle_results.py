@@ -563,6 +563,61 @@ def test_mul_third_order_vs_dense_and_closed_forms():
     assert np.array_equal(fi, oi) and np.array_equal(fk, ok) and np.array_equal(fv, v)
 
 
+# ------------------------------------------------------------------ element-wise with a dense operand / result
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_mul_dense_vs_scipy_on_every_format(dtype):
+    N, M = 37, 53
+    r, c, v = wl.random_coo_entries(N, M, 400, seed=94, dtype=dtype)
+    D = np.random.default_rng(95).uniform(-1, 1, (N, M)).astype(dtype)
+    S = sp.coo_matrix((v.astype(np.float64), (r, c)), shape=(N, M)).tocsr().multiply(D.astype(np.float64)).tocsr()
+    S.sort_indices()
+    for spec in (wl.coo_spec(N, M, r, c, v), wl.csr_from_sorted_coo(N, M, r, c, v),
+                 wl.dcsr_from_sorted_coo(N, M, r, c, v)):
+        out = oracle.mul_dense(spec, D)                     # row-major storage order = scipy's sorted CSR
+        np.testing.assert_allclose(out, S.data, rtol=0, atol=1e-15)
+    # a column-major format: values come out in its own storage order
+    csc = wl.csc_from_coo(N, M, r, c, v)
+    coords, _ = oracle.to_coo(csc)
+    np.testing.assert_allclose(oracle.mul_dense(csc, D), S.toarray()[coords[0], coords[1]], rtol=0, atol=1e-15)
+    # ELL: padding positions give 0, the rest the products
+    c3 = wl.config3(N=40, lo=0, hi=6, seed=96, dtype=dtype)
+    ell = c3["ell"]
+    D2 = np.random.default_rng(97).uniform(-1, 1, ell.dims).astype(dtype)
+    out = oracle.mul_dense(ell, D2)
+    crd = ell.levels[2].crd
+    rows = np.tile(np.arange(40), len(crd) // 40)
+    want = np.where(crd >= 0, ell.vals.astype(np.float64) * D2[rows, np.maximum(crd, 0)], 0.0)
+    np.testing.assert_allclose(out, want, rtol=0, atol=1e-15)
+    # D = 1 returns B's values, a non-square D of the transposed shape is refused
+    assert np.array_equal(oracle.mul_dense(wl.coo_spec(N, M, r, c, v), np.ones((N, M), dtype)), v.astype(np.float64))
+    with pytest.raises(TypeError):
+        oracle.mul_dense(wl.coo_spec(N, M, r, c, v), D.T)
+
+
+def test_add_to_dense_vs_numpy():
+    N, M = 29, 31
+    r1, c1, v1 = wl.random_coo_entries(N, M, 300, seed=98, dtype=np.float64)
+    r2, c2, v2 = wl.random_coo_entries(N, M, 350, seed=99, dtype=np.float64)
+    want = (sp.coo_matrix((v1, (r1, c1)), shape=(N, M)).toarray() + sp.coo_matrix((v2, (r2, c2)), shape=(N, M)).toarray())
+    wmag = (sp.coo_matrix((np.abs(v1), (r1, c1)), shape=(N, M)).toarray() +
+            sp.coo_matrix((np.abs(v2), (r2, c2)), shape=(N, M)).toarray())
+    pairs = [(wl.csr_from_sorted_coo(N, M, r1, c1, v1), wl.coo_spec(N, M, r2, c2, v2)),   # the paper's CSR + COO
+             (wl.coo_spec(N, M, r1, c1, v1), wl.csc_from_coo(N, M, r2, c2, v2)),
+             (wl.dcsr_from_sorted_coo(N, M, r1, c1, v1), wl.csr_from_sorted_coo(N, M, r2, c2, v2))]
+    for b, c in pairs:
+        A, mag = oracle.add_to_dense(b, c)
+        np.testing.assert_allclose(A, want, rtol=0, atol=1e-15)
+        np.testing.assert_allclose(mag, wmag, rtol=0, atol=1e-15)
+    # agrees with the sparse-result addition where that one stores an entry, 0 elsewhere
+    (ri, ci), sv, _ = oracle.add(*pairs[0])
+    A, _ = oracle.add_to_dense(*pairs[0])
+    assert np.array_equal(A[ri, ci], sv)
+    mask = np.ones((N, M), bool)
+    mask[ri, ci] = False
+    assert not A[mask].any()
+
+
 # ------------------------------------------------------------------ packing into CSF / ELL / DIA
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
