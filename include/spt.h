@@ -343,6 +343,26 @@ spt_status spt_mul(const spt_tensor* B, const spt_tensor* C, int32_t* out_pos, i
                    void* ws, size_t ws_bytes, void* stream);
 size_t spt_add_workspace_bytes(const spt_tensor* B, const spt_tensor* C);
 
+/*
+ * Element-wise operations with a dense operand or a dense result, on matrices in ANY legal
+ * composition of level formats (read per stored value through the level functions).
+ * spt_mul_dense: A = B .* D (the first element-wise product of Figure 1). D: dense N x M,
+ *   row-major with leading dimension ld >= M, B's dtype. The result has B's structure, so only
+ *   values are produced: out_vals[p] = B.vals[p] * D(i, j) for the component (i, j) stored at
+ *   leaf position p, 0 at positions that hold no component (ELL padding, empty hash buckets,
+ *   cells outside a range level). out_vals: B.nvals entries; may not alias B.vals.
+ * spt_add_to_dense: A = B + C with a dense result (the CSR + COO example of Section 4.4,
+ *   Figure 9). A: dense N x M, row-major with leading dimension ld, OVERWRITTEN (cells that
+ *   neither operand stores get 0). A dense result supports insertion at a computed position
+ *   (Table 3), so the operands are not merged: each is walked on its own and its components
+ *   are added with floating-point atomics (a cell receives at most one term per operand when
+ *   coordinates are unique, so the result does not depend on the order). B, C: equal
+ *   dimensions and dtype, formats may differ.
+ * Neither needs a workspace.
+ */
+spt_status spt_mul_dense(const spt_tensor* B, const void* D, int64_t ld, void* out_vals, void* stream);
+spt_status spt_add_to_dense(const spt_tensor* B, const spt_tensor* C, void* A, int64_t ld, void* stream);
+
 /* Workspace size in bytes for `op` on tensor T (J only for MTTKRP and TTM).
  * Returns 0 for invalid descriptors (spt_last_error says why). Never fails for
  * a valid one; the result is always >= 256. */

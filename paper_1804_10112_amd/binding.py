@@ -26,7 +26,7 @@ SPT_F32, SPT_F64 = 0, 1
 SYMBOLS = ["spt_spmv", "spt_coo_to_csr", "spt_ttv", "spt_mttkrp", "spt_workspace_bytes",
            "spt_last_error", "spt_version", "spt_probe_read", "spt_probe_gather",
            "spt_spmv_sparse_x", "spt_spdm", "spt_innerprod", "spt_ttm",
-           "spt_add", "spt_mul", "spt_add_workspace_bytes", "spt_coo3_to_csf", "spt_to_ell",
+           "spt_add", "spt_mul", "spt_add_workspace_bytes", "spt_mul_dense", "spt_add_to_dense", "spt_coo3_to_csf", "spt_to_ell",
            "spt_coo_dia_offsets", "spt_coo_to_dia", "spt_to_coo", "spt_to_hashed_rows"]
 
 
@@ -87,6 +87,10 @@ def lib():
         L.spt_add.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.spt_mul.restype = i32
         L.spt_mul.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.spt_mul_dense.restype = i32
+        L.spt_mul_dense.argtypes = [vp, vp, C.c_int64, vp, vp]
+        L.spt_add_to_dense.restype = i32
+        L.spt_add_to_dense.argtypes = [vp, vp, vp, C.c_int64, vp]
         L.spt_add_workspace_bytes.restype = sz
         L.spt_add_workspace_bytes.argtypes = [vp, vp]
         L.spt_ttm.restype = i32
@@ -246,6 +250,14 @@ def spt_mul(B, Ct, out_pos, out_crd0, out_crd1, out_crd2, out_vals, out_nnz_dev,
     p, n = _ws(ws)
     _check(lib().spt_mul(_desc(B), _desc(Ct), _p(out_pos), _p(out_crd0), _p(out_crd1), _p(out_crd2),
                          _p(out_vals), _p(out_nnz_dev), p, n, _stream(stream)))
+
+
+def spt_mul_dense(B, D, ld, out_vals, stream=None):
+    _check(lib().spt_mul_dense(_desc(B), _p(D), ld, _p(out_vals), _stream(stream)))
+
+
+def spt_add_to_dense(B, Ct, A, ld, stream=None):
+    _check(lib().spt_add_to_dense(_desc(B), _desc(Ct), _p(A), ld, _stream(stream)))
 
 
 def spt_add_workspace_bytes(B, Ct):

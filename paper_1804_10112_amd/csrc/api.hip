@@ -77,6 +77,9 @@ bool bcsr_fast_ok(const spt_tensor* A);
 spt_status to_coo_dispatch(const spt_tensor* T, int32_t* o0, int32_t* o1, int32_t* o2, void* ov,
                            int64_t* out_nnz, void* ws, size_t ws_bytes, hipStream_t s);
 size_t to_coo_workspace(int64_t nvals);
+spt_status mul_dense_dispatch(const spt_tensor* B, const void* D, int64_t ld, void* out, hipStream_t s);
+spt_status add_to_dense_dispatch(const spt_tensor* B, const spt_tensor* C, void* A, int64_t ld,
+                                 hipStream_t s);
 
 static bool is(const spt_level& L, int kind) { return L.kind == kind; }
 static bool unique(const spt_level& L) { return (L.flags & SPT_UNIQUE) != 0; }
@@ -575,6 +578,46 @@ spt_status spt_mul(const spt_tensor* B, const spt_tensor* C, int32_t* out_pos, i
                    void* ws, size_t ws_bytes, void* stream) {
   return add_or_mul(1, B, C, out_pos, out_crd0, out_crd1, out_crd2, out_vals, out_nnz_dev, ws,
                     ws_bytes, stream);
+}
+
+// A matrix in any composition the per-value reading is defined for.
+static spt_status any_matrix(const spt_tensor* T, const char* what) {
+  Format f = recognize(T);
+  if (f == Format::Invalid) return SPT_ERR_INVALID_ARG;
+  if (T->order != 2) return fail(SPT_ERR_UNSUPPORTED, "%s: operand must be a matrix", what);
+  if (!generic_ok(T)) return SPT_ERR_UNSUPPORTED;
+  return SPT_OK;
+}
+
+static int64_t dim_of(const spt_tensor* T, int mode) {
+  for (int k = 0; k < T->nlevels; ++k)
+    if (T->level[k].mode == mode) return T->level[k].N;
+  return 0;
+}
+
+spt_status spt_mul_dense(const spt_tensor* B, const void* D, int64_t ld, void* out_vals, void* stream) {
+  clear_error();
+  spt_status st = any_matrix(B, "mul_dense");
+  if (st != SPT_OK) return st;
+  if (ld < dim_of(B, 1)) return fail(SPT_ERR_INVALID_ARG, "mul_dense: ld = %lld below the column count", (long long)ld);
+  if (B->nvals > 0 && (!D || !out_vals)) return fail(SPT_ERR_INVALID_ARG, "mul_dense: D or out_vals is null");
+  return mul_dense_dispatch(B, D, ld, out_vals, static_cast<hipStream_t>(stream));
+}
+
+spt_status spt_add_to_dense(const spt_tensor* B, const spt_tensor* C, void* A, int64_t ld, void* stream) {
+  clear_error();
+  spt_status st = any_matrix(B, "add_to_dense");
+  if (st != SPT_OK) return st;
+  st = any_matrix(C, "add_to_dense");
+  if (st != SPT_OK) return st;
+  if (B->dtype != C->dtype) return fail(SPT_ERR_INVALID_ARG, "add_to_dense: B and C differ in dtype");
+  for (int m = 0; m < 2; ++m)
+    if (dim_of(B, m) != dim_of(C, m))
+      return fail(SPT_ERR_INVALID_ARG, "add_to_dense: dimension %d differs (%lld vs %lld)", m,
+                  (long long)dim_of(B, m), (long long)dim_of(C, m));
+  if (ld < dim_of(B, 1)) return fail(SPT_ERR_INVALID_ARG, "add_to_dense: ld = %lld below the column count", (long long)ld);
+  if (!A && dim_of(B, 0) * dim_of(B, 1) > 0) return fail(SPT_ERR_INVALID_ARG, "add_to_dense: A is null");
+  return add_to_dense_dispatch(B, C, A, ld, static_cast<hipStream_t>(stream));
 }
 
 size_t spt_add_workspace_bytes(const spt_tensor* B, const spt_tensor* C) {

@@ -161,6 +161,87 @@ spt_status generic_spmv_dispatch(const spt_tensor* A, const void* x, void* y, hi
                                    static_cast<float*>(y), s);
 }
 
+// ---- element-wise with a dense operand or a dense result ----
+
+// out[p] = vals[p] * D(i, j) on the structure of the sparse operand (Figure 1); positions that
+// hold no component give 0.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void generic_mul_dense_kernel(const GTensor G, int64_t nvals,
+                                                                   const T* __restrict__ vals,
+                                                                   const T* __restrict__ D, int64_t ld,
+                                                                   T* __restrict__ out) {
+  const int64_t p = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+  if (p >= nvals) return;
+  int64_t c[4] = {0, 0, 0, 0};
+  out[p] = leaf_coordinates(G, p, c) ? vals[p] * D[c[0] * ld + c[1]] : T(0);
+}
+
+// A(i, j) += v for every component: insertion into a dense result (Table 3: a dense level
+// supports insert, its position is i * ld + j), so the operands need no merge.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void generic_add_to_dense_kernel(const GTensor G, int64_t nvals,
+                                                                      const T* __restrict__ vals,
+                                                                      T* __restrict__ A, int64_t ld) {
+  const int64_t p = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+  if (p >= nvals) return;
+  int64_t c[4] = {0, 0, 0, 0};
+  if (leaf_coordinates(G, p, c)) unsafeAtomicAdd(A + (c[0] * ld + c[1]), vals[p]);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void generic_zero_rows_kernel(T* __restrict__ A, int64_t rows,
+                                                                   int64_t cols, int64_t ld) {
+  const int64_t q = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+  if (q < rows * cols) A[(q / cols) * ld + q % cols] = T(0);
+}
+
+template <typename T>
+static spt_status mul_dense_typed(const spt_tensor* B, const T* D, int64_t ld, T* out, hipStream_t s) {
+  if (B->nvals == 0) return SPT_OK;
+  hipLaunchKernelGGL(generic_mul_dense_kernel<T>,
+                     dim3(static_cast<unsigned>((B->nvals + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+                     make_gtensor(B), B->nvals, static_cast<const T*>(B->vals), D, ld, out);
+  SPT_CHECK_LAUNCH("mul_dense");
+  return SPT_OK;
+}
+
+spt_status mul_dense_dispatch(const spt_tensor* B, const void* D, int64_t ld, void* out, hipStream_t s) {
+  if (B->nvals >= (int64_t{1} << 40)) return fail(SPT_ERR_UNSUPPORTED, "mul_dense: tensor too large");
+  if (B->dtype == SPT_F64)
+    return mul_dense_typed<double>(B, static_cast<const double*>(D), ld, static_cast<double*>(out), s);
+  return mul_dense_typed<float>(B, static_cast<const float*>(D), ld, static_cast<float*>(out), s);
+}
+
+template <typename T>
+static spt_status add_to_dense_typed(const spt_tensor* B, const spt_tensor* C, T* A, int64_t ld,
+                                     hipStream_t s) {
+  const int64_t rows = mode_size(B, 0), cols = mode_size(B, 1);
+  if (rows * cols > 0) {
+    hipLaunchKernelGGL(generic_zero_rows_kernel<T>,
+                       dim3(static_cast<unsigned>((rows * cols + kBlock - 1) / kBlock)), dim3(kBlock), 0,
+                       s, A, rows, cols, ld);
+    SPT_CHECK_LAUNCH("add_to_dense zero");
+  }
+  for (const spt_tensor* X : {B, C}) {
+    if (X->nvals == 0) continue;
+    hipLaunchKernelGGL(generic_add_to_dense_kernel<T>,
+                       dim3(static_cast<unsigned>((X->nvals + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+                       make_gtensor(X), X->nvals, static_cast<const T*>(X->vals), A, ld);
+    SPT_CHECK_LAUNCH("add_to_dense");
+  }
+  return SPT_OK;
+}
+
+spt_status add_to_dense_dispatch(const spt_tensor* B, const spt_tensor* C, void* A, int64_t ld,
+                                 hipStream_t s) {
+  const int64_t rows = mode_size(B, 0), cols = mode_size(B, 1);
+  if (B->nvals >= (int64_t{1} << 40) || C->nvals >= (int64_t{1} << 40) ||
+      rows * cols >= (int64_t{1} << 40))
+    return fail(SPT_ERR_UNSUPPORTED, "add_to_dense: operands or result too large");
+  if (B->dtype == SPT_F64) return add_to_dense_typed<double>(B, C, static_cast<double*>(A), ld, s);
+  return add_to_dense_typed<float>(B, C, static_cast<float*>(A), ld, s);
+}
+
 // ---- any format -> COO, in storage order (count per chunk, scan, fill) ----
 
 constexpr int kCooChunk = kBlock;  // one leaf per lane
