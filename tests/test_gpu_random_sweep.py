@@ -1,6 +1,8 @@
 """GPU parity on seeded random shapes: every entry point against the oracle on inputs whose
 dimensions, entry counts, skew and dtype are drawn per seed (small enough for the oracle, ragged
 against every tile size by construction)."""
+import os
+
 import numpy as np
 import pytest
 
@@ -11,7 +13,9 @@ from gpu_util import (assert_close, gpu_add, gpu_coo_to_csr, gpu_innerprod, gpu_
 
 pytestmark = pytest.mark.gpu
 
-SEEDS = list(range(12))
+# SPT_SWEEP_SEEDS=a:b widens the sweep for a one-off soak of new kernels (default: 12 seeds)
+_lo, _hi = (int(t) for t in os.environ.get("SPT_SWEEP_SEEDS", "0:12").split(":"))
+SEEDS = list(range(_lo, _hi))
 
 
 def _draw_matrix(seed):
