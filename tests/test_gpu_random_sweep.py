@@ -16,13 +16,15 @@ pytestmark = pytest.mark.gpu
 # SPT_SWEEP_SEEDS=a:b widens the sweep for a one-off soak of new kernels (default: 12 seeds)
 _lo, _hi = (int(t) for t in os.environ.get("SPT_SWEEP_SEEDS", "0:12").split(":"))
 SEEDS = list(range(_lo, _hi))
+SCALE = int(os.environ.get("SPT_SWEEP_SCALE", "1"))   # multiplies the largest entry count drawn
 
 
 def _draw_matrix(seed):
     rng = np.random.default_rng(10_000 + seed)
     dtype = [np.float32, np.float64][seed % 2]
-    N, M = int(rng.integers(1, 6000)), int(rng.integers(1, 6000))
-    nnz = int(rng.integers(0, min(N * M, 60_000) + 1))
+    side = int(6000 * SCALE ** 0.5)
+    N, M = int(rng.integers(1, side)), int(rng.integers(1, side))
+    nnz = int(rng.integers(0, min(N * M, 60_000 * SCALE) + 1))
     r, c, v = wl.random_coo_entries(N, M, nnz, seed=20_000 + seed, dtype=dtype)
     if seed % 3 == 0 and len(r) > 10:                       # a few heavy rows
         heavy = rng.integers(0, N, 3)
@@ -56,7 +58,7 @@ def test_matrix_kernels(seed):
     Cm = rng.uniform(-1, 1, (M, J)).astype(dtype)
     A, Amag = oracle.spdm(coo, Cm)
     assert_close(gpu_spdm(coo, Cm), A, Amag, dtype, f"seed {seed} spdm J={J}")
-    r2, c2, v2 = wl.random_coo_entries(N, M, int(rng.integers(0, min(N * M, 40_000) + 1)),
+    r2, c2, v2 = wl.random_coo_entries(N, M, int(rng.integers(0, min(N * M, 40_000 * SCALE) + 1)),
                                        seed=30_000 + seed, dtype=dtype)
     other = wl.coo_spec(N, M, r2, c2, v2)
     (ri, ci), rv, rm = oracle.add(coo, other)
@@ -92,9 +94,9 @@ def test_matrix_kernels(seed):
 def test_tensor_kernels(seed):
     rng = np.random.default_rng(40_000 + seed)
     dtype = [np.float64, np.float32][seed % 2]
-    dims = tuple(int(d) for d in rng.integers(1, 120, 3))
+    dims = tuple(int(d) for d in rng.integers(1, int(120 * SCALE ** (1 / 3)), 3))
     cells = dims[0] * dims[1] * dims[2]
-    nnz = int(rng.integers(0, min(cells, 50_000) + 1))
+    nnz = int(rng.integers(0, min(cells, 50_000 * SCALE) + 1))
     skew = [None, 1.2, 2.0][seed % 3]
     ci, cj, ck, v = wl.random_coo3_entries(dims, nnz, 50_000 + seed, dtype=dtype, dist="u11", skew=skew)
     coo = wl.coo3_spec(dims, ci, cj, ck, v)
@@ -118,7 +120,7 @@ def test_tensor_kernels(seed):
     assert np.array_equal(qi, mi) and np.array_equal(qj, mj)
     assert_close(qv, mv, mm, dtype, f"seed {seed} ttm coo K={K}")
     assert_close(gpu_ttm(csf, Ck, is_csf=True)[2], mv, mm, dtype, f"seed {seed} ttm csf K={K}")
-    oi, oj, ok, ov = wl.random_coo3_entries(dims, int(rng.integers(0, min(cells, 30_000) + 1)),
+    oi, oj, ok, ov = wl.random_coo3_entries(dims, int(rng.integers(0, min(cells, 30_000 * SCALE) + 1)),
                                             60_000 + seed, dtype=dtype, dist="u11")
     other = wl.coo3_spec(dims, oi, oj, ok, ov)
     a, m = oracle.innerprod(coo, other)
