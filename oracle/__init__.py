@@ -29,7 +29,7 @@ def build(force: bool = True) -> str:
 class OrcLevel(C.Structure):
     _fields_ = [("kind", C.c_int32), ("mode", C.c_int32), ("N", C.c_int64),
                 ("M", C.c_int64), ("pos", C.c_void_p), ("crd", C.c_void_p),
-                ("offset", C.c_void_p)]
+                ("offset", C.c_void_p), ("crd_stride", C.c_int64)]
 
 
 class OrcTensor(C.Structure):
@@ -134,6 +134,7 @@ class OTensor:
         for k, lv in enumerate(spec.levels):
             o = t.lvl[k]
             o.kind, o.mode, o.N, o.M = lv.kind, lv.mode, lv.N, lv.M
+            o.crd_stride = getattr(lv, "crd_stride", 1)
             for name in ("pos", "crd", "offset"):
                 a = getattr(lv, name)
                 if a is not None:

@@ -65,21 +65,28 @@ static void pos_bounds(const orc_level* L, int64_t p_parent, int64_t* lo,
  * Singleton follows Table 2 except that a negative coordinate is read as
  * "unlabeled node" (ELL padding stored as -1), the same test the hashed level
  * applies to its empty buckets. */
+/* Coordinate stored for position p: crd[p] for the struct-of-arrays layout; crd[p * stride]
+ * for the array-of-structs variant of Section 5.2, where all levels of a component share one
+ * interleaved array and each level starts at its own offset in it. */
+static int64_t stored_crd(const orc_level* L, int64_t p) {
+  return L->crd[L->crd_stride > 1 ? p * L->crd_stride : p];
+}
+
 static int pos_access(const orc_level* L, int64_t p, int64_t i_parent,
                       int64_t i_grand, int64_t* i_out) {
   switch (L->kind) {
     case ORC_COMPRESSED:
-      *i_out = L->crd[p];
+      *i_out = stored_crd(L, p);
       return 1;
     case ORC_SINGLETON:
-      *i_out = L->crd[p];
-      return L->crd[p] >= 0;
+      *i_out = stored_crd(L, p);
+      return *i_out >= 0;
     case ORC_OFFSET: /* i_{k-1} + offset[i_{k-2}] */
       *i_out = i_parent + L->offset[i_grand];
       return 1;
     default: /* hashed */
-      *i_out = L->crd[p];
-      return L->crd[p] != -1;
+      *i_out = stored_crd(L, p);
+      return *i_out != -1;
   }
 }
 

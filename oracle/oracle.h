@@ -27,6 +27,9 @@ typedef struct {
   const int32_t* pos;
   const int32_t* crd;
   const int32_t* offset;
+  int64_t crd_stride; /* elements between the coordinates of consecutive positions; 0 or 1 =
+                         contiguous; > 1 = interleaved (array-of-structs COO, Section 5.2),
+                         honoured by the level walk (orc_enumerate and what builds on it) */
 } orc_level;
 
 typedef struct {

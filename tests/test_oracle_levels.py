@@ -235,3 +235,30 @@ def test_dense_compressed_compressed_tensor_walk():
     co, w = oracle.to_coo(spec)
     assert np.array_equal(co[0], ci) and np.array_equal(co[1], cj) and np.array_equal(co[2], ck)
     assert np.array_equal(w, v)
+
+
+def test_aos_coo_walks_like_soa_coo():
+    """Array-of-structs COO (Section 5.2): one interleaved coordinate array, each level reading it
+    with a stride. The walk, SpMV and the 3rd-order kernels see the same tensor as through SoA."""
+    import scipy.sparse as sp
+    N, M = 23, 31
+    r, c, v = wl.random_coo_entries(N, M, 200, seed=301, dtype=np.float64)
+    aos = wl.coo_aos_spec((N, M), (r, c), v)
+    inter = aos.levels[0].crd
+    assert np.array_equal(inter[0::2], r) and np.array_equal(inter[1::2], c)      # (i, j) (i, j) ...
+    assert np.shares_memory(aos.levels[0].crd, aos.levels[1].crd)                 # one array, two views
+    assert aos.levels[1].crd[0] == c[0] and aos.levels[0].crd_stride == 2
+    coords, vals = oracle.to_coo(aos)
+    assert np.array_equal(coords[0], r) and np.array_equal(coords[1], c) and np.array_equal(vals, v)
+    x = wl.dense_vector(M, 302)
+    y, mag = oracle.spmv(aos, x)
+    np.testing.assert_allclose(y, sp.coo_matrix((v, (r, c)), shape=(N, M)).tocsr() @ x, rtol=0,
+                               atol=1e-13 * max(mag.max(), 1))
+    dims = (7, 6, 5)
+    ci, cj, ck, w = wl.random_coo3_entries(dims, 90, 303, dtype=np.float64)
+    aos3 = wl.coo_aos_spec(dims, (ci, cj, ck), w)
+    assert np.array_equal(aos3.levels[2].crd[0::3], ck)
+    cvec = wl.dense_vector(dims[2], 304)
+    a = oracle.ttv(aos3, cvec)
+    b = oracle.ttv(wl.coo3_spec(dims, ci, cj, ck, w), cvec)
+    assert all(np.array_equal(p, q) for p, q in zip(a, b))

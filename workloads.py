@@ -35,6 +35,7 @@ class LevelSpec:
     ordered: bool = True
     unique: bool = True
     max_children: int = 0     # optional declared bound on children per parent (0 = unknown)
+    crd_stride: int = 1       # elements between consecutive positions in crd (> 1: interleaved)
 
 
 @dataclass
@@ -70,6 +71,21 @@ def coo_spec(N, M, row, col, vals, ordered=True, name="coo") -> TensorSpec:
                   ordered=ordered, unique=False),
         LevelSpec(SINGLETON, 1, M, crd=_i32(col), ordered=ordered),
     ], np.ascontiguousarray(vals), name)
+
+
+def coo_aos_spec(dims, coords, vals, ordered=True, name="coo-aos") -> TensorSpec:
+    """Array-of-structs COO (Section 5.2): one array holds the coordinates of each component
+    contiguously, (i, j[, k]) (i, j[, k]) ...; level m reads it from element m with stride
+    order. The level arrays below are views into that one array."""
+    order = len(dims)
+    inter = np.ascontiguousarray(np.stack([_i32(c) for c in coords], axis=1).reshape(-1))
+    nnz = len(vals)
+    levels = [LevelSpec(COMPRESSED, 0, dims[0], M=1, pos=_i32([0, nnz]), crd=inter[0:], ordered=ordered,
+                        unique=False, crd_stride=order)]
+    for m in range(1, order):
+        levels.append(LevelSpec(SINGLETON, m, dims[m], crd=inter[m:], ordered=ordered,
+                                unique=m == order - 1, crd_stride=order))
+    return TensorSpec(tuple(dims), levels, np.ascontiguousarray(vals), name)
 
 
 def csr_spec(N, M, pos, crd, vals, ordered=True, unique=True, name="csr",
