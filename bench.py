@@ -367,6 +367,12 @@ def build_items(args):
             items.append(Item(f"n5_spmv_{nm}", lambda Ag=Ag, wg5=wg5: spt.spt_spmv(Ag, xg, yg, wg5), 2 * nnz3,
                               8 * nnz3 + 12 * N3,
                               "one atomic per stored value" if nm == "csc" else "CSR kernel over the stored rows"))
+        # array-of-structs COO of the same matrix (entries in row order): pairs split, then COO kernels
+        Aa = spt.DeviceTensor(wl.coo_aos_spec((N3, N3), (rr, cc), vv))
+        wa = Aa.workspace(spt.SPT_OP_SPMV)
+        keep.extend([Aa, wa])
+        items.append(Item("n5_spmv_coo_aos", lambda: spt.spt_spmv(Aa, xg, yg, wa), 2 * nnz3,
+                          12 * nnz3 + 16 * nnz3 + 8 * N3, "pairs split into the workspace (8 B read + 8 B written per entry), then sorted-COO SpMV"))
         Ae = spt.DeviceTensor(c3["ell"])
         cells = len(c3["ell"].vals)
         g0, g1 = (torch.empty(cells, dtype=torch.int32, device=dev) for _ in range(2))

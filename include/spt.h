@@ -104,6 +104,13 @@ typedef enum {
  *          SpMV streams the entries of 256 rows at a time through LDS and lets
  *          one lane add up each row, instead of running the entry-balanced
  *          kernel. A bound that the data violates costs time, not correctness.
+ *   crd_stride  elements of crd between the coordinates of consecutive positions: 0 or 1 =
+ *          contiguous (struct of arrays). A larger stride describes the array-of-structs
+ *          variant of Section 5.2, where one interleaved array holds the coordinates of each
+ *          component side by side, (i, j) (i, j) ..., and level m points at element m of it
+ *          with stride = order. Such tensors are "any composition" (spt_spmv, spt_to_coo,
+ *          spt_mul_dense, spt_add_to_dense); spt_spmv on an array-of-structs COO matrix
+ *          splits the coordinates into the workspace first and then runs the COO kernels.
  */
 typedef struct {
   int32_t kind;
@@ -115,6 +122,7 @@ typedef struct {
   const int32_t* pos;
   const int32_t* crd;
   const int32_t* offset;
+  int64_t crd_stride;
 } spt_level;
 
 /*

@@ -33,7 +33,8 @@ SYMBOLS = ["spt_spmv", "spt_coo_to_csr", "spt_ttv", "spt_mttkrp", "spt_workspace
 class SptLevel(C.Structure):
     _fields_ = [("kind", C.c_int32), ("mode", C.c_int32), ("flags", C.c_int32),
                 ("max_children", C.c_int32), ("N", C.c_int64), ("M", C.c_int64),
-                ("pos", C.c_void_p), ("crd", C.c_void_p), ("offset", C.c_void_p)]
+                ("pos", C.c_void_p), ("crd", C.c_void_p), ("offset", C.c_void_p),
+                ("crd_stride", C.c_int64)]
 
 
 class SptTensor(C.Structure):
@@ -298,9 +299,22 @@ class DeviceTensor:
             o.kind, o.mode, o.N, o.M = int(lv.kind), int(lv.mode), int(lv.N), int(lv.M)
             o.flags = (SPT_ORDERED if lv.ordered else 0) | (SPT_UNIQUE if lv.unique else 0)
             o.max_children = int(getattr(lv, "max_children", 0))
+            o.crd_stride = int(getattr(lv, "crd_stride", 1))
             for name in ("pos", "crd", "offset"):
                 a = getattr(lv, name)
                 if a is None:
+                    continue
+                if name == "crd" and o.crd_stride > 1 and a.base is not None:
+                    # interleaved coordinates: the levels are views into one array, which is
+                    # uploaded once; each level points at its own first element of it
+                    base = a.base
+                    if id(base) not in shared:
+                        d = self._upload(np.ascontiguousarray(base, dtype=np.int32).reshape(-1), device, misalign)
+                        shared[id(base)] = d
+                        self.keep.append(d)
+                        setattr(self, "crd_interleaved", d)
+                    off = a.__array_interface__["data"][0] - base.__array_interface__["data"][0]
+                    o.crd = shared[id(base)].data_ptr() + off
                     continue
                 if id(a) not in shared:   # DIA shares one offset array between two levels
                     d = self._upload(np.ascontiguousarray(a, dtype=np.int32), device, misalign)

@@ -24,6 +24,9 @@ spt_status spmv_dispatch(Format f, const spt_tensor* A, const void* x, void* y, 
                          size_t ws_bytes, hipStream_t s);
 size_t seg_spmv_workspace(int64_t nnz);
 size_t dcsr_spmv_workspace(const spt_tensor* A);
+spt_status aos_coo_spmv_dispatch(const spt_tensor* A, const void* x, void* y, void* ws,
+                                 size_t ws_bytes, hipStream_t s);
+size_t aos_coo_spmv_workspace(const spt_tensor* A);
 spt_status spmv_sparse_x_dispatch(const spt_tensor* A, const spt_tensor* X, void* y, void* ws,
                                   size_t ws_bytes, hipStream_t s);
 size_t coo_unordered_workspace(int dtype, int64_t nnz, int64_t nrows);
@@ -99,8 +102,8 @@ static bool level_ok(const spt_tensor* T, int k) {
     fail(SPT_ERR_INVALID_ARG, "level %d: a hashed level cannot be ordered (Table 1)", k);
     return false;
   }
-  if (L.N < 0 || L.M < 0) {
-    fail(SPT_ERR_INVALID_ARG, "level %d: negative size", k);
+  if (L.N < 0 || L.M < 0 || L.crd_stride < 0) {
+    fail(SPT_ERR_INVALID_ARG, "level %d: negative size or stride", k);
     return false;
   }
   if (L.mode < -1 || L.mode >= T->order) {
@@ -154,6 +157,14 @@ Format recognize(const spt_tensor* T) {
   for (int k = 0; k < T->nlevels; ++k)
     if (!level_ok(T, k)) return Format::Invalid;
   const spt_level* L = T->level;
+  for (int k = 0; k < T->nlevels; ++k)
+    if (L[k].crd_stride > 1) {  // interleaved coordinates: none of the format kernels reads them
+      fail(SPT_ERR_UNSUPPORTED,
+           "level %d has interleaved coordinates (crd_stride %lld): supported by spt_spmv, spt_to_coo, "
+           "spt_mul_dense and spt_add_to_dense; spt_to_coo converts to contiguous coordinates",
+           k, (long long)L[k].crd_stride);
+      return Format::Unsupported;
+    }
   auto modes = [&](int a, int b, int c, int d) {
     const int want[4] = {a, b, c, d};
     for (int k = 0; k < T->nlevels; ++k)
@@ -280,6 +291,14 @@ static bool ws_misaligned(const void* ws) {
   return false;
 }
 
+// An array-of-structs COO matrix: both levels read one array of (row, col) pairs.
+static bool is_aos_coo_matrix(const spt_tensor* T) {
+  const spt_level* L = T->level;
+  return T->order == 2 && T->nlevels == 2 && L[0].kind == SPT_COMPRESSED && L[0].M == 1 &&
+         L[1].kind == SPT_SINGLETON && L[0].mode == 0 && L[1].mode == 1 && L[0].crd_stride == 2 &&
+         L[1].crd_stride == 2 && L[0].crd && L[1].crd == L[0].crd + 1 && T->nvals < INT32_MAX;
+}
+
 static spt_status status_of(Format f) {
   return f == Format::Invalid ? SPT_ERR_INVALID_ARG : SPT_ERR_UNSUPPORTED;
 }
@@ -299,6 +318,11 @@ spt_status spt_spmv(const spt_tensor* A, const void* x, void* y, void* ws, size_
   if (ws_misaligned(ws)) return SPT_ERR_INVALID_ARG;
   Format f = recognize(A);
   if (f == Format::Invalid) return status_of(f);
+  if (f == Format::Unsupported && is_aos_coo_matrix(A)) {
+    clear_error();
+    if (!x || !y) return fail(SPT_ERR_INVALID_ARG, "spmv: x or y is null");
+    return aos_coo_spmv_dispatch(A, x, y, ws, ws_bytes, static_cast<hipStream_t>(stream));
+  }
   if (f == Format::Unsupported || (f == Format::BCSR && !bcsr_fast_ok(A))) {
     // no kernel of its own: per-value reading of the level functions
     if (A->order != 2 && A->order != 4)
@@ -633,6 +657,10 @@ size_t spt_workspace_bytes(int32_t op, const spt_tensor* T, int32_t J) {
   Format f = recognize(T);
   if (f == Format::Invalid) return 0;
   if (f == Format::Unsupported || op == SPT_OP_TO_COO) {  // operations defined for any composition
+    if (op == SPT_OP_SPMV && f == Format::Unsupported && is_aos_coo_matrix(T)) {
+      clear_error();
+      return aos_coo_spmv_workspace(T) + 256;
+    }
     if (op == SPT_OP_SPMV && f == Format::Unsupported && (T->order == 2 || T->order == 4) &&
         generic_ok(T))
       return 256;

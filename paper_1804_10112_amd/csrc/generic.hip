@@ -22,6 +22,7 @@ struct GLevel {
   int32_t kind, mode;
   int64_t N, M;
   const int32_t *pos, *crd, *offset;
+  int64_t stride;  // elements between consecutive positions in crd (1 unless interleaved)
 };
 struct GTensor {
   int32_t nlevels, order;
@@ -34,7 +35,7 @@ static GTensor make_gtensor(const spt_tensor* T) {
   G.order = T->order;
   for (int k = 0; k < 4; ++k) {
     const spt_level& S = T->level[k < T->nlevels ? k : 0];
-    G.L[k] = GLevel{S.kind, S.mode, S.N, S.M, S.pos, S.crd, S.offset};
+    G.L[k] = GLevel{S.kind, S.mode, S.N, S.M, S.pos, S.crd, S.offset, S.crd_stride > 1 ? S.crd_stride : 1};
   }
   return G;
 }
@@ -89,7 +90,7 @@ __device__ __forceinline__ bool leaf_coordinates(const GTensor& G, int64_t p, in
         }
         case SPT_OFFSET: c = ck[k >= 1 ? k - 1 : 0] + L.offset[ck[k >= 2 ? k - 2 : 0]]; break;
         default:  // compressed, singleton, hashed: the stored coordinate
-          c = L.crd[pk[k]];
+          c = L.crd[pk[k] * L.stride];
           if (c < 0) return false;
       }
       ck[k] = c;

@@ -708,6 +708,55 @@ spt_status csr_rows_reduce(int dtype, int64_t nnz, int64_t nrows, const int32_t*
                                  s);
 }
 
+// ---- array-of-structs COO (Section 5.2): (row, col) pairs in one array ----
+
+__global__ __launch_bounds__(kBlock) void split_pairs_kernel(int64_t n, const int32_t* __restrict__ rc,
+                                                             int32_t* __restrict__ row,
+                                                             int32_t* __restrict__ col) {
+  const int64_t p = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+  if (p >= n) return;
+  row[p] = rc[2 * p];  // the two loads of a lane share 8 bytes, a wave reads 512 contiguous bytes
+  col[p] = rc[2 * p + 1];
+}
+
+static size_t coo_matrix_spmv_workspace(const spt_tensor* A) {
+  return (A->level[0].flags & SPT_ORDERED) ? seg_spmv_workspace(A->nvals)
+                                           : coo_unordered_workspace(A->dtype, A->nvals, A->level[0].N);
+}
+
+size_t aos_coo_spmv_workspace(const spt_tensor* A) {
+  return 2 * align_up(static_cast<size_t>(A->nvals) * 4, 256) + coo_matrix_spmv_workspace(A);
+}
+
+spt_status spmv_dispatch(Format f, const spt_tensor* A, const void* x, void* y, void* ws,
+                         size_t ws_bytes, hipStream_t s);
+
+// The pairs are split into a row and a column array in the workspace (8 bytes read and 8
+// written per entry), then the COO kernels run on those.
+spt_status aos_coo_spmv_dispatch(const spt_tensor* A, const void* x, void* y, void* ws,
+                                 size_t ws_bytes, hipStream_t s) {
+  const int64_t nnz = A->nvals;
+  const size_t need = aos_coo_spmv_workspace(A);
+  if (nnz > 0 && (!ws || ws_bytes < need))
+    return fail(SPT_ERR_WORKSPACE, "spmv: workspace of %zu bytes needed, %zu given", need, ws_bytes);
+  spt_tensor S = *A;
+  S.level[0].crd_stride = S.level[1].crd_stride = 1;
+  size_t used = 0;
+  if (nnz > 0) {
+    Workspace W(ws, ws_bytes);
+    int32_t* row = W.take<int32_t>(nnz);
+    int32_t* col = W.take<int32_t>(nnz);
+    used = W.used;
+    hipLaunchKernelGGL(split_pairs_kernel, dim3(static_cast<unsigned>((nnz + kBlock - 1) / kBlock)),
+                       dim3(kBlock), 0, s, nnz, A->level[0].crd, row, col);
+    SPT_CHECK_LAUNCH("split pairs");
+    S.level[0].crd = row;
+    S.level[1].crd = col;
+  }
+  return spmv_dispatch(Format::COO2, &S, x, y, ws ? static_cast<char*>(ws) + used : nullptr,
+                       ws_bytes > used ? ws_bytes - used : 0, s);
+}
+
 spt_status spmv_dispatch(Format f, const spt_tensor* A, const void* x, void* y, void* ws,
                          size_t ws_bytes, hipStream_t s) {
   if (A->dtype == SPT_F64)

@@ -42,9 +42,23 @@ def test_library_exports_every_declared_symbol():
     assert "gfx950" in spt.spt_version()
 
 
-def test_struct_layout_matches_header():
-    assert C.sizeof(B.SptLevel) == 4 * 4 + 2 * 8 + 3 * 8
+def test_struct_layout_matches_header(tmp_path):
+    assert C.sizeof(B.SptLevel) == 4 * 4 + 2 * 8 + 3 * 8 + 8
     assert C.sizeof(B.SptTensor) == 16 + 4 * C.sizeof(B.SptLevel) + 16
+    # the same numbers from the header itself, through the C compiler
+    import os
+    import subprocess
+    src = tmp_path / "layout.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "spt.h"\n'
+                   'int main(void) { printf("%zu %zu %zu %zu %zu %zu\\n", sizeof(spt_level), sizeof(spt_tensor), '
+                   'offsetof(spt_level, crd), offsetof(spt_level, crd_stride), offsetof(spt_tensor, level), '
+                   'offsetof(spt_tensor, nvals)); return 0; }\n')
+    exe = tmp_path / "layout"
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    subprocess.run(["gcc", "-std=c99", "-I", inc, str(src), "-o", str(exe)], check=True)
+    got = [int(t) for t in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert got == [C.sizeof(B.SptLevel), C.sizeof(B.SptTensor), B.SptLevel.crd.offset,
+                   B.SptLevel.crd_stride.offset, B.SptTensor.level.offset, B.SptTensor.nvals.offset]
 
 
 def test_recognised_compositions_have_workspace_sizes():
