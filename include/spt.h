@@ -136,6 +136,9 @@ typedef struct {
  *   ELL   (D slots W, D rows, S cols)             vals[W*N], cell (k,i) at k*N+i
  *   COO3  (C~U, S~U, S)                           vals[nnz]
  *   CSF3  (C, C, C)                               vals[nnz]
+ *   CSC   (D cols, C rows), the levels in the order (mode 1, mode 0); vals[nnz] in column
+ *         order. spt_spmv only (columns expanded from pos, then binned by row like an
+ *         unordered COO), otherwise any composition
  *   DCSR  (C rows with pos=[0,stored rows], C cols) vals[nnz]; spt_spmv only (a fast path
  *         when the row level is flagged unique), otherwise any composition
  *   BCSR  (D block rows, C block cols, D b1, D b2) vals[nblocks*b1*b2], blocks row-major;
@@ -170,7 +173,7 @@ typedef struct {
  * DCSR (compressed rows flagged SPT_UNIQUE, compressed cols) runs the CSR kernels over the
  * stored rows and places each sum at its row coordinate (deterministic; workspace from
  * spt_workspace_bytes(SPT_OP_SPMV, ...)). Any other composition of levels that stores a
- * matrix (CSC, dense, hashed rows or columns, DCSR with repeated row coordinates, ...) is
+ * matrix (dense, hashed rows or columns, DCSR with repeated row coordinates, ...) is
  * evaluated by reading the level functions of Table 2 per stored value, again with
  * floating-point atomics; it needs no workspace.
  * A blocked matrix (order 4, Section 3.2): x has (block columns * b2) entries, y has

@@ -231,6 +231,16 @@ __global__ __launch_bounds__(kBlock) void add_zero_i32_kernel(int32_t* __restric
 
 // ---- host ------------------------------------------------------------------
 
+// parent[p] = index of the pos segment that holds position p (the row of a CSR entry, the
+// column of a CSC entry); used by other translation units as well
+spt_status launch_expand_parents(int n, int nparents, const int32_t* pos, int32_t* out, hipStream_t s) {
+  if (n <= 0) return SPT_OK;
+  hipLaunchKernelGGL(expand_rows_kernel, dim3((n + kExpChunk - 1) / kExpChunk), dim3(kBlock), 0, s, n,
+                     nparents, pos, out);
+  SPT_CHECK_LAUNCH("expand parents");
+  return SPT_OK;
+}
+
 static int64_t add_tiles(int64_t nb, int64_t nc) { return (nb + nc + kAddTile - 1) / kAddTile; }
 
 // fb / fc: formats of the operands (matrices may mix CSR and COO; the result takes B's format)

@@ -24,6 +24,7 @@ spt_status spmv_dispatch(Format f, const spt_tensor* A, const void* x, void* y, 
                          size_t ws_bytes, hipStream_t s);
 size_t seg_spmv_workspace(int64_t nnz);
 size_t dcsr_spmv_workspace(const spt_tensor* A);
+size_t csc_spmv_workspace(const spt_tensor* A);
 spt_status aos_coo_spmv_dispatch(const spt_tensor* A, const void* x, void* y, void* ws,
                                  size_t ws_bytes, hipStream_t s);
 size_t aos_coo_spmv_workspace(const spt_tensor* A);
@@ -179,6 +180,10 @@ Format recognize(const spt_tensor* T) {
       }
       return Format::CSR;
     }
+    // CSC: the levels store the dimensions in the order (column, row); SpMV only
+    if (is(L[0], SPT_DENSE) && is(L[1], SPT_COMPRESSED) && modes(1, 0, 0, 0) && L[1].M == L[0].N &&
+        L[1].pos)
+      return Format::CSC;
     // DCSR with unique rows has a fast path for SpMV; every other operation and DCSR with
     // repeated row coordinates take it as "any composition"
     if (is(L[0], SPT_COMPRESSED) && is(L[1], SPT_COMPRESSED) && modes(0, 1, 0, 0) && L[0].M == 1 &&
@@ -679,6 +684,8 @@ size_t spt_workspace_bytes(int32_t op, const spt_tensor* T, int32_t J) {
         n = bcsr_workspace(T);
       else if (f == Format::DCSR)
         n = dcsr_spmv_workspace(T);
+      else if (f == Format::CSC)
+        n = csc_spmv_workspace(T);
       break;
     case SPT_OP_COO_TO_CSR:
       n = f == Format::COO2 ? coo_to_csr_workspace(T) : 0;

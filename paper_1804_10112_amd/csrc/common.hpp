@@ -15,7 +15,7 @@ constexpr int kBlock = 256;  // 4 waves per workgroup everywhere
 
 // ---- host side -----------------------------------------------------------
 
-enum class Format { Invalid, Unsupported, CSR, COO2, DIA, ELL, COO3, CSF3, BCSR, DCSR };
+enum class Format { Invalid, Unsupported, CSR, COO2, DIA, ELL, COO3, CSF3, BCSR, DCSR, CSC };
 
 // Validates the descriptor (Table 1 legality, pointers, sizes) and names the
 // level composition. On Invalid/Unsupported the thread-local error is set.

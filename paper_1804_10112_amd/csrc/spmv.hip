@@ -577,6 +577,13 @@ __global__ __launch_bounds__(kBlock) void scatter_rows_kernel(int n, const int32
   if (r < n) y[row[r]] = t[r];
 }
 
+spt_status launch_expand_parents(int n, int nparents, const int32_t* pos, int32_t* out, hipStream_t s);
+
+size_t csc_spmv_workspace(const spt_tensor* A) {
+  return align_up(static_cast<size_t>(A->nvals) * 4, 256) +
+         coo_unordered_workspace(A->dtype, A->nvals, A->level[1].N);
+}
+
 size_t dcsr_spmv_workspace(const spt_tensor* A) {
   return align_up(static_cast<size_t>(A->level[1].M) * 8, 256) + seg_spmv_workspace(A->nvals);
 }
@@ -621,6 +628,32 @@ static spt_status spmv_typed(Format f, const spt_tensor* A, const T* x, T* y, vo
                                                A->level[1].crd, vals, DenseX<T>{x}, y, s);
       return launch_seg<T, true>(A->nvals, A->level[0].N, A->level[1].pos, A->level[1].crd, vals,
                                  x, y, ws, ws_bytes, s);
+    }
+    case Format::CSC: {
+      // (dense columns, compressed rows): the entries lie in column order, which makes the
+      // matrix a COO whose row coordinates are unordered and whose column coordinates are
+      // implicit in pos. The columns are written out once, then the entries are binned by row
+      // like any unordered COO; x is read in ascending order on the way.
+      const int64_t nnz = A->nvals, N = A->level[1].N, M = A->level[0].N;
+      if (nnz >= INT32_MAX || M + 1 >= INT32_MAX)
+        return fail(SPT_ERR_UNSUPPORTED, "spmv: more than 2^31 entries or columns");
+      if (nnz == 0) return launch_fill<T>(y, N, T(0), s);
+      if (!ws || ws_bytes < csc_spmv_workspace(A))
+        return fail(SPT_ERR_WORKSPACE, "spmv: workspace of %zu bytes needed, %zu given",
+                    csc_spmv_workspace(A), ws_bytes);
+      Workspace W(ws, ws_bytes);
+      int32_t* cols = W.take<int32_t>(nnz);
+      spt_status st = launch_expand_parents((int)nnz, (int)M, A->level[1].pos, cols, s);
+      if (st != SPT_OK) return st;
+      if (nnz >= kBinnedMinEntries)
+        return coo_binned_spmv<T>(nnz, N, A->level[1].crd, cols, vals, x, y,
+                                  static_cast<char*>(ws) + W.used, ws_bytes - W.used, s);
+      st = launch_fill<T>(y, N, T(0), s);
+      if (st != SPT_OK) return st;
+      hipLaunchKernelGGL(coo_atomic_spmv_kernel<T>, dim3((unsigned)((nnz + kBlock - 1) / kBlock)),
+                         dim3(kBlock), 0, s, (int)nnz, A->level[1].crd, cols, vals, x, y);
+      SPT_CHECK_LAUNCH("coo_atomic_spmv");
+      return SPT_OK;
     }
     case Format::COO2: {
       const int64_t nnz = A->nvals, N = A->level[0].N;

@@ -183,3 +183,23 @@ def test_dcsr_fast_path_and_its_fallbacks(dtype):
     e = np.zeros(0, np.int32)
     empty = wl.dcsr_from_sorted_coo(N, M, e, e, np.zeros(0, dtype))
     assert not gpu_spmv(empty, x).any()
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_csc_spmv_binned_path(dtype):
+    """CSC above the size where entries are binned by row: columns expanded from pos, x read in
+    column order. A few very long columns, empty columns, misaligned arrays."""
+    N, M = 9000, 7000
+    r, c, v = wl.random_coo_entries(N, M, 250_000, seed=1800, dtype=dtype)
+    rng = np.random.default_rng(1801)
+    c[rng.random(len(c)) < 0.3] = 17                          # one column holds ~30 % of the entries
+    c[(c % 5) == 1] += 1                                      # every fifth column empty
+    c = np.minimum(c, M - 1)
+    key, first = np.unique(r.astype(np.int64) * M + c, return_index=True)
+    r, c, v = r[first], c[first], v[first]
+    x = wl.dense_vector(M, 1802, dtype)
+    ref, mag = oracle.spmv(wl.coo_spec(N, M, r, c, v), x)
+    csc = wl.csc_from_coo(N, M, r, c, v)
+    assert len(v) > 1 << 15
+    assert_close(gpu_spmv(csc, x), ref, mag, dtype, "csc binned")
+    assert_close(gpu_spmv(csc, x, misalign=True), ref, mag, dtype, "csc binned misaligned")
