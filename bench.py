@@ -436,7 +436,8 @@ def oracle_free_coo(csr_spec):
 def measure_ceilings():
     """Achievable ceilings of this machine for the two access patterns that bound the path:
     a pure streaming read (16 / 8 / 4 bytes per lane) and random gathers from tables of the
-    sizes of config 3's x (1M fp32) and config 4's x (4M fp64). Library probe kernels."""
+    sizes of config 3's x (1M fp32) and config 4's x (4M fp64) with the library's probe kernels,
+    and the runtime's device-to-device copy."""
     import torch
     import paper_1804_10112_amd as spt
     dev = "cuda:0"
@@ -469,7 +470,11 @@ def measure_ceilings():
         o = torch.empty(n, dtype=tdt, device=dev)
         t = timed(lambda: spt.spt_probe_gather(idx, n, table, sdt, o))
         out[name + "_Gelem_s"] = round(n / t / 1e9, 1)
-    del src
+    # the runtime's own device-to-device copy: the yardstick for a radix pass (read + write)
+    dst = torch.empty_like(src)
+    t = timed(lambda: dst.copy_(src))
+    out["copy_read_plus_write_GBs"] = round(2 * nbytes / t / 1e9, 1)
+    del src, dst
     return out
 
 
