@@ -172,7 +172,10 @@ typedef struct {
  * the entries are accumulated with floating-point atomics (any order).
  * DCSR (compressed rows flagged SPT_UNIQUE, compressed cols) runs the CSR kernels over the
  * stored rows and places each sum at its row coordinate (deterministic; workspace from
- * spt_workspace_bytes(SPT_OP_SPMV, ...)). Any other composition of levels that stores a
+ * spt_workspace_bytes(SPT_OP_SPMV, ...)). CSC has its columns written out of pos into the
+ * workspace and its entries binned by row like an unordered COO; an array-of-structs COO
+ * matrix (crd_stride = 2 on both levels) has its pairs split into the workspace and then runs
+ * as COO. Both need the workspace the query returns. Any other composition of levels that stores a
  * matrix (dense, hashed rows or columns, DCSR with repeated row coordinates, ...) is
  * evaluated by reading the level functions of Table 2 per stored value, again with
  * floating-point atomics; it needs no workspace.
