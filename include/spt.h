@@ -338,7 +338,7 @@ spt_status spt_to_coo(const spt_tensor* T, int32_t* out_crd0, int32_t* out_crd1,
  * receives the entry count.
  *   B COO matrix: out_crd0 (rows), out_crd1 (cols), out_vals; out_pos, out_crd2 ignored.
  *   B COO3:       out_crd0, out_crd1, out_crd2, out_vals; out_pos ignored.
- *   B CSR:        out_pos[N+1] (Table 3: counts, then running sum), out_crd1 (cols), out_vals;
+ *   B CSR:        out_pos[N+1] (what Table 3's append_edges + append_finalize produce), out_crd1 (cols), out_vals;
  *                 out_crd0, out_crd2 ignored.
  * Workspace: spt_add_workspace_bytes(B, C), about 4 bytes per stored entry of both operands
  * (CSR operands: up to 12).

@@ -20,6 +20,7 @@
 // from the ordered result rows.
 #include "common.hpp"
 #include "merge.hpp"
+#include "rows.hpp"
 #include "scan.hpp"
 
 namespace spt {
@@ -211,19 +212,6 @@ __global__ __launch_bounds__(kBlock) void expand_rows_kernel(int nnz, int nrows,
   }
 }
 
-// Per-row counts of the ordered result rows, as Table 3's append_edges stores them:
-// cnt[r + 1] = number of entries of row r; the entry count is read from device memory.
-__global__ __launch_bounds__(kBlock) void result_row_count_kernel(const int32_t* __restrict__ row,
-                                                                  const int64_t* __restrict__ n_dev,
-                                                                  int32_t* __restrict__ cnt) {
-  const int n = static_cast<int>(*n_dev);
-  const int p = blockIdx.x * kBlock + threadIdx.x;
-  if (p >= n) return;
-  const int32_t r = row[p];
-  if (p == 0 || row[p - 1] != r) atomicSub(&cnt[r + 1], p);
-  if (p == n - 1 || row[p + 1] != r) atomicAdd(&cnt[r + 1], p + 1);
-}
-
 __global__ __launch_bounds__(kBlock) void add_zero_i32_kernel(int32_t* __restrict__ out, int64_t n) {
   const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
   if (i < n) out[i] = 0;
@@ -249,8 +237,7 @@ size_t add_workspace(Format fb, Format fc, const spt_tensor* B, const spt_tensor
   size_t n = 3 * align_up(static_cast<size_t>(nt + 1) * 4, 256) +
              align_up(static_cast<size_t>(nt) * kAddTile * 4, 256) + scan_workspace(nt) + 256;
   if (fb == Format::CSR)
-    n += align_up(static_cast<size_t>(nb) * 4, 256) + align_up(static_cast<size_t>(nb + nc) * 4, 256) +
-         scan_workspace(B->level[0].N + 1);
+    n += align_up(static_cast<size_t>(nb) * 4, 256) + align_up(static_cast<size_t>(nb + nc) * 4, 256);
   if (fc == Format::CSR) n += align_up(static_cast<size_t>(nc) * 4, 256);
   return n;
 }
@@ -338,14 +325,8 @@ static spt_status add_typed(Format fb, Format fc, const spt_tensor* B, const spt
                      offs, cb, static_cast<const T*>(B->vals), cc, static_cast<const T*>(C->vals), co,
                      out_vals);
   SPT_CHECK_LAUNCH("add fill");
-  if (fb == Format::CSR) {
-    const unsigned egrid = static_cast<unsigned>((static_cast<int64_t>(nb) + nc + kBlock - 1) / kBlock);
-    hipLaunchKernelGGL(result_row_count_kernel, dim3(egrid), dim3(kBlock), 0, s, co.a0, out_nnz,
-                       out_pos);
-    SPT_CHECK_LAUNCH("add row count");
-    int32_t* scan_tmp2 = reinterpret_cast<int32_t*>(W.take<char>(scan_workspace(N + 1)));
-    return device_scan_i32<true>(out_pos, out_pos, N + 1, scan_tmp2, s);
-  }
+  if (fb == Format::CSR)  // pos of the result from its ordered rows (zero-filled above: an empty result keeps it)
+    return launch_pos_from_sorted_rows(co.a0, nb + nc, static_cast<int>(N), out_pos, s, out_nnz);
   return SPT_OK;
 }
 

@@ -25,10 +25,14 @@ static __device__ __forceinline__ void store_pos_range(int32_t* __restrict__ pos
   }
 }
 template <bool VEC>
+// n_dev: if not null, the number of entries is read from there (a count that an earlier
+// kernel produced); the grid then covers the capacity n and the lanes beyond the count idle.
 static __global__ __launch_bounds__(kBlock) void pos_from_sorted_rows_kernel(const int32_t* __restrict__ row,
                                                                       int n, int nrows,
-                                                                      int32_t* __restrict__ pos) {
+                                                                      int32_t* __restrict__ pos,
+                                                                      const int64_t* __restrict__ n_dev) {
   typedef int32_t i4 __attribute__((ext_vector_type(4)));
+  if (n_dev) n = static_cast<int>(*n_dev);
   const int p0 = (blockIdx.x * kBlock + threadIdx.x) * 4;  // four consecutive entries per lane
   int r4[4];
   if (VEC && p0 + 4 <= n) {
@@ -50,16 +54,17 @@ static __global__ __launch_bounds__(kBlock) void pos_from_sorted_rows_kernel(con
   }
 }
 
-// Enqueues pos_from_sorted_rows_kernel for n > 0 ordered row coordinates.
+// Enqueues pos_from_sorted_rows_kernel for n > 0 ordered row coordinates (with n_dev: for at
+// most n of them, the count being in device memory; a count of 0 leaves pos untouched).
 inline spt_status launch_pos_from_sorted_rows(const int32_t* rows, int n, int nrows, int32_t* pos,
-                                              hipStream_t s) {
+                                              hipStream_t s, const int64_t* n_dev = nullptr) {
   const unsigned grid = (unsigned)((n + 4 * kBlock - 1) / (4 * kBlock));
   if ((reinterpret_cast<uintptr_t>(rows) & 15) == 0)
     hipLaunchKernelGGL(pos_from_sorted_rows_kernel<true>, dim3(grid), dim3(kBlock), 0, s, rows, n,
-                       nrows, pos);
+                       nrows, pos, n_dev);
   else
     hipLaunchKernelGGL(pos_from_sorted_rows_kernel<false>, dim3(grid), dim3(kBlock), 0, s, rows, n,
-                       nrows, pos);
+                       nrows, pos, n_dev);
   SPT_CHECK_LAUNCH("pos_from_sorted_rows");
   return SPT_OK;
 }
