@@ -139,3 +139,73 @@ def test_widening_entry_points_in_a_captured_graph():
         assert torch.equal(outs["csf"][3][:n1], e[3][:n1]) and torch.equal(outs["csf"][4][:n1 + 1], e[4][:n1 + 1])
         nb = len(bv)
         assert torch.equal(outs["csf"][5][:nb], e[5][:nb]) and torch.equal(outs["csf"][6][:nb], e[6][:nb])
+
+
+def test_later_entry_points_in_a_captured_graph():
+    """Element-wise product (CSR x COO, CSR result), SpMV on BCSR / DCSR / CSC / array-of-structs
+    COO, and the two element-wise operations with a dense operand or result: captured once,
+    replayed three times with eager work in between, compared with the eager results (bit for bit
+    where the kernels add in a fixed order, within the tolerance where they use atomics)."""
+    import torch
+    import paper_1804_10112_amd as spt
+    from gpu_util import assert_close
+    N, M = 600, 500
+    r1, c1, v1 = wl.random_coo_entries(N, M, 40_000, seed=11, dtype=np.float64)
+    r2, c2, v2 = wl.random_coo_entries(N, M, 50_000, seed=12, dtype=np.float64)
+    csr = spt.DeviceTensor(wl.csr_from_sorted_coo(N, M, r1, c1, v1))
+    coo = spt.DeviceTensor(wl.coo_spec(N, M, r2, c2, v2))
+    dcsr = spt.DeviceTensor(wl.dcsr_from_sorted_coo(N, M, r1, c1, v1))
+    csc = spt.DeviceTensor(wl.csc_from_coo(N, M, r1, c1, v1))
+    aos = spt.DeviceTensor(wl.coo_aos_spec((N, M), (r1, c1), v1))
+    blk = wl.random_bcsr(150, 125, 4, 4, 0, 30, seed=13, dtype=np.float64)
+    bcsr = spt.DeviceTensor(blk["bcsr"])
+    x = torch.from_numpy(wl.dense_vector(M, 14)).cuda()
+    xb = torch.from_numpy(blk["x"]).cuda()
+    D = torch.from_numpy(np.random.default_rng(15).uniform(-1, 1, (N, M))).cuda()
+    f64 = lambda *shape: torch.zeros(*shape, dtype=torch.float64, device="cuda")
+    i32 = lambda n: torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    cap = 40_000
+    outs = {"mul": [i32(N + 1), i32(cap), f64(cap), torch.zeros(1, dtype=torch.int64, device="cuda")],
+            "y": [f64(N) for _ in range(3)], "y_csc": [f64(N)], "yb": [f64(600)],
+            "muld": [f64(len(v1))], "dense": [f64(N, M)]}
+    ws = {"mul": torch.empty(spt.spt_add_workspace_bytes(csr, coo), dtype=torch.uint8, device="cuda"),
+          "dcsr": dcsr.workspace(spt.SPT_OP_SPMV), "csc": csc.workspace(spt.SPT_OP_SPMV),
+          "aos": aos.workspace(spt.SPT_OP_SPMV), "bcsr": bcsr.workspace(spt.SPT_OP_SPMV)}
+
+    def run_all():
+        m = outs["mul"]
+        spt.spt_mul(csr, coo, m[0], None, m[1], None, m[2], m[3], ws["mul"])
+        spt.spt_spmv(dcsr, x, outs["y"][0], ws["dcsr"])
+        spt.spt_spmv(aos, x, outs["y"][1], ws["aos"])
+        spt.spt_spmv(csr, x, outs["y"][2], ws["dcsr"])         # any workspace large enough will do
+        spt.spt_spmv(csc, x, outs["y_csc"][0], ws["csc"])
+        spt.spt_spmv(bcsr, xb, outs["yb"][0], ws["bcsr"])
+        spt.spt_mul_dense(csr, D, M, outs["muld"][0])
+        spt.spt_add_to_dense(csr, coo, outs["dense"][0], M)
+
+    run_all()
+    torch.cuda.synchronize()
+    eager = {k: [t.clone() for t in v] for k, v in outs.items()}
+    n_mul = int(eager["mul"][3].item())
+    assert 0 < n_mul < 40_000
+    assert torch.equal(eager["y"][0], eager["y"][2]) and torch.equal(eager["y"][1], eager["y"][2])
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run_all()
+    for rep in range(3):
+        for v in outs.values():
+            for t in v:
+                t.fill_(-3)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert int(outs["mul"][3].item()) == n_mul
+        for k, v in outs.items():
+            for j, (t, e) in enumerate(zip(v, eager[k])):
+                if k == "mul" and j in (1, 2):
+                    t, e = t[:n_mul], e[:n_mul]
+                if k == "y_csc":                              # binned rows are summed with LDS atomics
+                    ref = e.cpu().numpy()
+                    assert_close(t.cpu().numpy(), ref, np.abs(ref) + 1.0, np.float64, f"replay {rep} csc")
+                else:
+                    assert torch.equal(t, e), f"replay {rep}: {k}[{j}] differs"
