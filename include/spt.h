@@ -319,7 +319,9 @@ spt_status spt_coo_to_dia(const spt_tensor* A, int32_t K, const int32_t* offsets
 
 /*
  * Any composition -> COO, in storage order (Section 3.1: every format is a coordinate
- * hierarchy; its components are the root-to-leaf paths). T: order 1..3, any composition.
+ * hierarchy; its components are the root-to-leaf paths). T: order 1..3, any composition; or a
+ * blocked matrix of order 4 (BCSR, CSB, ...), written as the matrix it stores: out_crd0 /
+ * out_crd1 receive i1*b1 + i2 and j1*b2 + j2, every cell of a stored dense block counts.
  * out_crd0 .. out_crd[order-1] and out_vals need capacity nvals; components whose position
  * holds none (padding, empty buckets, cells outside a range level) are left out;
  * *out_nnz_dev (device int64) receives the number written. Workspace: SPT_OP_TO_COO.

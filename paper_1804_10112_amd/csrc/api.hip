@@ -542,10 +542,10 @@ spt_status spt_to_coo(const spt_tensor* T, int32_t* out_crd0, int32_t* out_crd1,
   if (ws_misaligned(ws)) return SPT_ERR_INVALID_ARG;
   Format f = recognize(T);
   if (f == Format::Invalid) return status_of(f);
-  if (T->order > 3) return fail(SPT_ERR_UNSUPPORTED, "to_coo: order %d above 3", T->order);
   if (!generic_ok(T)) return SPT_ERR_UNSUPPORTED;
+  // a blocked matrix (order 4) is written as the matrix it stores: two coordinate arrays
   if (!out_nnz_dev || (T->nvals > 0 && (!out_crd0 || !out_vals || (T->order > 1 && !out_crd1) ||
-                                        (T->order > 2 && !out_crd2))))
+                                        (T->order == 3 && !out_crd2))))
     return fail(SPT_ERR_INVALID_ARG, "to_coo: null output");
   return to_coo_dispatch(T, out_crd0, out_crd1, out_crd2, out_vals, out_nnz_dev, ws, ws_bytes,
                          static_cast<hipStream_t>(stream));
@@ -669,7 +669,7 @@ size_t spt_workspace_bytes(int32_t op, const spt_tensor* T, int32_t J) {
     if (op == SPT_OP_SPMV && f == Format::Unsupported && (T->order == 2 || T->order == 4) &&
         generic_ok(T))
       return 256;
-    if (op == SPT_OP_TO_COO && T->order <= 3 && generic_ok(T)) return to_coo_workspace(T->nvals);
+    if (op == SPT_OP_TO_COO && generic_ok(T)) return to_coo_workspace(T->nvals);
     if (g_err[0] == 0) fail(SPT_ERR_UNSUPPORTED, "operation %d is not defined for this composition", op);
     return 0;
   }

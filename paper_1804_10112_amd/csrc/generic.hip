@@ -259,6 +259,7 @@ __global__ __launch_bounds__(kBlock) void to_coo_count_kernel(const GTensor G, i
 
 template <typename VT>
 __global__ __launch_bounds__(kBlock) void to_coo_fill_kernel(const GTensor G, int64_t nvals,
+                                                             int64_t b1, int64_t b2,
                                                              const VT* __restrict__ vals,
                                                              const int32_t* __restrict__ offs,
                                                              int32_t* __restrict__ o0,
@@ -271,9 +272,14 @@ __global__ __launch_bounds__(kBlock) void to_coo_fill_kernel(const GTensor G, in
   int total;
   const int slot = offs[blockIdx.x] + block_inclusive_sum(has, &total) - has;
   if (has) {
-    o0[slot] = static_cast<int32_t>(c[0]);
-    if (G.order > 1) o1[slot] = static_cast<int32_t>(c[1]);
-    if (G.order > 2) o2[slot] = static_cast<int32_t>(c[2]);
+    if (G.order == 4) {  // blocked matrix: element (i1 * b1 + i2, j1 * b2 + j2)
+      o0[slot] = static_cast<int32_t>(c[0] * b1 + c[2]);
+      o1[slot] = static_cast<int32_t>(c[1] * b2 + c[3]);
+    } else {
+      o0[slot] = static_cast<int32_t>(c[0]);
+      if (G.order > 1) o1[slot] = static_cast<int32_t>(c[1]);
+      if (G.order > 2) o2[slot] = static_cast<int32_t>(c[2]);
+    }
     ov[slot] = vals[p];
   }
 }
@@ -315,7 +321,11 @@ static spt_status to_coo_typed(const spt_tensor* T, int32_t* o0, int32_t* o1, in
   if (st != SPT_OK) return st;
   hipLaunchKernelGGL(to_coo_total_kernel, dim3(1), dim3(kWave), 0, s, nch, counts, offs, out_nnz);
   SPT_CHECK_LAUNCH("to_coo total");
-  hipLaunchKernelGGL(to_coo_fill_kernel<VT>, dim3(nch), dim3(kBlock), 0, s, G, nvals,
+  const bool blocked = T->order == 4;
+  const int64_t b1 = blocked ? mode_size(T, 2) : 1, b2 = blocked ? mode_size(T, 3) : 1;
+  if (blocked && (mode_size(T, 0) * b1 >= INT32_MAX || mode_size(T, 1) * b2 >= INT32_MAX))
+    return fail(SPT_ERR_UNSUPPORTED, "to_coo: blocked matrix beyond 2^31 rows or columns");
+  hipLaunchKernelGGL(to_coo_fill_kernel<VT>, dim3(nch), dim3(kBlock), 0, s, G, nvals, b1, b2,
                      static_cast<const VT*>(T->vals), offs, o0, o1, o2, ov);
   SPT_CHECK_LAUNCH("to_coo fill");
   return SPT_OK;

@@ -106,3 +106,48 @@ def test_blocked_errors():
     A.c.level[1].M = 49                                      # one parent per block row
     with pytest.raises(spt.SptError):
         spt.spt_spmv(A, x, y, torch.empty(1 << 16, dtype=torch.uint8, device="cuda"))
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_blocked_to_coo_and_on_to_csr(dtype):
+    """spt_to_coo writes a blocked matrix as the matrix it stores (row i1*b1+i2, column j1*b2+j2),
+    in storage order; BCSR -> COO -> CSR then multiplies like the BCSR it came from."""
+    import torch
+    import paper_1804_10112_amd as spt
+    from gpu_util import gpu_coo_to_csr
+    b1, b2 = 3, 2
+    w = wl.random_bcsr(400, 350, b1, b2, 0, 12, seed=80, dtype=dtype)
+    N, M = 400 * b1, 350 * b2
+    for spec in (w["bcsr"],):
+        T = spt.DeviceTensor(spec)
+        n = len(spec.vals)
+        r = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+        c = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+        v = torch.zeros(n, dtype=T.torch_dtype, device="cuda")
+        cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+        spt.spt_to_coo(T, r, c, None, v, cnt, T.workspace(spt.SPT_OP_TO_COO))
+        torch.cuda.synchronize()
+        assert int(cnt.item()) == n                               # every cell of a stored block counts
+        coords, vals = oracle.to_coo(spec)                        # (i1, j1, i2, j2) per leaf
+        assert np.array_equal(r.cpu().numpy(), coords[0] * b1 + coords[2])
+        assert np.array_equal(c.cpu().numpy(), coords[1] * b2 + coords[3])
+        assert np.array_equal(v.cpu().numpy().astype(np.float64), vals)
+        coo = wl.coo_spec(N, M, r.cpu().numpy(), c.cpu().numpy(), v.cpu().numpy(), ordered=False)
+        pos, crd, cv = gpu_coo_to_csr(coo, 0)
+        ref, mag = oracle.spmv_blocked(spec, w["x"])
+        assert_close(gpu_spmv(wl.csr_spec(N, M, pos, crd, cv), w["x"]), ref, mag, dtype, "bcsr -> coo -> csr")
+    # CSB: exactly the stored entries
+    rr, cc, vv = wl.random_coo_entries(90, 70, 1500, seed=81, dtype=dtype)
+    csb = wl.csb_from_coo(90, 70, rr, cc, vv, 8, 4)
+    T = spt.DeviceTensor(csb)
+    r = torch.zeros(1500, dtype=torch.int32, device="cuda")
+    c = torch.zeros(1500, dtype=torch.int32, device="cuda")
+    v = torch.zeros(1500, dtype=T.torch_dtype, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+    spt.spt_to_coo(T, r, c, None, v, cnt, T.workspace(spt.SPT_OP_TO_COO))
+    torch.cuda.synchronize()
+    k = int(cnt.item())
+    assert k == len(vv)
+    o = np.lexsort((c.cpu().numpy()[:k], r.cpu().numpy()[:k]))
+    assert np.array_equal(r.cpu().numpy()[:k][o], rr) and np.array_equal(c.cpu().numpy()[:k][o], cc)
+    assert np.array_equal(v.cpu().numpy()[:k][o], vv)
