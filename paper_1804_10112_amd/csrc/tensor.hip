@@ -299,6 +299,31 @@ struct MttkrpShared {
 };
 
 
+// First r in [0, n] with a[r] >= target (a ascending, n entries).
+__device__ __forceinline__ int first_at_or_after(const int32_t* __restrict__ a, int n, int target) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    const int mid = lo + ((hi - lo) >> 1);
+    if (a[mid] < target) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+// CSF: for chunk boundary c (entries from c * chunk on), out[3c] = first fiber that starts at or
+// after it, out[3c+1] = first slice that starts at or after that fiber, out[3c+2] = the same as
+// the end of the chunk before (all slices once the fibers are used up). Boundary nchunks = the end.
+__global__ __launch_bounds__(kBlock) void csf_chunk_bounds_kernel(
+    int nchunks, int chunk, int nslices, int nfibers, const int32_t* __restrict__ pos1,
+    const int32_t* __restrict__ pos2, int32_t* __restrict__ out) {
+  const int c = blockIdx.x * kBlock + threadIdx.x;
+  if (c > nchunks) return;
+  const int f = c == nchunks ? nfibers : first_at_or_after(pos2, nfibers + 1, c * chunk);
+  const int sl = first_at_or_after(pos1, nslices + 1, f);
+  out[3 * c] = f;
+  out[3 * c + 1] = sl;
+  out[3 * c + 2] = f >= nfibers ? nslices : sl;
+}
+
 template <typename T, int G, int MODE>
 __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
     int n, int J,
@@ -317,7 +342,6 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
   __shared__ MttkrpShared<T, G> sh;
   __shared__ int32_t s_i[MODE == MT_CSF ? CHUNK : 1];
   __shared__ int32_t s_k[MODE == MT_CSF ? CHUNK : 1];
-  __shared__ int s_bounds[4];
   __shared__ int s_mark0;
   // SpDM closes a row every few entries. A store issued between two batches of gathers
   // makes the next batch wait for the store's acknowledgement (loads and stores retire
@@ -339,33 +363,20 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
     // Expand the coordinates of levels 0 and 1 for the entries of this chunk:
     // mark the first entry of every fiber / slice that starts inside the chunk,
     // then let every entry take the last mark at or before it.
-    const bool lastc = chunk_end == n;
-    if (wave_id() == 0) {
-      int f = wave_lower_bound(pos2, nfibers + 1, chunk_base);
-      if (lane_id() == 0) s_bounds[0] = f;
-    } else if (wave_id() == 1) {
-      int f = lastc ? nfibers : wave_lower_bound(pos2, nfibers + 1, chunk_end);
-      if (lane_id() == 0) s_bounds[1] = f;
-    }
+    // fibers [f_lo, f_hi) and slices [s_lo, s_hi) start inside the chunk; found beforehand, one
+    // bisection per chunk boundary (csf_chunk_bounds_kernel), passed through in_key
+    const int f_lo = in_key[3 * chunk], f_hi = in_key[3 * chunk + 3];
     for (int e = tid; e < CHUNK; e += kBlock) {
       s_i[e] = -1;
       s_k[e] = -1;
     }
     __syncthreads();
-    const int f_lo = s_bounds[0], f_hi = s_bounds[1];
-    if (wave_id() == 0) {
-      int sl = wave_lower_bound(pos1, nslices + 1, f_lo);
-      if (lane_id() == 0) s_bounds[2] = sl;
-    } else if (wave_id() == 1) {
-      int sl = (f_hi >= nfibers) ? nslices : wave_lower_bound(pos1, nslices + 1, f_hi);
-      if (lane_id() == 0) s_bounds[3] = sl;
-    }
     for (int f = f_lo + tid; f < f_hi; f += kBlock) {
       const int a = pos2[f];
       if (pos2[f + 1] > a) s_k[a - chunk_base] = crd1[f];
     }
     __syncthreads();
-    const int s_lo = s_bounds[2], s_hi = s_bounds[3];
+    const int s_lo = in_key[3 * chunk + 1], s_hi = in_key[3 * chunk + 5];
     for (int sl = s_lo + tid; sl < s_hi; sl += kBlock) {
       const int f0 = pos1[sl];
       if (pos1[sl + 1] > f0) {
@@ -602,7 +613,8 @@ size_t mttkrp_workspace(Format, const spt_tensor* B, int32_t J) {
   const int64_t n1 = (B->nvals + chunk - 1) / chunk;
   const int64_t n2 = (n1 + chunk2 - 1) / chunk2;
   return align_up((size_t)n1 * 4, 256) + align_up((size_t)n1 * J * 8, 256) +
-         align_up((size_t)n2 * 4, 256) + align_up((size_t)n2 * J * 8, 256) + 256;
+         align_up((size_t)n2 * 4, 256) + align_up((size_t)n2 * J * 8, 256) +
+         align_up((size_t)(n1 + 1) * 12, 256) + 256;
 }
 
 // rows_override / cols_override (SpDM mode only): row and column index per stored entry taken
@@ -652,9 +664,13 @@ static spt_status mttkrp_launch(Format f, const spt_tensor* B, const T* Cm, cons
     const int64_t nsl = L[1].M, nfib = L[2].M;
     if (nsl + 1 >= INT32_MAX || nfib + 1 >= INT32_MAX)
       return fail(SPT_ERR_UNSUPPORTED, "mttkrp: tensor too large");
+    int32_t* bounds = W.take<int32_t>(3 * ((size_t)n1 + 1));
+    hipLaunchKernelGGL(csf_chunk_bounds_kernel, dim3((n1 + 1 + kBlock - 1) / kBlock), dim3(kBlock), 0, s,
+                       n1, CHUNK, (int)nsl, (int)nfib, L[1].pos, L[2].pos, bounds);
+    SPT_CHECK_LAUNCH("csf chunk bounds");
     hipLaunchKernelGGL((mttkrp_kernel<T, G, MT_CSF>), dim3(n1, jt), dim3(kBlock), 0, s, nnz, J,
                        nullptr, nullptr, L[2].crd, static_cast<const T*>(B->vals), Cm, Dm, L[0].crd,
-                       L[1].pos, L[1].crd, L[2].pos, (int)nsl, (int)nfib, nullptr, nullptr, A, key1,
+                       L[1].pos, L[1].crd, L[2].pos, (int)nsl, (int)nfib, bounds, nullptr, A, key1,
                        vec1);
   }
   SPT_CHECK_LAUNCH("mttkrp");
