@@ -187,8 +187,13 @@ Format recognize(const spt_tensor* T) {
     // DCSR with unique rows has a fast path for SpMV; every other operation and DCSR with
     // repeated row coordinates take it as "any composition"
     if (is(L[0], SPT_COMPRESSED) && is(L[1], SPT_COMPRESSED) && modes(0, 1, 0, 0) && L[0].M == 1 &&
-        unique(L[0]) && L[1].pos && (L[0].crd || L[1].M == 0))
+        unique(L[0]) && L[1].pos && (L[0].crd || L[1].M == 0)) {
+      if (T->nvals > 0 && L[1].M < 1) {
+        fail(SPT_ERR_INVALID_ARG, "DCSR: values are stored but the column level has no parent row (M = 0)");
+        return Format::Invalid;
+      }
       return Format::DCSR;
+    }
     if (is(L[0], SPT_COMPRESSED) && is(L[1], SPT_SINGLETON) && modes(0, 1, 0, 0)) {
       if (L[0].M != 1) {
         fail(SPT_ERR_INVALID_ARG, "COO: the row level has one root parent (M = 1)");
@@ -233,6 +238,14 @@ Format recognize(const spt_tensor* T) {
     if (is(L[0], SPT_COMPRESSED) && is(L[1], SPT_COMPRESSED) && is(L[2], SPT_COMPRESSED)) {
       if (L[0].M != 1 || !unique(L[0]) || !unique(L[1])) {
         fail(SPT_ERR_INVALID_ARG, "CSF: root level needs M = 1 and the upper levels are unique");
+        return Format::Invalid;
+      }
+      // M of a compressed level is the number of positions of its parent level (Section 3.1):
+      // level 1 has one segment per stored slice, level 2 one per stored fibre. The kernels
+      // bisect pos[0 .. M]; the host can only check that values imply parents
+      // (spt_validate checks pos0[1] = M1, pos1[M1] = M2, pos2[M2] = nvals on the device).
+      if (T->nvals > 0 && (L[1].M < 1 || L[2].M < 1)) {
+        fail(SPT_ERR_INVALID_ARG, "CSF: values are stored but level 1 or 2 has no parent position (M = 0)");
         return Format::Invalid;
       }
       return Format::CSF3;

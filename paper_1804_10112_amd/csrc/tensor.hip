@@ -377,12 +377,11 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
     }
     __syncthreads();
     const int s_lo = in_key[3 * chunk + 1], s_hi = in_key[3 * chunk + 5];
+    // a slice is marked at its first stored entry, whichever of its fibers holds it (a
+    // compressed level may hold empty segments: leading fibers of a slice can be empty)
     for (int sl = s_lo + tid; sl < s_hi; sl += kBlock) {
-      const int f0 = pos1[sl];
-      if (pos1[sl + 1] > f0) {
-        const int a = pos2[f0];
-        if (pos2[f0 + 1] > a) s_i[a - chunk_base] = crd0[sl];
-      }
+      const int a = pos2[pos1[sl]];
+      if (pos2[pos1[sl + 1]] > a && a < chunk_base + CHUNK) s_i[a - chunk_base] = crd0[sl];
     }
     __syncthreads();
     // propagate marks forward: 256 threads, CHUNK/256 consecutive entries each
@@ -813,6 +812,18 @@ __global__ __launch_bounds__(kBlock) void expand_fiber_ids_kernel(int nfib,
   for (int p = a; p < b; ++p) fid[p] = f;
 }
 
+// CSF: a fibre without entries (a compressed level may hold empty segments) still owns K
+// output values; no entry ever writes them, so they are set to zero here. One lane per
+// (fibre, k) pair would read pos2 K times: a lane tests one fibre and the rare hit loops.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void zero_empty_fibres_kernel(int nfib, int K,
+                                                                   const int32_t* __restrict__ pos2,
+                                                                   T* __restrict__ out) {
+  const int f = blockIdx.x * kBlock + threadIdx.x;
+  if (f >= nfib || pos2[f + 1] > pos2[f]) return;
+  for (int k = 0; k < K; ++k) out[(int64_t)f * K + k] = T(0);
+}
+
 // Ct[l * K + k] = C[k * L + l]
 template <typename T>
 __global__ __launch_bounds__(kBlock) void transpose_kernel(int K, int64_t L, const T* __restrict__ C,
@@ -884,6 +895,9 @@ static spt_status ttm_typed(Format f, const spt_tensor* B, const T* C, int K, in
     hipLaunchKernelGGL(expand_fiber_ids_kernel, dim3((unsigned)((nfib + kBlock - 1) / kBlock)),
                        dim3(kBlock), 0, s, (int)nfib, B->level[2].pos, fid);
     SPT_CHECK_LAUNCH("ttm expand fibre ids");
+    hipLaunchKernelGGL(zero_empty_fibres_kernel<T>, dim3((unsigned)((nfib + kBlock - 1) / kBlock)),
+                       dim3(kBlock), 0, s, (int)nfib, K, B->level[2].pos, out_v);
+    SPT_CHECK_LAUNCH("ttm zero empty fibres");
   }
   hipLaunchKernelGGL(transpose_kernel<T>, dim3((unsigned)((L * K + kBlock - 1) / kBlock)),
                      dim3(kBlock), 0, s, K, L, C, Ct);

@@ -136,3 +136,30 @@ def test_scaled_config5():
     c5 = wl.config5(dims=(2000, 1600, 1000), nnz=400_000)
     _check_ttv(c5["coo"], c5["csf"], c5["c"], "c5 ttv")
     _check_mttkrp(c5["coo"], c5["csf"], c5["C"], c5["D"], "c5 mttkrp")
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("nnz,extra", [(300, 400), (5000, 3000), (60_000, 20_000)])
+def test_csf_with_empty_fibres_and_slices(dtype, nnz, extra):
+    """Empty segments in the compressed levels (first, middle and last fibre of a slice empty,
+    slices made of empty fibres only, slices without fibres) against the unfactored oracle."""
+    dims = (20_000, 60, 70)
+    ci, ck, cl, v = wl.random_coo3_entries(dims, nnz, 700 + nnz, dtype, "u01", skew=1.5)
+    coo = wl.coo3_spec(dims, ci, ck, cl, v)
+    gap = wl.csf3_with_empty_segments(dims, ci, ck, cl, v, seed=nnz, extra_fibers=extra, extra_slices=200)
+    p1, p2 = np.asarray(gap.levels[1].pos), np.asarray(gap.levels[2].pos)
+    lead = p1[:-1][np.diff(p1) > 0]
+    assert (np.diff(p2)[lead] == 0).sum() > 0 and (np.diff(p1) == 0).sum() > 0
+    rng = np.random.default_rng(nnz)
+    for J in (32, 40):
+        Cm = rng.uniform(0, 1, (dims[1], J)).astype(dtype)
+        Dm = rng.uniform(0, 1, (dims[2], J)).astype(dtype)
+        ref, mag = oracle.mttkrp(coo, Cm, Dm)
+        assert_close(gpu_mttkrp(gap, Cm, Dm), ref, mag, dtype, f"mttkrp csf with gaps J={J}")
+    # TTV: one value per fibre position, 0 for a fibre without entries
+    c = wl.dense_vector(dims[2], 5, dtype, "u01")
+    ri, rj, rv, rm = oracle.ttv(coo, c)
+    _, _, ov, n = gpu_ttv(gap, c)
+    full = np.diff(p2) > 0
+    assert n == len(full) and np.all(ov[~full] == 0)
+    assert_close(ov[full], rv, rm, dtype, "ttv csf with gaps")

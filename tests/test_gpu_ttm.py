@@ -110,3 +110,21 @@ def test_ttm_full_size_sampled():
     assert np.array_equal(ri, gi[sample]) and np.array_equal(rj, gj[sample])
     assert_close(gv[sample], rv, rm, np.float32, "ttm coo full size sample")
     assert_close(fv[sample], rv, rm, np.float32, "ttm csf full size sample")
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_ttm_csf_with_empty_fibres(dtype):
+    """A fibre position without entries still owns K output values: they must come back 0, not
+    whatever the (NaN-prefilled) buffer held."""
+    dims = (700, 50, 90)
+    ci, cj, cl, v = wl.random_coo3_entries(dims, 8000, 31, dtype=dtype, dist="u11", skew=1.5)
+    gap = wl.csf3_with_empty_segments(dims, ci, cj, cl, v, seed=32, extra_fibers=5000, extra_slices=50)
+    p2 = np.asarray(gap.levels[2].pos)
+    full = np.diff(p2) > 0
+    for K in (5, 32):
+        Cm = np.random.default_rng(K).uniform(-1, 1, (K, dims[2])).astype(dtype)
+        ri, rj, rv, rm = oracle.ttm(wl.coo3_spec(dims, ci, cj, cl, v), Cm)
+        _, _, fv = gpu_ttm(gap, Cm, is_csf=True, fiber_capacity=len(full))
+        assert fv.shape == (len(full), K)
+        assert np.all(fv[~full] == 0), "values of empty fibres"
+        assert_close(fv[full], rv, rm, dtype, f"ttm csf with gaps K={K}")

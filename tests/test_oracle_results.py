@@ -329,6 +329,36 @@ def test_mttkrp_closed_forms():
     assert np.array_equal(oracle.plain_mttkrp(si, Ci, Di, "coo"), want)
 
 
+def test_csf_with_empty_fibres_and_slices_vs_dense_einsum():
+    """A compressed level may hold empty segments (Table 2: pos[p] = pos[p+1]): empty fibres at
+    the start, middle and end of slices and slices without fibres change nothing."""
+    dims = (40, 9, 7)
+    ci, ck, cl, v = wl.random_coo3_entries(dims, 120, seed=61, dtype=np.float64, skew=1.5)
+    gap = wl.csf3_with_empty_segments(dims, ci, ck, cl, v, seed=62, extra_fibers=150, extra_slices=12)
+    p1, p2 = np.asarray(gap.levels[1].pos), np.asarray(gap.levels[2].pos)
+    lead = p1[:-1][np.diff(p1) > 0]
+    assert (np.diff(p2) == 0).sum() > 50 and (np.diff(p1) == 0).sum() > 0   # gaps are really there
+    assert (np.diff(p2)[lead] == 0).sum() > 0                               # ... also as first fibre of a slice
+    B = _dense3(dims, ci, ck, cl, v)
+    rng = np.random.default_rng(63)
+    Cm, Dm, c = rng.uniform(0, 1, (9, 3)), rng.uniform(0, 1, (7, 3)), rng.uniform(0, 1, 7)
+    A, mag = oracle.mttkrp(gap, Cm, Dm)
+    np.testing.assert_allclose(A, np.einsum("ikl,kj,lj->ij", B, Cm, Dm), rtol=0, atol=1e-14 * mag.max())
+    assert np.all(np.abs(oracle.plain_mttkrp(gap, Cm, Dm, "csf") - A) <= 1e-13 * mag + 1e-300)
+    oi, oj, ov, om = oracle.ttv(gap, c)
+    want = np.einsum("ijk,k->ij", B, c)
+    assert np.array_equal(oi.astype(np.int64) * 9 + oj, np.unique(ci.astype(np.int64) * 9 + ck))
+    np.testing.assert_allclose(ov, want[oi, oj], rtol=0, atol=1e-14 * om.max())
+    # the plain CSF loop writes one value per fibre position, 0 for the empty ones
+    pv = oracle.plain_ttv(gap, c, "csf")
+    fi = np.repeat(np.asarray(gap.levels[0].crd), np.diff(p1))
+    np.testing.assert_allclose(pv, want[fi, np.asarray(gap.levels[1].crd)] * (np.diff(p2) > 0), atol=1e-14)
+    Ck = rng.uniform(0, 1, (4, 7))
+    ti, tj, tv, tm = oracle.ttm(gap, Ck)
+    assert np.array_equal(ti, oi) and np.array_equal(tj, oj)
+    np.testing.assert_allclose(tv, np.einsum("ijl,kl->ijk", B, Ck)[ti, tj], rtol=0, atol=1e-14 * tm.max())
+
+
 # ------------------------------------------------------------------ SpMV with sparse / hashed x
 
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])

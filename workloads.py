@@ -359,6 +359,33 @@ def csf3_from_sorted_coo(dims, ci, cj, ck, vals, name="csf3") -> TensorSpec:
     return csf3_spec(dims, pos0, crd0, pos1, crd1, pos2, ck, vals, name)
 
 
+def csf3_with_empty_segments(dims, ci, cj, ck, vals, seed, extra_fibers, extra_slices,
+                             name="csf3-gaps") -> TensorSpec:
+    """CSF of a sorted, duplicate-free entry list whose compressed levels also hold EMPTY
+    segments (Table 2: pos[p] = pos[p+1] is legal): `extra_fibers` (i,j) fibres without
+    entries and `extra_slices` slices without fibres are mixed in at random coordinates, so
+    empty fibres occur at the start, in the middle and at the end of slices, and whole slices
+    consist of empty fibres only. The stored components are exactly the given entries."""
+    rng = np.random.default_rng(seed)
+    ci, cj, ck = (np.asarray(a, dtype=np.int64) for a in (ci, cj, ck))
+    I, J = int(dims[0]), int(dims[1])
+    real = np.unique(ci * J + cj)                       # fibres that hold entries
+    gi = rng.integers(0, I, extra_fibers)
+    if len(ci):                                         # most ghosts fall into slices that exist
+        pick = rng.random(extra_fibers) < 0.8
+        gi[pick] = ci[rng.integers(0, len(ci), int(pick.sum()))]
+    ghosts = gi * J + rng.integers(0, J, extra_fibers)
+    fibers = np.union1d(real, ghosts)                   # ascending (i,j), unique
+    count = np.zeros(len(fibers), np.int64)
+    if len(ci):
+        np.add.at(count, np.searchsorted(fibers, ci * J + cj), 1)
+    pos2 = np.concatenate(([0], np.cumsum(count)))
+    fi = fibers // J
+    slices = np.union1d(np.unique(fi), rng.integers(0, I, extra_slices))
+    pos1 = np.searchsorted(fi, np.append(slices, I), side="left")
+    return csf3_spec(dims, [0, len(slices)], slices, pos1, fibers % J, pos2, ck, vals, name)
+
+
 # ---------------------------------------------------------------------------
 # generic small random inputs (parity sweeps)
 # ---------------------------------------------------------------------------
