@@ -189,6 +189,22 @@ spt_status spt_spmv(const spt_tensor* A, const void* x, void* y, void* ws,
                     size_t ws_bytes, void* stream);
 
 /*
+ * spt_spmv for callers that cannot allocate or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc. Same operands, result and
+ * errors as spt_spmv; the scratch memory comes from a fixed array of
+ * SPT_STATIC_SCRATCH_BYTES in device memory that belongs to the library's code object (every
+ * GPU the library runs on holds its own copy until the process ends). The call allocates
+ * nothing and frees nothing. An operand whose spt_workspace_bytes(SPT_OP_SPMV, ...) exceeds
+ * SPT_STATIC_SCRATCH_BYTES is refused with SPT_ERR_WORKSPACE (CSR, ordered COO, DIA, ELL of
+ * any size fit; the binned scatter of a large unordered COO does not). The array's address
+ * is looked up on the first call on each device, so make that first call outside a graph
+ * capture. All calls on one GPU share the array: calls that overlap in time on one GPU
+ * (different streams, or threads) race; calls on one stream are ordered and safe.
+ */
+#define SPT_STATIC_SCRATCH_BYTES ((size_t)4 << 20)
+spt_status spt_spmv_static(const spt_tensor* A, const void* x, void* y, void* stream);
+
+/*
  * y = A x with A in CSR and x stored as a 1st-order tensor (Section 5.4, Figure
  * 16: dense array vs sparse vector vs hash map as the format of x):
  *   sparse vector  one compressed level, ordered and unique: pos = [0, nnz_x]

@@ -22,12 +22,13 @@ SPT_OP_TO_CSF, SPT_OP_TO_ELL, SPT_OP_DIA_OFFSETS, SPT_OP_TO_COO = 6, 7, 8, 9
 SPT_ORDER_ROW_COL, SPT_ORDER_ROW_STABLE = 0, 1
 SPT_ORDERED, SPT_UNIQUE = 1, 2
 SPT_F32, SPT_F64 = 0, 1
+SPT_STATIC_SCRATCH_BYTES = 4 << 20
 
 SYMBOLS = ["spt_spmv", "spt_coo_to_csr", "spt_ttv", "spt_mttkrp", "spt_workspace_bytes",
            "spt_last_error", "spt_version", "spt_probe_read", "spt_probe_gather",
            "spt_spmv_sparse_x", "spt_spdm", "spt_innerprod", "spt_ttm",
            "spt_add", "spt_mul", "spt_add_workspace_bytes", "spt_mul_dense", "spt_add_to_dense", "spt_coo3_to_csf", "spt_to_ell",
-           "spt_coo_dia_offsets", "spt_coo_to_dia", "spt_to_coo", "spt_to_hashed_rows"]
+           "spt_coo_dia_offsets", "spt_coo_to_dia", "spt_to_coo", "spt_to_hashed_rows", "spt_spmv_static"]
 
 
 class SptLevel(C.Structure):
@@ -64,6 +65,8 @@ def lib():
         vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
         L.spt_spmv.restype = i32
         L.spt_spmv.argtypes = [vp, vp, vp, vp, sz, vp]
+        L.spt_spmv_static.restype = i32
+        L.spt_spmv_static.argtypes = [vp, vp, vp, vp]
         L.spt_spmv_sparse_x.restype = i32
         L.spt_spmv_sparse_x.argtypes = [vp, vp, vp, vp, sz, vp]
         L.spt_coo_to_csr.restype = i32
@@ -166,6 +169,10 @@ def spt_workspace_bytes(op, T, J=0) -> int:
 def spt_spmv(A, x, y, ws=None, stream=None):
     p, n = _ws(ws)
     _check(lib().spt_spmv(_desc(A), _p(x), _p(y), p, n, _stream(stream)))
+
+
+def spt_spmv_static(A, x, y, stream=None):
+    _check(lib().spt_spmv_static(_desc(A), _p(x), _p(y), _stream(stream)))
 
 
 def spt_spmv_sparse_x(A, x, y, ws=None, stream=None):
