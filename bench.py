@@ -549,6 +549,9 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink every configuration (testing)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true")
+    ap.add_argument("--flush-mb", type=int, default=0,
+                    help="write a buffer of this many MiB before every call (outside its timed interval): "
+                         "cold caches for partial runs with --only")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB streaming read and one 1 GiB fill per step (known traffic, "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE); excluded from every figure")
@@ -572,6 +575,15 @@ def main():
             spt.spt_probe_read(ca, 1 << 30, 16, sink)
             ca.zero_()
 
+    flush = None
+    if args.flush_mb > 0:
+        # a partial step (--only) leaves its few operands in the 256 MB Infinity Cache; writing a
+        # large buffer before every call restores what the full step does by itself
+        # (read, not written: in the full step a call follows kernels that mostly read, and
+        # dirty lines left in the memory-side cache would charge their write-back to the call)
+        flush = torch.zeros(args.flush_mb << 20, dtype=torch.uint8, device="cuda:0")
+        flush_sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
+
     def step(record):
         # one event between consecutive calls: the end of call k is the start of call k+1
         prev = None
@@ -579,6 +591,11 @@ def main():
             prev = torch.cuda.Event(enable_timing=True)
             prev.record(stream)
         for it in items:
+            if flush is not None:
+                spt.spt_probe_read(flush, args.flush_mb << 20, 16, flush_sink)
+                if record:
+                    prev = torch.cuda.Event(enable_timing=True)
+                    prev.record(stream)
             it.run()
             if record:
                 e = torch.cuda.Event(enable_timing=True)

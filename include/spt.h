@@ -100,10 +100,14 @@ typedef enum {
  *   max_children  optional hint for a compressed level: an upper bound on the
  *          number of children of any one parent (CSR: the longest row), 0 =
  *          unknown. Like the level properties of Section 3.3 it is a declared
- *          invariant that only selects a faster loop: with a bound <= 32 CSR
- *          SpMV streams the entries of 256 rows at a time through LDS and lets
- *          one lane add up each row, instead of running the entry-balanced
- *          kernel. A bound that the data violates costs time, not correctness.
+ *          invariant that only selects between loops. CSR SpMV has two: one that
+ *          streams the entries of 256 rows at a time through LDS and lets one lane
+ *          add up each row (best for short rows), and one that deals the entries
+ *          out evenly whatever their rows (best for strongly skewed row lengths).
+ *          Without the hint the mean row length nvals / rows decides (<= 32: the
+ *          streamed loop); a declared bound <= 32 selects the streamed loop, a
+ *          larger one the entry-balanced loop. A bound that the data violates
+ *          costs time, not correctness.
  *   crd_stride  elements of crd between the coordinates of consecutive positions: 0 or 1 =
  *          contiguous (struct of arrays). A larger stride describes the array-of-structs
  *          variant of Section 5.2, where one interleaved array holds the coordinates of each

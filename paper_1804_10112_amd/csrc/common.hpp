@@ -54,6 +54,15 @@ struct Workspace {
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 __device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
 
+// Workgroup barrier that orders LDS traffic only. __syncthreads() also waits for every
+// outstanding global load of the wave (its fence covers global memory), which would
+// serialise loads issued ahead for a later step; this one waits for the wave's LDS
+// operations and then meets the other waves, so such loads stay in flight across it.
+// Use it only where nothing written to global memory has to be seen by the workgroup.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its
 // own L2. This maps blockIdx.x to a logical block id such that every XCD works
 // on one contiguous range of logical blocks, so neighbouring blocks (which

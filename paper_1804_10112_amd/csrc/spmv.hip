@@ -10,6 +10,9 @@
 //  * Unsorted COO is the paper's scatter loop: atomic adds into y.
 //  * DIA and ELL read the diagonal-major / slot-major arrays with consecutive
 //    rows in consecutive lanes.
+#include <algorithm>
+#include <cstdlib>
+
 #include "common.hpp"
 #include "segreduce.hpp"
 
@@ -87,10 +90,15 @@ template <> struct VecOf<float> { static constexpr int R = 4; typedef float type
 // KT > 0: the number of diagonals is the compile-time constant KT, so all KT
 // diagonal loads and their x loads are issued before the first use (one memory
 // round trip per lane). KT == 0: any K, in batches of 8 (the tail batch re-reads
-// the last diagonal and masks it out). No load sits behind a branch: cells
-// outside the diagonal's row range are loaded (they are inside the array) but
-// never used, and x is read at a clamped index.
-template <typename T, int KT>
+// the last diagonal and masks it out).
+// A diagonal whose row range [max(0,-off), min(N, M-off)) misses all rows of the
+// wave is skipped by the whole wave (a scalar branch): far diagonals are empty
+// over half the matrix, and loading their cells would move bytes that are never
+// used. Inside a live wave no load sits behind a per-lane branch: cells outside the
+// range are loaded (they are inside the array) and masked, x is read at a clamped
+// index. XV: x is 16-byte aligned and M a multiple of R, so a diagonal whose offset
+// is a multiple of R reads its R values of x as one aligned 16-byte load.
+template <typename T, int KT, bool XV>
 __global__ __launch_bounds__(kBlock) void dia_spmv_vec_kernel(int64_t N, int64_t M, int K,
                                                               const int32_t* __restrict__ offset,
                                                               const T* __restrict__ vals,
@@ -99,23 +107,38 @@ __global__ __launch_bounds__(kBlock) void dia_spmv_vec_kernel(int64_t N, int64_t
   constexpr int R = VecOf<T>::R;
   constexpr int B = KT > 0 ? KT : 8;
   using V = typename VecOf<T>::type;
-  const int64_t i0 = ((int64_t)xcd_contiguous_block_id() * kBlock + threadIdx.x) * R;
+  const int64_t blk0 = (int64_t)xcd_contiguous_block_id() * kBlock;
+  const int64_t i0 = (blk0 + threadIdx.x) * R;
+  // rows [w0, w1) belong to this wave (uniform: kept in scalar registers)
+  const int64_t w0 = (blk0 + __builtin_amdgcn_readfirstlane(threadIdx.x & ~(kWave - 1))) * R;
+  const int64_t w1 = w0 + kWave * R;
   if (i0 >= N) return;
   V acc = 0;
   const int kend = KT > 0 ? KT : K;
   for (int d0 = 0; d0 < kend; d0 += B) {
     V v[B];
-    T xv[B][R];
+    V xv[B];
     int64_t j0[B];
 #pragma unroll
     for (int u = 0; u < B; ++u) {
       const int d = min(d0 + u, kend - 1);
-      j0[u] = i0 + offset[d];  // uniform address: a scalar load
-      v[u] = ld_stream(reinterpret_cast<const V*>(vals + (int64_t)d * N + i0));
+      const int64_t off = offset[d];  // uniform address: a scalar load
+      j0[u] = i0 + off;
+      v[u] = 0;
+      xv[u] = 0;
+      const int64_t lo = off < 0 ? -off : 0, hi = (M - off) < N ? (M - off) : N;
+      if (w0 < hi && w1 > lo) {  // uniform
+        v[u] = ld_stream(reinterpret_cast<const V*>(vals + (int64_t)d * N + i0));
+        if (XV && (off % R) == 0) {  // uniform; j0 is a multiple of R
+          const int64_t jc = j0[u] < 0 ? 0 : (j0[u] > M - R ? M - R : j0[u]);
+          xv[u] = *reinterpret_cast<const V*>(x + jc);
+        } else {
 #pragma unroll
-      for (int r = 0; r < R; ++r) {
-        const int64_t j = j0[u] + r;
-        xv[u][r] = x[j < 0 ? 0 : (j >= M ? M - 1 : j)];
+          for (int r = 0; r < R; ++r) {
+            const int64_t j = j0[u] + r;
+            xv[u][r] = x[j < 0 ? 0 : (j >= M ? M - 1 : j)];
+          }
+        }
       }
     }
 #pragma unroll
@@ -354,15 +377,32 @@ __global__ __launch_bounds__(kBlock) void seg_spmv_kernel(
 }
 
 // ---------------------------------------------------------------- CSR, short rows, streamed
-// A workgroup owns kStreamRows consecutive rows. Their entries are one contiguous range of
-// crd / vals, which the lanes read side by side with 16-byte loads (no lane waits on pos to
-// find its entries), multiply by x and park in LDS; then one lane per row adds its row's
-// products from LDS in order and stores y. The range is taken in pieces of kStreamCap entries,
-// so any row length is handled correctly; the kernel is chosen for short rows because there a
-// piece holds many whole rows. Fixed order of additions: bit-reproducible.
-constexpr int kStreamRPT = 1;                       // rows per lane in the reduction
-constexpr int kStreamRows = kStreamRPT * kBlock;    // rows per workgroup
-constexpr int kStreamCap = 2048;                    // products parked per piece
+// A workgroup owns 256 consecutive rows. Their entries are one contiguous range of crd /
+// vals, which the lanes read side by side with 16-byte loads (no lane waits on pos to find
+// its entries), multiply by x and park in LDS in pieces of kStreamCap products; then one
+// lane per row adds, in order, the part of its row that lies in the piece (eight LDS reads
+// per round trip). A row part longer than kStreamCoop products is added up by the whole wave
+// instead (strided partial sums, then a butterfly), so one long row costs its length / 64,
+// not its length. Any row length is handled; the kernel is chosen for short mean rows because
+// there a piece holds many whole rows and nothing has to be searched. Fixed order of
+// additions: bit-reproducible.
+// Measured and left out (banded matrix, 6 entries per row, fp64, 41 us): 2 or 4 rows per lane
+// (43 / 46 us: fewer, longer workgroups leave the last round of workgroups half empty);
+// workgroups that stay resident and walk through their blocks with the next piece's loads
+// issued before the current piece is reduced (43-45 us with 1024 or 2048 products per piece,
+// at 5, 6 or 8 waves per SIMD). The kernel runs at the rate at which the memory system serves
+// this mix of three streams and a gather of 64-byte pieces of x, not at a latency limit.
+constexpr int kStreamRows = kBlock;  // rows per workgroup, one per lane
+constexpr int kStreamCap = 2048;     // products parked per piece
+constexpr int kStreamCoop = 48;      // longer row parts are summed by the whole wave
+constexpr int kStreamLong = 3 * kStreamCap;  // rows from this length on take the register path
+
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+  for (int d = kWave / 2; d > 0; d >>= 1) v += __shfl_xor(v, d);
+  return v;
+}
 
 template <typename T, bool VEC, class XP>
 __global__ __launch_bounds__(kBlock) void csr_stream_kernel(int nrows, int nnz,
@@ -374,58 +414,137 @@ __global__ __launch_bounds__(kBlock) void csr_stream_kernel(int nrows, int nnz,
   using V = typename VecOf<T>::type;  // 16 bytes of values
   constexpr int R = VecOf<T>::R;
   __shared__ int32_t s_pos[kStreamRows + 1];
-  __shared__ T s_prod[kStreamCap + 4];
+  __shared__ T s_prod[kStreamCap];
+  __shared__ T s_wpart[kBlock / kWave];
+  __shared__ int s_lend;
+  const int tid = threadIdx.x;
   const int row0 = xcd_contiguous_block_id() * kStreamRows;
-  for (int q = threadIdx.x; q <= kStreamRows; q += kBlock) s_pos[q] = pos[min(row0 + q, nrows)];
+  for (int q = tid; q <= kStreamRows; q += kBlock) s_pos[q] = pos[min(row0 + q, nrows)];
   __syncthreads();
   const int e0 = s_pos[0], e1 = s_pos[kStreamRows];
   const int e0a = e0 & ~3;  // pieces start on a multiple of 4 entries: aligned 16-byte loads
-  T acc[kStreamRPT];
-  int ra[kStreamRPT], rb[kStreamRPT];
-#pragma unroll
-  for (int u = 0; u < kStreamRPT; ++u) {
-    acc[u] = T(0);
-    ra[u] = s_pos[u * kBlock + threadIdx.x];
-    rb[u] = s_pos[u * kBlock + threadIdx.x + 1];
+  const int ra = s_pos[tid], rb = s_pos[tid + 1];
+  T acc = T(0);
+  // can this block hold a row of kStreamLong entries or more? (uniform; rare)
+  const bool has_long = e1 - e0 >= kStreamLong;
+  if (has_long) {
+    if (tid == 0) s_lend = 0;
+    __syncthreads();
   }
+  constexpr int G = kStreamCap / (4 * kBlock);
   for (int c0 = e0a; c0 < e1; c0 += kStreamCap) {
+    if (has_long) {
+      // Long stretch of one row ahead: its whole pieces are added up in registers, without
+      // LDS and without a barrier per piece (so the loads of consecutive pieces overlap), and
+      // folded into the row's lane once. Keeps a block with a 100 000-entry row from taking
+      // fifty serial load -> park -> add rounds.
+      const bool mine = ra <= c0 && rb - c0 >= 2 * kStreamCap;  // at most one lane
+      if (mine) s_lend = rb;
+      __syncthreads();
+      const int lend = s_lend;
+      __syncthreads();
+      if (mine) s_lend = 0;
+      if (lend) {
+        T part = T(0);
+        int c = c0;
+#pragma unroll 1
+        for (; c + kStreamCap <= lend; c += kStreamCap) {
+#pragma unroll
+          for (int g = 0; g < G; ++g) {
+            const int p = c + 4 * (g * kBlock + tid);
+            if (VEC) {
+              const i4 cc = ld_stream(reinterpret_cast<const i4*>(crd + p));
+              T v[4];
+#pragma unroll
+              for (int h = 0; h < 4 / R; ++h) {
+                const V w = ld_stream(reinterpret_cast<const V*>(vals + p + R * h));
+#pragma unroll
+                for (int r = 0; r < R; ++r) v[R * h + r] = w[r];
+              }
+#pragma unroll
+              for (int r = 0; r < 4; ++r) part += v[r] * x.at(cc[r]);
+            } else {
+#pragma unroll
+              for (int r = 0; r < 4; ++r) part += ld_stream(vals + p + r) * x.at(ld_stream(crd + p + r));
+            }
+          }
+        }
+        part = wave_sum(part);
+        if (lane_id() == 0) s_wpart[wave_id()] = part;
+        __syncthreads();
+        if (mine) {
+#pragma unroll
+          for (int w = 0; w < kBlock / kWave; ++w) acc += s_wpart[w];
+        }
+        __syncthreads();
+        c0 = c - kStreamCap;  // the loop's increment moves on to c
+        continue;
+      }
+    }
     const int c1 = min(c0 + kStreamCap, e1);
-    const int groups = (c1 - c0 + 3) >> 2;
-    for (int g4 = threadIdx.x; g4 < groups; g4 += kBlock) {
-      const int p = c0 + 4 * g4;
-      T pr[4];
-      if (VEC && p + 4 <= nnz) {
-        const i4 c = ld_stream(reinterpret_cast<const i4*>(crd + p));
-        T v[4];
+    // a lane holds up to G groups of 4 consecutive entries; all their loads are issued before
+    // the first use, none behind a per-lane branch: a lane without work in this piece re-reads
+    // the piece's first group (one cache line for all such lanes) and parks products nobody adds
+    const bool whole = VEC && c1 + 3 <= nnz;  // uniform: every 16-byte group lies inside the arrays
+    T pr[G][4];
+    if (whole) {
+      i4 c[G];
+      T v[G][4];
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const int p = c0 + 4 * (g * kBlock + tid);
+        const int pc = p < c1 ? p : c0;
+        c[g] = ld_stream(reinterpret_cast<const i4*>(crd + pc));
 #pragma unroll
         for (int h = 0; h < 4 / R; ++h) {
-          const V w = ld_stream(reinterpret_cast<const V*>(vals + p + R * h));
+          const V w = ld_stream(reinterpret_cast<const V*>(vals + pc + R * h));
 #pragma unroll
-          for (int r = 0; r < R; ++r) v[R * h + r] = w[r];
+          for (int r = 0; r < R; ++r) v[g][R * h + r] = w[r];
         }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) pr[r] = v[r] * x.at(c[r]);
-      } else {
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-          pr[r] = p + r < nnz ? ld_stream(vals + p + r) * x.at(ld_stream(crd + p + r)) : T(0);
       }
 #pragma unroll
-      for (int r = 0; r < 4; ++r) s_prod[4 * g4 + r] = pr[r];
-    }
-    __syncthreads();
+      for (int g = 0; g < G; ++g)
 #pragma unroll
-    for (int u = 0; u < kStreamRPT; ++u) {
-      const int a = max(ra[u], c0), b = min(rb[u], c1);
-      for (int q = a; q < b; ++q) acc[u] += s_prod[q - c0];
+        for (int r = 0; r < 4; ++r) pr[g][r] = v[g][r] * x.at(c[g][r]);
+    } else {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const int p = c0 + 4 * (g * kBlock + tid);
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          pr[g][r] = p + r < c1 ? ld_stream(vals + p + r) * x.at(ld_stream(crd + p + r)) : T(0);
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) s_prod[4 * (g * kBlock + tid) + r] = pr[g][r];
+    __syncthreads();
+    const int a = max(ra, c0), e = min(rb, c1);
+    const bool big = e - a > kStreamCoop;
+    if (!big && a < e) {
+      for (int q0 = a; q0 < e; q0 += 8) {  // reads at a clamped index, added in order
+        T t[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) t[k] = s_prod[min(q0 + k, e - 1) - c0];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc += q0 + k < e ? t[k] : T(0);
+      }
+    }
+    uint64_t todo = __ballot(big);
+    while (todo) {  // uniform: the wave adds up one long row part at a time
+      const int src = __ffsll(static_cast<long long>(todo)) - 1;
+      todo &= todo - 1;
+      const int la = __shfl(a, src), lb = __shfl(e, src);
+      T part = T(0);
+      for (int q = la + lane_id(); q < lb; q += kWave) part += s_prod[q - c0];
+      part = wave_sum(part);
+      if (lane_id() == src) acc += part;
     }
     __syncthreads();
   }
-#pragma unroll
-  for (int u = 0; u < kStreamRPT; ++u) {
-    const int r = row0 + u * kBlock + threadIdx.x;
-    if (r < nrows) y[r] = acc[u];
-  }
+  const int r = row0 + tid;
+  if (r < nrows) y[r] = acc;
 }
 
 template <typename T, class XP>
@@ -444,11 +563,22 @@ static spt_status launch_csr_stream(int64_t nnz, int64_t nrows, const int32_t* p
   return SPT_OK;
 }
 
-// Longest declared row (max_children of the column level) for which the streamed kernel is
-// used. Measured against the entry-balanced kernel + fix-up: banded matrix, rows <= 7, fp64:
-// 36.9 vs 64.9 us (a row per group of 8 lanes: 48.6 us); rows of 8..32 entries, fp32: 119.6 vs
-// 135 us. Without a declared bound a single long row would be added up by one lane.
-constexpr int kShortRowHint = 32;
+// Which CSR kernel runs. The streamed kernel needs no search and no second launch and wins
+// where rows are short (banded matrix, 6 entries per row, fp64: 42 vs 65 us; rows of 8..32
+// entries, fp32: 117 vs 135 us); the entry-balanced kernel does not care how the entries are
+// spread over the rows (power-law rows, mean 15, longest 10^5: 0.97 ms against 1.08 ms
+// streamed). The host knows the mean row length (nvals / rows) and nothing about the spread,
+// so the mean decides, and a declared bound on the longest row (max_children of the column
+// level, 0 = unknown) overrides it either way.
+constexpr int kStreamMeanRow = 32;
+static bool csr_use_stream(int64_t nnz, int64_t nrows, int hint) {
+  if (nnz < 1 || nnz >= INT32_MAX || nrows + kBlock >= INT32_MAX) return false;
+  static const char* force = getenv("SPT_CSR_KERNEL");  // measurement aid: "stream" or "balanced"
+  if (force && force[0] == 's') return true;
+  if (force && force[0] == 'b') return false;
+  if (hint > 0) return hint <= kStreamMeanRow;
+  return nnz <= kStreamMeanRow * nrows;
+}
 
 // ---------------------------------------------------------------- unsorted COO
 // The fused single loop over all entries of the paper's COO kernel: a scatter
@@ -545,7 +675,7 @@ static spt_status spmv_sparse_x_typed(const spt_tensor* A, const spt_tensor* X, 
   const T* vals = static_cast<const T*>(A->vals);
   if (X->nvals >= INT32_MAX) return fail(SPT_ERR_UNSUPPORTED, "spmv: x too large");
   const int hint = A->level[1].max_children;  // declared short rows: the streamed kernel
-  const bool stream = hint > 0 && hint <= kShortRowHint && nnz > 0 && N + 1 < INT32_MAX && nnz < INT32_MAX;
+  const bool stream = csr_use_stream(nnz, N, hint);
   if (L.kind == SPT_HASHED) {
     if (L.M < 1) return fail(SPT_ERR_INVALID_ARG, "spmv: hashed x needs a table width W >= 1");
     if (stream)
@@ -608,7 +738,7 @@ static spt_status spmv_typed(Format f, const spt_tensor* A, const T* x, T* y, vo
       T* t = reinterpret_cast<T*>(W.take<double>(stored));
       char* rest = static_cast<char*>(ws) + W.used;
       const int hint = A->level[1].max_children;
-      if (hint > 0 && hint <= kShortRowHint && A->nvals > 0 && A->nvals < INT32_MAX)
+      if (csr_use_stream(A->nvals, stored, hint))
         st = launch_csr_stream<T, DenseX<T>>(A->nvals, stored, A->level[1].pos, A->level[1].crd, vals,
                                              DenseX<T>{x}, t, s);
       else
@@ -622,8 +752,7 @@ static spt_status spmv_typed(Format f, const spt_tensor* A, const T* x, T* y, vo
     }
     case Format::CSR: {
       const int hint = A->level[1].max_children;
-      if (hint > 0 && hint <= kShortRowHint && A->nvals > 0 && A->level[0].N + 1 < INT32_MAX &&
-          A->nvals < INT32_MAX)
+      if (csr_use_stream(A->nvals, A->level[0].N, hint))
         return launch_csr_stream<T, DenseX<T>>(A->nvals, A->level[0].N, A->level[1].pos,
                                                A->level[1].crd, vals, DenseX<T>{x}, y, s);
       return launch_seg<T, true>(A->nvals, A->level[0].N, A->level[1].pos, A->level[1].crd, vals,
@@ -683,10 +812,15 @@ static spt_status spmv_typed(Format f, const spt_tensor* A, const T* x, T* y, vo
         const int64_t lanes = N / R;
         const dim3 grid((unsigned)((lanes + kBlock - 1) / kBlock));
         const int32_t* off = A->level[1].offset;
+        const bool xvec = aligned16(x) && M % R == 0 && M >= R;
 #define SPT_DIA_CASE(KT)                                                                       \
   case KT:                                                                                     \
-    hipLaunchKernelGGL((dia_spmv_vec_kernel<T, KT>), grid, dim3(kBlock), 0, s, N, M, (int)K, off, \
-                       vals, x, y);                                                            \
+    if (xvec)                                                                                  \
+      hipLaunchKernelGGL((dia_spmv_vec_kernel<T, KT, true>), grid, dim3(kBlock), 0, s, N, M,   \
+                         (int)K, off, vals, x, y);                                             \
+    else                                                                                       \
+      hipLaunchKernelGGL((dia_spmv_vec_kernel<T, KT, false>), grid, dim3(kBlock), 0, s, N, M,  \
+                         (int)K, off, vals, x, y);                                             \
     break;
         switch (K <= 16 ? (int)K : 0) {
           SPT_DIA_CASE(1) SPT_DIA_CASE(2) SPT_DIA_CASE(3) SPT_DIA_CASE(4) SPT_DIA_CASE(5)
@@ -694,8 +828,8 @@ static spt_status spmv_typed(Format f, const spt_tensor* A, const T* x, T* y, vo
           SPT_DIA_CASE(11) SPT_DIA_CASE(12) SPT_DIA_CASE(13) SPT_DIA_CASE(14) SPT_DIA_CASE(15)
           SPT_DIA_CASE(16)
           default:
-            hipLaunchKernelGGL((dia_spmv_vec_kernel<T, 0>), grid, dim3(kBlock), 0, s, N, M, (int)K,
-                               off, vals, x, y);
+            hipLaunchKernelGGL((dia_spmv_vec_kernel<T, 0, false>), grid, dim3(kBlock), 0, s, N, M,
+                               (int)K, off, vals, x, y);
         }
 #undef SPT_DIA_CASE
       } else {
@@ -732,6 +866,15 @@ static spt_status spmv_typed(Format f, const spt_tensor* A, const T* x, T* y, vo
 spt_status csr_rows_reduce(int dtype, int64_t nnz, int64_t nrows, const int32_t* pos,
                            const int32_t* crd, const void* vals, const void* x, void* out,
                            void* ws, size_t ws_bytes, hipStream_t s) {
+  if (csr_use_stream(nnz, nrows, 0)) {
+    if (dtype == SPT_F64)
+      return launch_csr_stream<double, DenseX<double>>(nnz, nrows, pos, crd, static_cast<const double*>(vals),
+                                                       DenseX<double>{static_cast<const double*>(x)},
+                                                       static_cast<double*>(out), s);
+    return launch_csr_stream<float, DenseX<float>>(nnz, nrows, pos, crd, static_cast<const float*>(vals),
+                                                   DenseX<float>{static_cast<const float*>(x)},
+                                                   static_cast<float*>(out), s);
+  }
   if (dtype == SPT_F64)
     return launch_seg<double, true>(nnz, nrows, pos, crd, static_cast<const double*>(vals),
                                     static_cast<const double*>(x), static_cast<double*>(out), ws,

@@ -91,7 +91,11 @@ def test_power_law_rows_scaled_config4():
     o = np.lexsort((c, r))
     rs, cs, vs = r[o], c[o], coo.vals[o]
     a = _check(wl.coo_spec(40_000, 40_000, rs, cs, vs), c4["x"], "c4 sorted coo")
-    b = _check(wl.csr_from_sorted_coo(40_000, 40_000, rs, cs, vs), c4["x"], "c4 csr")
+    csr = wl.csr_from_sorted_coo(40_000, 40_000, rs, cs, vs)
+    b = _check(csr, c4["x"], "c4 csr, kernel chosen by the mean row length")
+    lv = csr.levels[1]
+    _check(wl.csr_spec(40_000, 40_000, lv.pos, lv.crd, csr.vals, max_row=20_000), c4["x"],
+           "c4 csr, declared long rows: entry-balanced kernel")
     assert np.bincount(r).max() > 2 * CHUNK      # a row really spans several chunks
 
 
@@ -157,22 +161,71 @@ def test_ell_scaled_config3_with_poisoned_padding(dtype, N):
     _check(z["ell"], z["x"], "ell all padding")
 
 
+def _with_hint(spec, bound):
+    lv = spec.levels[1]
+    return wl.csr_spec(spec.dims[0], spec.dims[1], lv.pos, lv.crd, spec.vals, max_row=bound)
+
+
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
 @pytest.mark.parametrize("lo,hi", [(0, 3), (1, 7), (0, 12), (9, 16), (8, 32)])
-def test_csr_short_row_hint_selects_the_streamed_kernel(dtype, lo, hi):
-    """max_children <= 32 on the column level: the streamed kernel (256 rows' entries through
-    LDS, one lane per row); no hint runs the entry-balanced kernel; all match the oracle."""
+def test_csr_kernel_choice_by_mean_row_length_and_by_hint(dtype, lo, hi):
+    """Plain (pos, crd) CSR with a short mean row runs the streamed kernel (256 rows' entries
+    through LDS, one lane per row) with no hint at all; a declared bound <= 32 selects the same
+    kernel (same bits), a larger one the entry-balanced kernel; all match the oracle."""
     c3 = wl.config3(N=5003, lo=lo, hi=hi, dtype=dtype)
     hinted = c3["csr"]
-    assert hinted.levels[1].max_children == c3["W"] <= 64
-    lv = hinted.levels[1]
-    plain = wl.csr_spec(5003, 5003, lv.pos, lv.crd, hinted.vals)
+    assert hinted.levels[1].max_children == c3["W"] <= 32
+    plain = _with_hint(hinted, 0)
     ref, mag = oracle.spmv(hinted, c3["x"])
-    a, b = gpu_spmv(hinted, c3["x"], repeat=2)
-    assert_close(a, ref, mag, dtype, f"streamed kernel rows {lo}..{hi}")
+    a, b = gpu_spmv(plain, c3["x"], repeat=2)
+    assert_close(a, ref, mag, dtype, f"no hint, rows {lo}..{hi}")
+    assert np.array_equal(a, b), "run-to-run bits differ"
+    assert np.array_equal(gpu_spmv(hinted, c3["x"]), a), "the hint selects the same kernel"
+    assert_close(gpu_spmv(_with_hint(hinted, 100_000), c3["x"]), ref, mag, dtype,
+                 f"entry-balanced kernel rows {lo}..{hi}")
+    assert_close(gpu_spmv(plain, c3["x"], misalign=True), ref, mag, dtype, "streamed kernel, unaligned")
+
+
+@pytest.mark.parametrize("which", ["c2", "c3"])
+def test_unhinted_csr_of_configs_2_and_3_is_bit_reproducible(which):
+    cfg = wl.config2(N=300_001) if which == "c2" else wl.config3(N=100_003)
+    plain = _with_hint(cfg["csr"], 0)
+    dt = plain.vals.dtype
+    ref, mag = oracle.spmv(plain, cfg["x"])
+    a, b = gpu_spmv(plain, cfg["x"], repeat=2)
+    assert_close(a, ref, mag, dt, f"unhinted {which} csr")
     assert np.array_equal(a, b)
-    assert_close(gpu_spmv(plain, c3["x"]), ref, mag, dtype, f"entry-balanced kernel rows {lo}..{hi}")
-    assert_close(gpu_spmv(hinted, c3["x"], misalign=True), ref, mag, dtype, "streamed kernel, unaligned")
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("nnz_mod", [0, 1, 2, 3])
+def test_streamed_kernel_with_long_rows_among_short_ones(dtype, nnz_mod):
+    """Mean row length 8, so the streamed kernel runs, but single rows hold 60, 3000, 9000 and
+    40 000 entries: parts of a row longer than 48 products are added up by the whole wave, whole
+    LDS pieces inside one row are added up in registers. The entry count takes every remainder
+    modulo 4 (the last 16-byte group of the arrays is partial)."""
+    N, M = 12_000, 50_000
+    r, c, v = wl.random_coo_entries(N, M, 40_000 + nnz_mod, seed=70 + nnz_mod, dtype=dtype)
+    rng = np.random.default_rng(71)
+    rows, cols, vals = [r], [c], [v]
+    for row, n in ((3, 60), (700, 3000), (701, 9000), (5000, 40_000), (N - 1, 5000)):
+        keep = rows[0] != row
+        rows[0], cols[0], vals[0] = rows[0][keep], cols[0][keep], vals[0][keep]
+        rows.append(np.full(n, row))
+        cols.append(np.sort(rng.choice(M, n, replace=False)))
+        vals.append(rng.uniform(-1, 1, n).astype(dtype))
+    r, c, v = np.concatenate(rows), np.concatenate(cols), np.concatenate(vals)
+    r, c, v = r[: len(r) - (len(r) - nnz_mod) % 4], c[: len(r) - (len(r) - nnz_mod) % 4], v[: len(r) - (len(r) - nnz_mod) % 4]
+    order = np.lexsort((c, r))
+    spec = wl.csr_from_sorted_coo(N, M, r[order], c[order], v[order])
+    assert len(spec.vals) % 4 == nnz_mod and len(spec.vals) <= 32 * N
+    x = wl.dense_vector(M, 72, dtype)
+    ref, mag = oracle.spmv(spec, x)
+    a, b = gpu_spmv(spec, x, repeat=2)
+    assert_close(a, ref, mag, dtype, "long rows, streamed")
+    assert np.array_equal(a, b)
+    assert_close(gpu_spmv(spec, x, misalign=True), ref, mag, dtype, "long rows, streamed, unaligned")
+    assert_close(gpu_spmv(_with_hint(spec, 40_000), x), ref, mag, dtype, "long rows, entry-balanced")
 
 
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
@@ -199,6 +252,7 @@ def test_unsupported_and_invalid_descriptors_report_errors():
     import paper_1804_10112_amd as spt
     import torch
     c1 = wl.config1(N=64, nnz=100)
+    c1["csr"].levels[1].max_children = 5000     # declared long rows: the kernel that needs a workspace
     A = spt.DeviceTensor(c1["csr"])
     x = torch.zeros(64, dtype=torch.float64, device="cuda")
     y = torch.zeros(64, dtype=torch.float64, device="cuda")
