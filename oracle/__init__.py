@@ -41,8 +41,44 @@ def lib():
     global _lib
     if _lib is None:
         build(force=False)
-        L = C.CDLL(_SO)
+        _lib = _declare(C.CDLL(_SO))
+    return _lib
+
+
+_native = None
+
+
+def lib_native():
+    """The same source built for the machine it runs on, as the CPU baseline is meant to be
+    timed: gcc -O3 -march=native -fopenmp, compiled on first use into a temporary directory
+    (a library built for another CPU must not travel). Falls back to the portable build, with
+    `lib_native.flags` saying which one it is."""
+    global _native
+    if _native is None:
+        import tempfile
+        so = os.path.join(tempfile.mkdtemp(prefix="orc_native_"), "liboracle_native.so")
+        flags = ["-O3", "-march=native", "-fopenmp"]
+        try:
+            subprocess.run(["gcc", *flags, "-std=c11", "-fPIC", "-shared", "-o", so,
+                            os.path.join(_HERE, "oracle.c"), "-lm"], check=True, capture_output=True)
+            _native = _declare(C.CDLL(so))
+            lib_native.flags = " ".join(flags)
+        except Exception:
+            _native = lib()
+            lib_native.flags = "-O2 (portable build; the native build failed)"
+    return _native
+
+
+def set_threads(n: int) -> int:
+    """Threads of the parallel plain loops in the native build; returns the number in effect."""
+    return int(lib_native().orc_set_threads(int(n)))
+
+
+def _declare(L):
+    if True:
         vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int32
+        L.orc_set_threads.restype = i32
+        L.orc_set_threads.argtypes = [i32]
         L.orc_level_children.restype = i64
         L.orc_level_children.argtypes = [vp, i64, i64, i64, vp, vp, i64]
         L.orc_hashed_locate.restype = i64
@@ -105,8 +141,7 @@ def lib():
         L.orc_plain_mttkrp_coo.argtypes = [i64, i64, vp, vp, vp, vp, vp, vp, i32, vp, i32]
         L.orc_plain_mttkrp_csf.restype = None
         L.orc_plain_mttkrp_csf.argtypes = [i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, i32]
-        _lib = L
-    return _lib
+    return L
 
 
 def _ptr(a):
@@ -440,13 +475,13 @@ def mttkrp(spec, Cm, Dm):
 
 # ---- plain per-format loops (native dtype); spec must be the named format ----
 
-def plain_spmv(spec, x, fmt):
+def plain_spmv(spec, x, fmt, native=False):
     x = _same_dtype(spec, x)
     f = _is_f64(spec.vals.dtype)
     N, M = spec.dims
     y = np.zeros(N, spec.vals.dtype)
     lv = spec.levels
-    L = lib()
+    L = lib_native() if native else lib()
     if fmt == "csr":
         L.orc_plain_spmv_csr(N, _ptr(lv[1].pos), _ptr(lv[1].crd), _ptr(spec.vals), _ptr(x), _ptr(y), f)
     elif fmt == "coo":
@@ -461,11 +496,11 @@ def plain_spmv(spec, x, fmt):
     return y
 
 
-def plain_ttv(spec, c, fmt):
+def plain_ttv(spec, c, fmt, native=False):
     c = _same_dtype(spec, c)
     f = _is_f64(spec.vals.dtype)
     lv = spec.levels
-    L = lib()
+    L = lib_native() if native else lib()
     if fmt == "coo":
         nnz = len(spec.vals)
         oi = np.zeros(max(nnz, 1), np.int32)
@@ -480,7 +515,7 @@ def plain_ttv(spec, c, fmt):
     return ov[:nfib]
 
 
-def plain_mttkrp(spec, Cm, Dm, fmt):
+def plain_mttkrp(spec, Cm, Dm, fmt, native=False):
     Cm = _same_dtype(spec, Cm)
     Dm = _same_dtype(spec, Dm)
     f = _is_f64(spec.vals.dtype)
@@ -488,7 +523,7 @@ def plain_mttkrp(spec, Cm, Dm, fmt):
     I = spec.dims[0]
     A = np.zeros((I, J), spec.vals.dtype)
     lv = spec.levels
-    L = lib()
+    L = lib_native() if native else lib()
     if fmt == "coo":
         L.orc_plain_mttkrp_coo(len(spec.vals), I, _ptr(lv[0].crd), _ptr(lv[1].crd), _ptr(lv[2].crd),
                                _ptr(spec.vals), _ptr(Cm), _ptr(Dm), J, _ptr(A), f)

@@ -814,11 +814,32 @@ void orc_mttkrp(const orc_tensor* B, const void* C, const void* D, int32_t J,
 /* Part 3: plain loop nests per format, native dtype                   */
 /* ------------------------------------------------------------------ */
 
+/* The loops whose iterations write disjoint outputs (rows, fibres, slices) carry an OpenMP
+ * pragma that takes effect only in the build with -fopenmp (the all-cores leg of the CPU
+ * baseline); each iteration's arithmetic and its order of additions are the same either
+ * way. The scatter loops (COO SpMV, COO MTTKRP, COO TTV's append) stay serial: the paper's
+ * generated code is a single loop over the stored entries there. */
+#ifdef _OPENMP
+#include <omp.h>
+#define ORC_PARALLEL_FOR _Pragma("omp parallel for schedule(static)")
+int32_t orc_set_threads(int32_t n) {
+  if (n > 0) omp_set_num_threads(n);
+  return omp_get_max_threads();
+}
+#else
+#define ORC_PARALLEL_FOR
+int32_t orc_set_threads(int32_t n) {
+  (void)n;
+  return 1;
+}
+#endif
+
 #define PLAIN_SPMV_CSR(TY)                                              \
   {                                                                     \
     const TY* v = (const TY*)vals;                                      \
     const TY* xv = (const TY*)x;                                        \
     TY* yv = (TY*)y;                                                    \
+    ORC_PARALLEL_FOR                                                    \
     for (int64_t i = 0; i < N; ++i) {                                   \
       TY s = 0;                                                         \
       for (int32_t p = pos[i]; p < pos[i + 1]; ++p) s += v[p] * xv[crd[p]]; \
@@ -853,6 +874,7 @@ void orc_plain_spmv_coo(int64_t N, int64_t nnz, const int32_t* row,
     for (int64_t d = 0; d < K; ++d) {                                   \
       int64_t off = offset[d];                                          \
       int64_t lo = imax(0, -off), hi = imin(N, M - off);                \
+      ORC_PARALLEL_FOR                                                  \
       for (int64_t i = lo; i < hi; ++i) yv[i] += v[d * N + i] * xv[i + off]; \
     }                                                                   \
   }
@@ -867,11 +889,13 @@ void orc_plain_spmv_dia(int64_t N, int64_t M, int64_t K, const int32_t* offset,
     const TY* xv = (const TY*)x;                                        \
     TY* yv = (TY*)y;                                                    \
     for (int64_t i = 0; i < N; ++i) yv[i] = 0;                          \
-    for (int64_t k = 0; k < W; ++k)                                     \
+    for (int64_t k = 0; k < W; ++k) {                                   \
+      ORC_PARALLEL_FOR                                                  \
       for (int64_t i = 0; i < N; ++i) {                                 \
         int32_t j = crd[k * N + i];                                     \
         if (j >= 0) yv[i] += v[k * N + i] * xv[j];                      \
       }                                                                 \
+    }                                                                   \
   }
 void orc_plain_spmv_ell(int64_t N, int64_t W, const int32_t* crd,
                         const void* vals, const void* x, void* y, int32_t is_f64) {
@@ -911,6 +935,7 @@ int64_t orc_plain_ttv_coo(int64_t nnz, const int32_t* ci, const int32_t* cj,
     const TY* v = (const TY*)vals;                                      \
     const TY* cv = (const TY*)c;                                        \
     TY* ov = (TY*)out_v;                                                \
+    ORC_PARALLEL_FOR                                                    \
     for (int64_t f = 0; f < nfib; ++f) {                                \
       TY s = 0;                                                         \
       for (int32_t p = pos2[f]; p < pos2[f + 1]; ++p) s += v[p] * cv[crd2[p]]; \
@@ -950,9 +975,10 @@ void orc_plain_mttkrp_coo(int64_t nnz, int64_t dim0, const int32_t* ci,
     const TY* Cv = (const TY*)C;                                        \
     const TY* Dv = (const TY*)D;                                        \
     TY* Av = (TY*)A;                                                    \
-    TY* t = (TY*)malloc(sizeof(TY) * (size_t)J);                        \
     for (int64_t q = 0; q < dim0 * J; ++q) Av[q] = 0;                   \
+    ORC_PARALLEL_FOR                                                    \
     for (int32_t p0 = pos0[0]; p0 < pos0[1]; ++p0) {                    \
+      TY t[1024]; /* J <= 1024 */                                       \
       TY* ar = Av + (int64_t)crd0[p0] * J;                              \
       for (int32_t p1 = pos1[p0]; p1 < pos1[p0 + 1]; ++p1) {            \
         const TY* cr = Cv + (int64_t)crd1[p1] * J;                      \
@@ -964,7 +990,6 @@ void orc_plain_mttkrp_coo(int64_t nnz, int64_t dim0, const int32_t* ci,
         for (int32_t j = 0; j < J; ++j) ar[j] += cr[j] * t[j];          \
       }                                                                 \
     }                                                                   \
-    free(t);                                                            \
   }
 void orc_plain_mttkrp_csf(int64_t dim0, const int32_t* pos0, const int32_t* crd0,
                           const int32_t* pos1, const int32_t* crd1,

@@ -194,6 +194,9 @@ void orc_mttkrp(const orc_tensor* B, const void* C, const void* D, int32_t J,
 /* ---- plain per-format loop nests (what the paper's generated code does,
  * Section 5.2 / 5.3), native dtype, single thread. Timed as the CPU baseline
  * and cross-checked against the definitions above. ---- */
+/* Threads used by the loops above that are parallel over disjoint outputs: effective only in
+ * the build with -fopenmp (n <= 0 leaves the setting alone); returns the number in effect. */
+int32_t orc_set_threads(int32_t n);
 void orc_plain_spmv_csr(int64_t N, const int32_t* pos, const int32_t* crd,
                         const void* vals, const void* x, void* y, int32_t is_f64);
 void orc_plain_spmv_coo(int64_t N, int64_t nnz, const int32_t* row,

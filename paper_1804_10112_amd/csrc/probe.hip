@@ -25,8 +25,24 @@ template <typename T>
 __global__ __launch_bounds__(kBlock) void probe_gather_kernel(const int32_t* __restrict__ idx,
                                                               int64_t n, const T* __restrict__ table,
                                                               T* __restrict__ out) {
-  const int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (p < n) out[p] = table[__builtin_nontemporal_load(idx + p)];
+  // four independent gathers per lane, all issued before the first store: a kernel that keeps
+  // several gathers in flight per lane must not be able to outrun its own yardstick
+  constexpr int IPT = 4;
+  const int64_t base = (int64_t)blockIdx.x * kBlock * IPT + threadIdx.x;
+  int32_t j[IPT];
+  T v[IPT];
+#pragma unroll
+  for (int k = 0; k < IPT; ++k) {
+    const int64_t p = base + (int64_t)k * kBlock;
+    j[k] = p < n ? __builtin_nontemporal_load(idx + p) : 0;
+  }
+#pragma unroll
+  for (int k = 0; k < IPT; ++k) v[k] = table[j[k]];
+#pragma unroll
+  for (int k = 0; k < IPT; ++k) {
+    const int64_t p = base + (int64_t)k * kBlock;
+    if (p < n) __builtin_nontemporal_store(v[k], out + p);
+  }
 }
 
 }  // namespace spt
@@ -65,7 +81,7 @@ extern "C" spt_status spt_probe_gather(const int32_t* idx, int64_t n, const void
   if (!idx || !table || !out || n < 0)
     return fail(SPT_ERR_INVALID_ARG, "probe_gather: null argument or negative count");
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const unsigned grid = (unsigned)((n + kBlock - 1) / kBlock);
+  const unsigned grid = (unsigned)((n + 4 * kBlock - 1) / (4 * kBlock));
   if (grid == 0) return SPT_OK;
   if (dtype == SPT_F64)
     hipLaunchKernelGGL(probe_gather_kernel<double>, dim3(grid), dim3(kBlock), 0, s, idx, n,

@@ -137,5 +137,7 @@ def test_invalid_and_unsupported_descriptors():
     assert _status(spt.spt_mttkrp, _host_desc(c1["coo"]), 0x1000, 0x1000, 4, 0x1000, None, 0)[0] == B.SPT_ERR_UNSUPPORTED
     assert _status(spt.spt_ttv, t5, 0x1000, None, None, 0x1000, None, None, 0)[0] == B.SPT_ERR_INVALID_ARG
     # workspace too small is diagnosed before anything is launched
-    st, msg = _status(spt.spt_spmv, _host_desc(c1["csr"]), 0x1000, 0x1000, None, 0)
+    t = _host_desc(c1["csr"])
+    t.level[1].max_children = 100_000       # declared long rows: the entry-balanced kernel and its carries
+    st, msg = _status(spt.spt_spmv, t, 0x1000, 0x1000, None, 0)
     assert st == B.SPT_ERR_WORKSPACE and "workspace" in msg

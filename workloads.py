@@ -562,7 +562,7 @@ def config4(N=4_000_000, nnz_target=60_000_000, max_row=200_000, zipf=1.8,
     vals = _values(rng, len(row), dtype, "u11")
     x = dense_vector(M, seed + 1000, dtype, "u11")
     out = {"coo": coo_spec(N, M, row, col, vals, ordered=False, name="c4-coo"),
-           "x": x, "nnz": len(row)}
+           "x": x, "nnz": len(row), "max_row_len": int(L.max())}
     if with_sorted:                       # the same entries in (row, col) order
         vs = np.empty_like(vals)
         vs[perm] = vals
