@@ -95,3 +95,59 @@ def test_power_law_scaled_config4(order):
     c4 = wl.config4(N=50_000, nnz_target=700_000, max_row=30_000)
     coo = c4["coo"]
     _check(50_000, 50_000, coo.levels[0].crd, coo.levels[1].crd, coo.vals, order, what="c4 scaled")
+
+
+# ---- sizes, input orders and duplicate patterns that stress any sort implementation ----
+
+@pytest.mark.parametrize("nnz", [6143, 6144, 6145, 20_000, 524_288, 524_289, 1_300_000])
+def test_sizes_from_thousands_to_a_million(nnz):
+    N, M = 90_000, 70_000
+    r, c, v = wl.random_coo_entries(N, M, nnz, seed=300 + nnz % 97, dtype=np.float64, sort=False)
+    _check(N, M, r, c, v, 0, what=f"nnz={nnz}")
+
+
+@pytest.mark.parametrize("order", [0, 1])
+@pytest.mark.parametrize("kind", ["sorted", "reversed", "by_column", "interleaved"])
+def test_unordered_flagged_input_in_special_orders(kind, order):
+    """Input flagged unordered that is in fact sorted, reversed, column-major, or a regular
+    interleaving of 170 sorted runs."""
+    N, M, nnz = 3000, 5000, 700_000
+    r, c, v = wl.random_coo_entries(N, M, nnz, seed=41, dtype=np.float32, sort=True)
+    if kind == "reversed":
+        r, c, v = r[::-1].copy(), c[::-1].copy(), v[::-1].copy()
+    elif kind == "by_column":
+        o = np.lexsort((r, c))
+        r, c, v = r[o], c[o], v[o]
+    elif kind == "interleaved":
+        stride = len(v) // 4096
+        o = np.concatenate([np.arange(len(v))[i::stride] for i in range(stride)])
+        r, c, v = r[o], c[o], v[o]
+    _check(N, M, r, c, v, order, what=kind)
+
+
+@pytest.mark.parametrize("order", [0, 1])
+def test_many_copies_of_one_coordinate_keep_their_input_order(order):
+    """20 000 entries share one (row, col) pair and 9 000 another, scattered through the input."""
+    N, M = 4000, 4000
+    r, c, v = wl.random_coo_entries(N, M, 300_000, seed=43, dtype=np.float64, sort=False)
+    rng = np.random.default_rng(44)
+    r = np.concatenate([r, np.full(20_000, 1234), np.full(9_000, 77)])
+    c = np.concatenate([c, np.full(20_000, 999), np.full(9_000, 3)])
+    p = rng.permutation(len(r))
+    r, c = r[p], c[p]
+    v = np.arange(len(r), dtype=np.float64)            # values identify the input position
+    _check(N, M, r, c, v, order, what="heavy duplicates")
+    keep = slice(0, 200_000)
+    _check(N, M, r[keep], c[keep], v[keep].astype(np.float32), order, what="heavy duplicates, fp32")
+
+
+@pytest.mark.parametrize("order", [0, 1])
+def test_one_row_holds_most_entries_and_columns_use_31_bits(order):
+    rng = np.random.default_rng(45)
+    M = 2**31 - 10
+    n = 900_000
+    r = rng.integers(0, 5000, n)
+    r[: 2 * n // 3] = 4321                               # one row with 600 000 entries
+    c = rng.integers(0, M, n)
+    p = rng.permutation(n)
+    _check(5000, M, r[p], c[p], rng.uniform(-1, 1, n), order, what="heavy row, 31-bit columns")
