@@ -6,6 +6,8 @@
 // over ordered non-unique levels (Section 4.3): (i,j) fibers for TTV, i slices
 // for MTTKRP. Work is split evenly over stored entries; a run cut by a split
 // leaves a carry that a follow-up kernel adds in a fixed order (no atomics).
+#include <algorithm>
+
 #include "common.hpp"
 #include "scan.hpp"
 #include "segreduce.hpp"
@@ -324,7 +326,24 @@ __global__ __launch_bounds__(kBlock) void csf_chunk_bounds_kernel(
   out[3 * c + 2] = f >= nfibers ? nslices : sl;
 }
 
-template <typename T, int G, int MODE>
+// Broadcast of lane (addr / 4)'s value through the LDS crossbar.
+__device__ __forceinline__ int32_t bperm(int addr, int32_t v) { return __builtin_amdgcn_ds_bpermute(addr, v); }
+__device__ __forceinline__ float bperm(int addr, float v) {
+  return __int_as_float(__builtin_amdgcn_ds_bpermute(addr, __float_as_int(v)));
+}
+__device__ __forceinline__ double bperm(int addr, double v) {
+  const int lo = __builtin_amdgcn_ds_bpermute(addr, __double2loint(v));
+  const int hi = __builtin_amdgcn_ds_bpermute(addr, __double2hiint(v));
+  return __hiloint2double(hi, lo);
+}
+
+// FAST: the factor matrices are addressed with 32-bit byte offsets formed by one 24-bit
+// multiply-add (host-checked: dimensions and J * sizeof(T) below 2^23, matrices below 4 GiB),
+// and no load of the batch sits behind a branch: a batch slot beyond the group's entries
+// repeats the last entry, a lane beyond column J reads column J - 1 (neither is ever stored).
+// The 64-bit multiply-adds and the per-entry branches of the general path cost more vector
+// instructions than the arithmetic itself.
+template <typename T, int G, int MODE, bool FAST>
 __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
     int n, int J,
     // COO: ci/ck/cl; CSF: cl only (crd of level 2) plus the upper levels below
@@ -355,6 +374,11 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
   const int g = tid / G, gl = tid % G;
   const int j = blockIdx.y * G + gl;
   const bool jok = j < J;
+  // FAST: byte address of lane 0 of this lane's group for the broadcasts, bytes per factor
+  // row and this lane's byte offset inside a row
+  const int half_base = 4 * (lane_id() & ~(G - 1));
+  const uint32_t jbytes = static_cast<uint32_t>(J) * sizeof(T);
+  const uint32_t joff = static_cast<uint32_t>(min(j, J - 1)) * sizeof(T);
   const int chunk = xcd_contiguous_block_id();
   const int chunk_base = chunk * CHUNK;
   const int chunk_end = min(chunk_base + CHUNK, n);
@@ -462,10 +486,28 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
       for (int u = 0; u < kU; ++u) {
         const int sidx = s0 + u;  // < G because kU divides G
         const bool live = sidx < cntb;
-        ii[u] = __shfl(ri, sidx, G);
         fh[u] = false;
         vv[u] = T(1);
         fb[u] = T(1);
+        if (FAST && MODE != MT_LEVEL2) {
+          const int addr = half_base + 4 * min(sidx, cntb - 1);
+          ii[u] = bperm(addr, ri);
+          const int k = bperm(addr, rk);
+          vv[u] = bperm(addr, rv);
+          const int l = MODE != MT_SPDM ? bperm(addr, rl) : 0;
+          fa[u] = *reinterpret_cast<const T*>(reinterpret_cast<const char*>(Cm) + (__umul24(k, jbytes) + joff));
+          if (MODE != MT_SPDM)
+            fb[u] = *reinterpret_cast<const T*>(reinterpret_cast<const char*>(Dm) + (__umul24(l, jbytes) + joff));
+          if (MODE == MT_CSF) {  // C[k,:] is used where a new (i,k) fiber piece starts
+            fh[u] = live && (ii[u] != pi || k != pk);
+            if (live) {
+              pi = ii[u];
+              pk = k;
+            }
+          }
+          continue;
+        }
+        ii[u] = __shfl(ri, sidx, G);
         if (MODE == MT_LEVEL2) {
           fa[u] = (live && jok) ? in_vec[(int64_t)(b0 + sidx) * J + j] : T(0);
         } else {
@@ -619,7 +661,7 @@ size_t mttkrp_workspace(Format, const spt_tensor* B, int32_t J) {
 // rows_override / cols_override (SpDM mode only): row and column index per stored entry taken
 // from these arrays instead of B's first two levels, and no zero fill of A (every output row
 // then has at least one entry, and rows with entries are stored, not accumulated).
-template <typename T, int G>
+template <typename T, int G, bool FAST>
 static spt_status mttkrp_launch(Format f, const spt_tensor* B, const T* Cm, const T* Dm, int J,
                                 T* A, void* ws, size_t ws_bytes, hipStream_t s,
                                 const int32_t* rows_override = nullptr,
@@ -650,13 +692,13 @@ static spt_status mttkrp_launch(Format f, const spt_tensor* B, const T* Cm, cons
   const unsigned jt = (unsigned)((J + G - 1) / G);
   const spt_level* L = B->level;
   if (f == Format::COO2) {  // SpDM: the same slice reduction with one dense factor
-    hipLaunchKernelGGL((mttkrp_kernel<T, G, MT_SPDM>), dim3(n1, jt), dim3(kBlock), 0, s, nnz, J,
+    hipLaunchKernelGGL((mttkrp_kernel<T, G, MT_SPDM, FAST>), dim3(n1, jt), dim3(kBlock), 0, s, nnz, J,
                        rows_override ? rows_override : L[0].crd,
                        cols_override ? cols_override : L[1].crd, nullptr,
                        static_cast<const T*>(B->vals), Cm, nullptr, nullptr, nullptr, nullptr, nullptr,
                        0, 0, nullptr, nullptr, A, key1, vec1);
   } else if (f == Format::COO3) {
-    hipLaunchKernelGGL((mttkrp_kernel<T, G, MT_COO>), dim3(n1, jt), dim3(kBlock), 0, s, nnz, J,
+    hipLaunchKernelGGL((mttkrp_kernel<T, G, MT_COO, FAST>), dim3(n1, jt), dim3(kBlock), 0, s, nnz, J,
                        L[0].crd, L[1].crd, L[2].crd, static_cast<const T*>(B->vals), Cm, Dm, nullptr,
                        nullptr, nullptr, nullptr, 0, 0, nullptr, nullptr, A, key1, vec1);
   } else {
@@ -667,13 +709,13 @@ static spt_status mttkrp_launch(Format f, const spt_tensor* B, const T* Cm, cons
     hipLaunchKernelGGL(csf_chunk_bounds_kernel, dim3((n1 + 1 + kBlock - 1) / kBlock), dim3(kBlock), 0, s,
                        n1, CHUNK, (int)nsl, (int)nfib, L[1].pos, L[2].pos, bounds);
     SPT_CHECK_LAUNCH("csf chunk bounds");
-    hipLaunchKernelGGL((mttkrp_kernel<T, G, MT_CSF>), dim3(n1, jt), dim3(kBlock), 0, s, nnz, J,
+    hipLaunchKernelGGL((mttkrp_kernel<T, G, MT_CSF, FAST>), dim3(n1, jt), dim3(kBlock), 0, s, nnz, J,
                        nullptr, nullptr, L[2].crd, static_cast<const T*>(B->vals), Cm, Dm, L[0].crd,
                        L[1].pos, L[1].crd, L[2].pos, (int)nsl, (int)nfib, bounds, nullptr, A, key1,
                        vec1);
   }
   SPT_CHECK_LAUNCH("mttkrp");
-  hipLaunchKernelGGL((mttkrp_kernel<T, G, MT_LEVEL2>), dim3(n2, jt), dim3(kBlock), 0, s, n1, J,
+  hipLaunchKernelGGL((mttkrp_kernel<T, G, MT_LEVEL2, false>), dim3(n2, jt), dim3(kBlock), 0, s, n1, J,
                      nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
                      nullptr, 0, 0, key1, vec1, A, key2, vec2);
   SPT_CHECK_LAUNCH("mttkrp level 2");
@@ -691,11 +733,24 @@ static spt_status mttkrp_typed(Format f, const spt_tensor* B, const void* C, con
                                const int32_t* cols_override = nullptr) {
   const T* Cm = static_cast<const T*>(C);
   const T* Dm = static_cast<const T*>(D);
-  if (mttkrp_group(J) == 32)
-    return mttkrp_launch<T, 32>(f, B, Cm, Dm, J, static_cast<T*>(A), ws, ws_bytes, s, rows_override,
-                                cols_override);
-  return mttkrp_launch<T, 64>(f, B, Cm, Dm, J, static_cast<T*>(A), ws, ws_bytes, s, rows_override,
-                              cols_override);
+  // 32-bit factor addressing: every coordinate and the row size below 2^23 (one 24-bit multiply),
+  // every factor matrix below 4 GiB
+  int64_t big = 0;  // the largest dimension bounds every coordinate that indexes a factor row
+  for (int k = 0; k < B->nlevels; ++k) big = std::max(big, B->level[k].N);
+  const int64_t rowb = (int64_t)J * (int64_t)sizeof(T);
+  const bool fast = big < (1 << 23) && rowb < (1 << 23) && big * rowb < ((int64_t)1 << 32);
+  if (mttkrp_group(J) == 32) {
+    if (fast)
+      return mttkrp_launch<T, 32, true>(f, B, Cm, Dm, J, static_cast<T*>(A), ws, ws_bytes, s, rows_override,
+                                        cols_override);
+    return mttkrp_launch<T, 32, false>(f, B, Cm, Dm, J, static_cast<T*>(A), ws, ws_bytes, s, rows_override,
+                                       cols_override);
+  }
+  if (fast)
+    return mttkrp_launch<T, 64, true>(f, B, Cm, Dm, J, static_cast<T*>(A), ws, ws_bytes, s, rows_override,
+                                      cols_override);
+  return mttkrp_launch<T, 64, false>(f, B, Cm, Dm, J, static_cast<T*>(A), ws, ws_bytes, s, rows_override,
+                                     cols_override);
 }
 
 // SpDM A = B C (Section 5.2, Figure 11): B an ordered COO matrix, C and A dense row-major.
