@@ -223,7 +223,7 @@ def build_items(args):
         N, nnz = c3["csr"].dims[0], c3["nnz"]
         A = spt.DeviceTensor(c3["csr"])
         y = torch.empty(N, dtype=torch.float32, device=dev)
-        ws = A.workspace(spt.SPT_OP_SPMV)
+        ws = A.workspace(spt.SPT_OP_SPMV_SPARSE_X)
         keep.extend([A, y, ws])
         for dens in (1e-4, 1e-2, 0.5):
             nx = max(1, int(N * dens))
@@ -286,7 +286,7 @@ def build_items(args):
         Am = spt.DeviceTensor(wl.coo_spec(N3, N3, r3, q3, v3))
         Cd = up(np.random.default_rng(10).uniform(0, 1, (N3, 32)).astype(np.float32))
         Ad = torch.empty(N3, 32, dtype=torch.float32, device=dev)
-        w5 = Am.workspace(spt.SPT_OP_MTTKRP, 32)
+        w5 = Am.workspace(spt.SPT_OP_SPDM, 32)
         keep.extend([Am, Ad, w5])
         items.append(Item("n2_spdm_coo", lambda: spt.spt_spdm(Am, Cd, 32, Ad, w5), 2 * 32 * nnz3,
                           12 * nnz3 + 2 * 4 * 32 * N3, "compulsory HBM bytes; rows of C are gathered from cache"))

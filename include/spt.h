@@ -18,7 +18,8 @@
  * conditions are diagnosed (null pointers, unknown level kinds, illegal
  * kind/property combinations per Table 1, level compositions that are not
  * recognised, sizes that overflow int32 positions, workspace too small).
- * Device-side content (monotone pos, in-range crd) is NOT validated.
+ * Device-side content (monotone pos, in-range crd) is NOT validated by the
+ * operations themselves; spt_validate() checks it on request.
  * spt_last_error() returns a thread-local human readable message for the
  * last failing call on this thread.
  */
@@ -75,7 +76,10 @@ typedef enum {
   SPT_OP_TO_CSF = 6,
   SPT_OP_TO_ELL = 7,
   SPT_OP_DIA_OFFSETS = 8,
-  SPT_OP_TO_COO = 9
+  SPT_OP_TO_COO = 9,
+  SPT_OP_SPMV_SPARSE_X = 10, /* spt_spmv_sparse_x: query on A */
+  SPT_OP_SPDM = 11           /* spt_spdm: query on B with J */
+  /* spt_add / spt_mul size their workspace from BOTH operands: spt_add_workspace_bytes(B, C) */
 } spt_op;
 
 /*
@@ -218,7 +222,7 @@ spt_status spt_spmv_static(const spt_tensor* A, const void* x, void* y, void* st
  *                  at or after i % W, probing linearly with wrap (locate, Table 2)
  * x.nvals = number of entries of x's vals (nnz_x or W); same dtype as A.
  * Every stored entry of A locates its column in x; absent coordinates count as
- * 0. y is overwritten. Workspace as for spt_spmv on A.
+ * 0. y is overwritten. Workspace: SPT_OP_SPMV_SPARSE_X on A.
  */
 spt_status spt_spmv_sparse_x(const spt_tensor* A, const spt_tensor* x, void* y, void* ws,
                              size_t ws_bytes, void* stream);
@@ -260,8 +264,7 @@ spt_status spt_mttkrp(const spt_tensor* B, const void* C, const void* D,
 /*
  * SpDM, A = B C (Section 5.2, Figure 11): B an ordered COO matrix (N x M), C dense
  * M x J, A_out dense N x J, both row-major; A_out is OVERWRITTEN (rows of B
- * without entries give zero rows). 1 <= J <= 1024. Workspace: query with
- * SPT_OP_MTTKRP on B and the same J (the kernels are shared with spt_mttkrp).
+ * without entries give zero rows). 1 <= J <= 1024. Workspace: SPT_OP_SPDM with J.
  */
 spt_status spt_spdm(const spt_tensor* B, const void* C, int32_t J, void* A_out, void* ws,
                     size_t ws_bytes, void* stream);
@@ -398,6 +401,22 @@ size_t spt_add_workspace_bytes(const spt_tensor* B, const spt_tensor* C);
  */
 spt_status spt_mul_dense(const spt_tensor* B, const void* D, int64_t ld, void* out_vals, void* stream);
 spt_status spt_add_to_dense(const spt_tensor* B, const spt_tensor* C, void* A, int64_t ld, void* stream);
+
+/*
+ * Device-side check of the CONTENT of T's level arrays (Section 3.1), which every other entry
+ * point takes on trust: pos of each compressed level starts at 0, never decreases and ends at
+ * the number of positions of its level (so the declared M of the level below is right);
+ * stored coordinates lie in [0, N) (-1 is allowed where it marks padding: singleton and
+ * hashed levels); inside every segment of a compressed level flagged SPT_ORDERED the
+ * coordinates ascend (strictly if also SPT_UNIQUE); a COO tensor flagged ordered on all levels
+ * is in lexicographic order; every DIA offset leaves at least one cell inside the matrix.
+ * T: any composition spt_spmv / spt_to_coo accept. err_dev: two DEVICE int32: [0] receives the
+ * number of violations found, [1] the OR of their kinds (SPT_BAD_*). Enqueues a few small
+ * kernels and returns without synchronising; needs no workspace. Host-checkable problems are
+ * reported through the status as everywhere else.
+ */
+enum { SPT_BAD_POS = 1, SPT_BAD_POS_END = 2, SPT_BAD_CRD = 4, SPT_BAD_ORDER = 8, SPT_BAD_OFFSET = 16 };
+spt_status spt_validate(const spt_tensor* T, int32_t* err_dev, void* stream);
 
 /* Workspace size in bytes for `op` on tensor T (J only for MTTKRP and TTM).
  * Returns 0 for invalid descriptors (spt_last_error says why). Never fails for

@@ -19,6 +19,7 @@ _lib = None
 SPT_OK, SPT_ERR_INVALID_ARG, SPT_ERR_UNSUPPORTED, SPT_ERR_WORKSPACE, SPT_ERR_DEVICE = range(5)
 SPT_OP_SPMV, SPT_OP_COO_TO_CSR, SPT_OP_TTV, SPT_OP_MTTKRP, SPT_OP_INNERPROD, SPT_OP_TTM = range(6)
 SPT_OP_TO_CSF, SPT_OP_TO_ELL, SPT_OP_DIA_OFFSETS, SPT_OP_TO_COO = 6, 7, 8, 9
+SPT_OP_SPMV_SPARSE_X, SPT_OP_SPDM = 10, 11
 SPT_ORDER_ROW_COL, SPT_ORDER_ROW_STABLE = 0, 1
 SPT_ORDERED, SPT_UNIQUE = 1, 2
 SPT_F32, SPT_F64 = 0, 1
@@ -28,7 +29,7 @@ SYMBOLS = ["spt_spmv", "spt_coo_to_csr", "spt_ttv", "spt_mttkrp", "spt_workspace
            "spt_last_error", "spt_version", "spt_probe_read", "spt_probe_gather",
            "spt_spmv_sparse_x", "spt_spdm", "spt_innerprod", "spt_ttm",
            "spt_add", "spt_mul", "spt_add_workspace_bytes", "spt_mul_dense", "spt_add_to_dense", "spt_coo3_to_csf", "spt_to_ell",
-           "spt_coo_dia_offsets", "spt_coo_to_dia", "spt_to_coo", "spt_to_hashed_rows", "spt_spmv_static"]
+           "spt_coo_dia_offsets", "spt_coo_to_dia", "spt_to_coo", "spt_to_hashed_rows", "spt_spmv_static", "spt_validate"]
 
 
 class SptLevel(C.Structure):
@@ -65,6 +66,8 @@ def lib():
         vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
         L.spt_spmv.restype = i32
         L.spt_spmv.argtypes = [vp, vp, vp, vp, sz, vp]
+        L.spt_validate.restype = i32
+        L.spt_validate.argtypes = [vp, vp, vp]
         L.spt_spmv_static.restype = i32
         L.spt_spmv_static.argtypes = [vp, vp, vp, vp]
         L.spt_spmv_sparse_x.restype = i32
@@ -169,6 +172,13 @@ def spt_workspace_bytes(op, T, J=0) -> int:
 def spt_spmv(A, x, y, ws=None, stream=None):
     p, n = _ws(ws)
     _check(lib().spt_spmv(_desc(A), _p(x), _p(y), p, n, _stream(stream)))
+
+
+SPT_BAD_POS, SPT_BAD_POS_END, SPT_BAD_CRD, SPT_BAD_ORDER, SPT_BAD_OFFSET = 1, 2, 4, 8, 16
+
+
+def spt_validate(T, err_dev, stream=None):
+    _check(lib().spt_validate(_desc(T), _p(err_dev), _stream(stream)))
 
 
 def spt_spmv_static(A, x, y, stream=None):

@@ -85,6 +85,8 @@ spt_status mul_dense_dispatch(const spt_tensor* B, const void* D, int64_t ld, vo
 spt_status add_to_dense_dispatch(const spt_tensor* B, const spt_tensor* C, void* A, int64_t ld,
                                  hipStream_t s);
 
+spt_status validate_dispatch(const spt_tensor* T, int32_t* err, hipStream_t s);
+
 static bool is(const spt_level& L, int kind) { return L.kind == kind; }
 static bool unique(const spt_level& L) { return (L.flags & SPT_UNIQUE) != 0; }
 
@@ -353,6 +355,16 @@ spt_status spt_spmv(const spt_tensor* A, const void* x, void* y, void* ws, size_
   if (f == Format::BCSR)
     return bcsr_spmv_dispatch(A, x, y, ws, ws_bytes, static_cast<hipStream_t>(stream));
   return spmv_dispatch(f, A, x, y, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+spt_status spt_validate(const spt_tensor* T, int32_t* err_dev, void* stream) {
+  clear_error();
+  Format f = recognize(T);
+  if (f == Format::Invalid) return SPT_ERR_INVALID_ARG;
+  if (f == Format::Unsupported && !generic_ok(T)) return SPT_ERR_UNSUPPORTED;
+  clear_error();
+  if (!err_dev) return fail(SPT_ERR_INVALID_ARG, "validate: err_dev is null");
+  return validate_dispatch(T, err_dev, static_cast<hipStream_t>(stream));
 }
 
 spt_status spt_spmv_sparse_x(const spt_tensor* A, const spt_tensor* x, void* y, void* ws,
@@ -688,6 +700,12 @@ size_t spt_workspace_bytes(int32_t op, const spt_tensor* T, int32_t J) {
   }
   size_t n = 0;
   switch (op) {
+    case SPT_OP_SPMV_SPARSE_X:
+      n = f == Format::CSR ? seg_spmv_workspace(T->nvals) : 0;
+      break;
+    case SPT_OP_SPDM:
+      n = f == Format::COO2 ? mttkrp_workspace(f, T, J) : 0;
+      break;
     case SPT_OP_SPMV:
       if (f == Format::CSR || (f == Format::COO2 && (T->level[0].flags & SPT_ORDERED)))
         n = seg_spmv_workspace(T->nvals);

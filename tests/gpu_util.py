@@ -90,7 +90,7 @@ def gpu_spmv_sparse_x(spec, xspec):
     A = spt.DeviceTensor(spec)
     X = spt.DeviceTensor(xspec)
     y = torch.full((spec.dims[0],), float("nan"), dtype=A.torch_dtype, device="cuda")
-    spt.spt_spmv_sparse_x(A, X, y, A.workspace(spt.SPT_OP_SPMV))
+    spt.spt_spmv_sparse_x(A, X, y, A.workspace(spt.SPT_OP_SPMV_SPARSE_X))
     torch.cuda.synchronize()
     return y.cpu().numpy()
 
@@ -102,7 +102,7 @@ def gpu_spdm(spec, Cm):
     Cd = torch.from_numpy(np.ascontiguousarray(Cm)).cuda()
     J = Cm.shape[1]
     A = torch.full((spec.dims[0], J), float("nan"), dtype=B.torch_dtype, device="cuda")
-    spt.spt_spdm(B, Cd, J, A, B.workspace(spt.SPT_OP_MTTKRP, J))
+    spt.spt_spdm(B, Cd, J, A, B.workspace(spt.SPT_OP_SPDM, J))
     torch.cuda.synchronize()
     return A.cpu().numpy()
 

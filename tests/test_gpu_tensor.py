@@ -163,3 +163,20 @@ def test_csf_with_empty_fibres_and_slices(dtype, nnz, extra):
     full = np.diff(p2) > 0
     assert n == len(full) and np.all(ov[~full] == 0)
     assert_close(ov[full], rv, rm, dtype, "ttv csf with gaps")
+
+
+def test_mttkrp_with_a_dimension_beyond_24_bits_takes_the_general_addressing():
+    """Coordinates from 2^23 on do not fit the 24-bit multiply of the fast factor addressing."""
+    dims = (70, 9_000_000, 50)
+    rng = np.random.default_rng(8)
+    n = 30_000
+    key = np.unique(rng.integers(0, 70, n) * (9_000_000 * 50) + rng.integers(8_900_000, 9_000_000, n) * 50
+                    + rng.integers(0, 50, n))
+    ci, ck, cl = key // (9_000_000 * 50), (key // 50) % 9_000_000, key % 50
+    v = rng.uniform(0, 1, len(key)).astype(np.float32)
+    coo = wl.coo3_spec(dims, ci, ck, cl, v)
+    csf = wl.csf3_from_sorted_coo(dims, ci, ck, cl, v)
+    Cm = np.zeros((dims[1], 4), np.float32)
+    Cm[8_900_000:] = rng.uniform(0, 1, (100_000, 4)).astype(np.float32)
+    Dm = rng.uniform(0, 1, (dims[2], 4)).astype(np.float32)
+    _check_mttkrp(coo, csf, Cm, Dm, "mttkrp, 9M-row factor")
