@@ -73,11 +73,23 @@ __device__ __forceinline__ SegSum<A> block_seg_exclusive_scan(SegSum<A> me,
 // Adds the carries to y. Carries of one row are consecutive; the thread at the
 // start of a run adds the whole run in order (deterministic). The sum of a run
 // is formed in double also for float data.
+// A choice between two kernels made on the device: an earlier kernel writes kSelectFlags flags,
+// both candidates are launched, and each runs only if "any flag set" equals its `want`.
+constexpr int kSelectFlags = 64;  // one per lane of a wave
+__device__ __forceinline__ bool selected(const int32_t* __restrict__ select, int want) {
+  if (!select) return true;
+  const int any = __ballot(select[threadIdx.x & (kSelectFlags - 1)] != 0) != 0;
+  return any == want;
+}
+
 template <typename T>
 __global__ __launch_bounds__(kBlock) void carry_fixup_kernel(int n,
                                                              const int32_t* __restrict__ carry_key,
                                                              const T* __restrict__ carry_val,
-                                                             T* __restrict__ y) {
+                                                             T* __restrict__ y,
+                                                             const int32_t* __restrict__ select = nullptr,
+                                                             int want = 0) {
+  if (!selected(select, want)) return;
   const int w = blockIdx.x * kBlock + threadIdx.x;
   if (w >= n) return;
   const int32_t key = carry_key[w];

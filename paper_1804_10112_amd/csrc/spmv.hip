@@ -244,8 +244,10 @@ template <typename T, bool CSR, int IPT, bool VEC, class XP = DenseX<T>>
 __global__ __launch_bounds__(kBlock) void seg_spmv_kernel(
     int nnz, int nrows, const int32_t* __restrict__ pos_or_row, const int32_t* __restrict__ col,
     const T* __restrict__ vals, const XP x, T* __restrict__ y,
-    int32_t* __restrict__ carry_key, T* __restrict__ carry_val) {
+    int32_t* __restrict__ carry_key, T* __restrict__ carry_val,
+    const int32_t* __restrict__ select, int want) {
   constexpr int CHUNK = IPT * kBlock;
+  if (!selected(select, want)) return;  // the other CSR kernel was chosen on the device
   __shared__ T s_val[CHUNK + kBlock];
   __shared__ int32_t s_key[CHUNK + kBlock];
   __shared__ SegScanStorage<T> s_scan;
@@ -409,10 +411,12 @@ __global__ __launch_bounds__(kBlock) void csr_stream_kernel(int nrows, int nnz,
                                                             const int32_t* __restrict__ pos,
                                                             const int32_t* __restrict__ crd,
                                                             const T* __restrict__ vals, const XP x,
-                                                            T* __restrict__ y) {
+                                                            T* __restrict__ y,
+                                                            const int32_t* __restrict__ select, int want) {
   typedef int32_t i4 __attribute__((ext_vector_type(4)));
   using V = typename VecOf<T>::type;  // 16 bytes of values
   constexpr int R = VecOf<T>::R;
+  if (!selected(select, want)) return;  // the other CSR kernel was chosen on the device
   __shared__ int32_t s_pos[kStreamRows + 1];
   __shared__ T s_prod[kStreamCap];
   __shared__ T s_wpart[kBlock / kWave];
@@ -550,15 +554,15 @@ __global__ __launch_bounds__(kBlock) void csr_stream_kernel(int nrows, int nnz,
 template <typename T, class XP>
 static spt_status launch_csr_stream(int64_t nnz, int64_t nrows, const int32_t* pos,
                                     const int32_t* crd, const T* vals, const XP x, T* y,
-                                    hipStream_t s) {
+                                    hipStream_t s, const int32_t* select = nullptr, int want = 0) {
   const unsigned grid = (unsigned)((nrows + kStreamRows - 1) / kStreamRows);
   const bool vec = ((reinterpret_cast<uintptr_t>(crd) | reinterpret_cast<uintptr_t>(vals)) & 15) == 0;
   if (vec)
     hipLaunchKernelGGL((csr_stream_kernel<T, true, XP>), dim3(grid), dim3(kBlock), 0, s, (int)nrows,
-                       (int)nnz, pos, crd, vals, x, y);
+                       (int)nnz, pos, crd, vals, x, y, select, want);
   else
     hipLaunchKernelGGL((csr_stream_kernel<T, false, XP>), dim3(grid), dim3(kBlock), 0, s, (int)nrows,
-                       (int)nnz, pos, crd, vals, x, y);
+                       (int)nnz, pos, crd, vals, x, y, select, want);
   SPT_CHECK_LAUNCH("csr_stream");
   return SPT_OK;
 }
@@ -627,7 +631,8 @@ static spt_status launch_fill(T* out, int64_t n, T v, hipStream_t s) {
 template <typename T, bool CSR, class XP>
 static spt_status launch_seg_x(int64_t nnz, int64_t nrows, const int32_t* pos_or_row,
                                const int32_t* col, const T* vals, const XP x, T* y, void* ws,
-                               size_t ws_bytes, hipStream_t s) {
+                               size_t ws_bytes, hipStream_t s, const int32_t* select = nullptr,
+                               int want = 0) {
   constexpr int CHUNK = kSegIPT * kBlock;
   if (nnz == 0) return launch_fill<T>(y, nrows, T(0), s);
   if (nnz + CHUNK >= INT32_MAX || nrows + 1 >= INT32_MAX)
@@ -646,13 +651,13 @@ static spt_status launch_seg_x(int64_t nnz, int64_t nrows, const int32_t* pos_or
   const bool vec = aligned16(col) && aligned16(vals) && (CSR || aligned16(pos_or_row));
   if (vec)
     hipLaunchKernelGGL((seg_spmv_kernel<T, CSR, kSegIPT, true, XP>), dim3(nwg), dim3(kBlock), 0, s,
-                       (int)nnz, (int)nrows, pos_or_row, col, vals, x, y, ckey, cval);
+                       (int)nnz, (int)nrows, pos_or_row, col, vals, x, y, ckey, cval, select, want);
   else
     hipLaunchKernelGGL((seg_spmv_kernel<T, CSR, kSegIPT, false, XP>), dim3(nwg), dim3(kBlock), 0, s,
-                       (int)nnz, (int)nrows, pos_or_row, col, vals, x, y, ckey, cval);
+                       (int)nnz, (int)nrows, pos_or_row, col, vals, x, y, ckey, cval, select, want);
   SPT_CHECK_LAUNCH("seg_spmv");
   hipLaunchKernelGGL(carry_fixup_kernel<T>, dim3((nwg + kBlock - 1) / kBlock), dim3(kBlock), 0, s,
-                     nwg, ckey, cval, y);
+                     nwg, ckey, cval, y, select, want);
   SPT_CHECK_LAUNCH("carry_fixup");
   return SPT_OK;
 }
@@ -660,9 +665,35 @@ static spt_status launch_seg_x(int64_t nnz, int64_t nrows, const int32_t* pos_or
 template <typename T, bool CSR>
 static spt_status launch_seg(int64_t nnz, int64_t nrows, const int32_t* pos_or_row,
                              const int32_t* col, const T* vals, const T* x, T* y, void* ws,
-                             size_t ws_bytes, hipStream_t s) {
+                             size_t ws_bytes, hipStream_t s, const int32_t* select = nullptr,
+                             int want = 0) {
   return launch_seg_x<T, CSR, DenseX<T>>(nnz, nrows, pos_or_row, col, vals, DenseX<T>{x}, y, ws,
-                                         ws_bytes, s);
+                                         ws_bytes, s, select, want);
+}
+
+// Large CSR matrices without a declared row bound: which kernel suits is decided on the device.
+// kSelectFlags workgroups look at the entry count of every block of 256 rows; if some block
+// holds more than 1/kSkewShare of all entries, the streamed kernel would end on that block's
+// workgroup alone (a block of 10^5 entries keeps one workgroup busy for about 0.1 ms), and the
+// entry-balanced kernel runs instead. Both kernels are launched; the one not chosen returns at
+// once. That costs some 10 us, which is why only matrices of kDynamicMinEntries entries or
+// more (kernel times from half a millisecond) are looked at; smaller ones go by the mean alone.
+constexpr int64_t kDynamicMinEntries = int64_t(1) << 25;
+constexpr int kSkewShare = 1536;
+__global__ __launch_bounds__(kBlock) void csr_skew_kernel(int nrows, int nnz, const int32_t* __restrict__ pos,
+                                                          int32_t* __restrict__ select) {
+  __shared__ int s_any;
+  if (threadIdx.x == 0) s_any = 0;
+  __syncthreads();
+  const int nblocks = (nrows + kStreamRows - 1) / kStreamRows;
+  int heavy = 0;
+  for (int b = blockIdx.x * kBlock + threadIdx.x; b < nblocks; b += kSelectFlags * kBlock) {
+    const int64_t e = pos[min((b + 1) * kStreamRows, nrows)] - pos[b * kStreamRows];
+    heavy |= e * kSkewShare > nnz;
+  }
+  if (heavy) s_any = 1;
+  __syncthreads();
+  if (threadIdx.x == 0) select[blockIdx.x] = s_any;  // any flag set: the entry-balanced kernel
 }
 
 // y = A x, A in CSR, x a sparse vector (compressed level) or a hash map (hashed level).
@@ -752,9 +783,26 @@ static spt_status spmv_typed(Format f, const spt_tensor* A, const T* x, T* y, vo
     }
     case Format::CSR: {
       const int hint = A->level[1].max_children;
-      if (csr_use_stream(A->nvals, A->level[0].N, hint))
+      if (csr_use_stream(A->nvals, A->level[0].N, hint)) {
+        static const bool forced = getenv("SPT_CSR_KERNEL") != nullptr;
+        if (hint == 0 && A->nvals >= kDynamicMinEntries && !forced) {
+          if (!ws || ws_bytes < seg_spmv_workspace(A->nvals))
+            return fail(SPT_ERR_WORKSPACE, "spmv: workspace of %zu bytes needed, %zu given",
+                        seg_spmv_workspace(A->nvals), ws_bytes);
+          // the flags live in the last 256 bytes of the workspace, behind the carries
+          int32_t* select = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + seg_spmv_workspace(A->nvals) - 256);
+          hipLaunchKernelGGL(csr_skew_kernel, dim3(kSelectFlags), dim3(kBlock), 0, s, (int)A->level[0].N, (int)A->nvals,
+                             A->level[1].pos, select);
+          SPT_CHECK_LAUNCH("csr skew");
+          spt_status st = launch_csr_stream<T, DenseX<T>>(A->nvals, A->level[0].N, A->level[1].pos,
+                                                          A->level[1].crd, vals, DenseX<T>{x}, y, s, select, 0);
+          if (st != SPT_OK) return st;
+          return launch_seg<T, true>(A->nvals, A->level[0].N, A->level[1].pos, A->level[1].crd, vals, x, y,
+                                     ws, ws_bytes, s, select, 1);
+        }
         return launch_csr_stream<T, DenseX<T>>(A->nvals, A->level[0].N, A->level[1].pos,
                                                A->level[1].crd, vals, DenseX<T>{x}, y, s);
+      }
       return launch_seg<T, true>(A->nvals, A->level[0].N, A->level[1].pos, A->level[1].crd, vals,
                                  x, y, ws, ws_bytes, s);
     }

@@ -228,6 +228,41 @@ def test_streamed_kernel_with_long_rows_among_short_ones(dtype, nnz_mod):
     assert_close(gpu_spmv(_with_hint(spec, 40_000), x), ref, mag, dtype, "long rows, entry-balanced")
 
 
+@pytest.mark.parametrize("heavy_row", [0, 150_000])
+def test_large_unhinted_csr_picks_its_kernel_on_the_device(heavy_row):
+    """From 2^25 entries on, a CSR matrix without a declared row bound has the entry counts of
+    its 256-row blocks inspected on the device: even blocks keep the streamed kernel (same bits
+    as with a declared bound of 16), one block holding a 150 000-entry row switches to the
+    entry-balanced kernel (same bits as with a declared bound of 150 000)."""
+    N = M = 2_100_000
+    K = 16
+    rng = np.random.default_rng(90 + (heavy_row > 0))
+    cols = (rng.integers(0, M, N, dtype=np.int64)[:, None] + np.arange(K, dtype=np.int64)[None, :] * 131_071) % M
+    cols.sort(axis=1)
+    lens = np.full(N, K, dtype=np.int64)
+    crd = cols.reshape(-1)
+    if heavy_row:
+        at = 1_234_567
+        extra = np.sort(rng.choice(M, heavy_row, replace=False))
+        crd = np.concatenate([crd[: at * K], extra, crd[(at + 1) * K:]])
+        lens[at] = heavy_row
+    del cols
+    pos = np.concatenate([[0], np.cumsum(lens)])
+    nnz = int(pos[-1])
+    assert nnz >= 2**25 and nnz <= 32 * N
+    vals = rng.uniform(-1, 1, nnz).astype(np.float32)
+    plain = wl.csr_spec(N, M, pos, crd, vals)
+    x = wl.dense_vector(M, 92, np.float32)
+    ref, mag = oracle.spmv(plain, x)
+    a, b = gpu_spmv(plain, x, repeat=2)
+    assert_close(a, ref, mag, np.float32, f"large unhinted csr, heavy row {heavy_row}")
+    assert np.array_equal(a, b), "run-to-run bits differ"
+    same = gpu_spmv(_with_hint(plain, heavy_row if heavy_row else K), x)
+    assert np.array_equal(a, same), "the device-side choice differs from the expected kernel"
+    other = gpu_spmv(_with_hint(plain, K if heavy_row else 100_000), x)
+    assert_close(other, ref, mag, np.float32, "the kernel not chosen")
+
+
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
 def test_csr_hint_that_the_data_violates_stays_correct(dtype):
     """A declared bound of 8 on a matrix with one row of 9000 entries: the streamed kernel takes
