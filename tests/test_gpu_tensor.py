@@ -165,6 +165,55 @@ def test_csf_with_empty_fibres_and_slices(dtype, nnz, extra):
     assert_close(ov[full], rv, rm, dtype, "ttv csf with gaps")
 
 
+WAVE_MIN = 1 << 18  # from this many entries on TTV keeps c in LDS and lets every wave walk on its own
+
+
+@pytest.mark.parametrize("dtype,K", [(np.float32, 900), (np.float32, 32_768), (np.float32, 50_000),
+                                     (np.float64, 16_384), (np.float64, 16_385), (np.float64, 40_000)])
+@pytest.mark.parametrize("tail", [0, 1, 2, 3])
+def test_ttv_with_the_vector_in_lds(dtype, K, tail):
+    """Large tensors: c is cached in LDS whole (K up to 128 KiB of values) or in part (the
+    rest is gathered from global memory); the entry count takes every remainder modulo 4, so
+    the last 16-byte group and the last 256-entry piece of a wave are partial."""
+    dims = (3000, 500, K)
+    ci, cj, ck, v = wl.random_coo3_entries(dims, WAVE_MIN + 40_000, 900 + K % 97 + tail, dtype, "u01", skew=1.5)
+    n = len(v) - (len(v) - tail) % 4
+    ci, cj, ck, v = ci[:n], cj[:n], ck[:n], v[:n]
+    assert n >= WAVE_MIN and n % 4 == tail
+    coo, csf = wl.coo3_spec(dims, ci, cj, ck, v), wl.csf3_from_sorted_coo(dims, ci, cj, ck, v)
+    c = wl.dense_vector(K, 7, dtype, "u01")
+    _check_ttv(coo, csf, c, f"ttv in LDS K={K} tail={tail}")
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_ttv_in_lds_with_long_fibres_empty_fibres_and_unaligned_buffers(dtype):
+    """Fibres of 1 to 3000 entries (several 256-entry pieces: chains of carries), a CSF with
+    empty fibres and slices, exact small-integer data (bit-exact sums), unaligned arrays."""
+    rng = np.random.default_rng(17)
+    dims = (400, 300, 4000)
+    lens = np.minimum(rng.zipf(1.3, 9000), 3000)
+    fib = np.sort(rng.choice(dims[0] * dims[1], len(lens), replace=False))
+    ci, cj = np.repeat(fib // dims[1], lens), np.repeat(fib % dims[1], lens)
+    ck = np.concatenate([np.sort(rng.choice(dims[2], l, replace=False)) for l in lens])
+    v = rng.integers(-3, 4, len(ck)).astype(dtype)
+    assert len(v) >= WAVE_MIN, len(v)
+    c = rng.integers(-2, 3, dims[2]).astype(dtype)
+    coo, csf = wl.coo3_spec(dims, ci, cj, ck, v), wl.csf3_from_sorted_coo(dims, ci, cj, ck, v)
+    ri, rj, rv, _ = oracle.ttv(coo, c)
+    for misalign in (False, True):
+        oi, oj, ov, n = gpu_ttv(coo, c, misalign=misalign)
+        assert n == len(ri) and np.array_equal(oi, ri) and np.array_equal(oj, rj)
+        assert np.array_equal(ov.astype(np.float64), rv), "coo"
+        assert np.array_equal(gpu_ttv(csf, c, misalign=misalign)[2].astype(np.float64), rv), "csf"
+    gap = wl.csf3_with_empty_segments(dims, ci, cj, ck, v, seed=3, extra_fibers=30_000, extra_slices=100)
+    p2 = np.asarray(gap.levels[2].pos)
+    full = np.diff(p2) > 0
+    assert (~full).sum() > 1000
+    _, _, gv, n = gpu_ttv(gap, c)
+    assert n == len(full) and np.all(gv[~full] == 0)
+    assert np.array_equal(gv[full].astype(np.float64), rv), "csf with gaps"
+
+
 def test_mttkrp_with_a_dimension_beyond_24_bits_takes_the_general_addressing():
     """Coordinates from 2^23 on do not fit the 24-bit multiply of the fast factor addressing."""
     dims = (70, 9_000_000, 50)
