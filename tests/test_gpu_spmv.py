@@ -61,6 +61,33 @@ def test_csr_coo_degenerate_structures(dtype):
 
 
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("nnz", [255, 257, 1023, 65_535, 65_536, 65_537, 200_000])
+def test_sorted_coo_on_both_sides_of_the_single_launch_limit(dtype, nnz):
+    """Up to 65 536 entries sorted COO runs in one launch (a wave per 256 entries, the owner of
+    a row reads on past its piece); above, the chunked kernel with carries. Rows of 1 to 3000
+    entries, runs of empty rows, the last rows empty, an infinite x value under the last entry."""
+    N, M = 9000, 700
+    rng = np.random.default_rng(nnz)
+    lens = np.minimum(rng.zipf(1.4, 4000), min(3000, nnz // 3))
+    lens = lens[np.cumsum(lens) <= nnz]
+    rows = np.sort(rng.choice(N - 50, len(lens), replace=False))      # the last 50 rows stay empty
+    r = np.repeat(rows, lens)
+    r = np.concatenate([r, np.full(nnz - len(r), rows[-1] + 1)])      # fill up with one more long row
+    c = rng.integers(0, M, nnz)
+    c = c[np.lexsort((c, r))]                                         # columns ascend inside every row
+    v = rng.uniform(-1, 1, nnz).astype(dtype)
+    x = wl.dense_vector(M, 11, dtype)
+    _check(wl.coo_spec(N, M, r, c, v), x, f"sorted coo nnz={nnz}")
+    x2 = x.copy()
+    x2[c[-1]] = np.inf
+    v[c == c[-1]] = 1.0
+    spec = wl.coo_spec(N, M, r, c, v)
+    ref, _ = oracle.spmv(spec, x2)
+    got = gpu_spmv(spec, x2)
+    assert np.array_equal(np.isinf(got), np.isinf(ref)) and not np.isnan(got).any()
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
 def test_buffers_that_are_not_16_byte_aligned(dtype):
     """Arrays one element past an aligned address take the scalar-load paths."""
     N, M = 1000, 1200
