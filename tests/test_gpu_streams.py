@@ -188,7 +188,9 @@ def test_later_entry_points_in_a_captured_graph():
     eager = {k: [t.clone() for t in v] for k, v in outs.items()}
     n_mul = int(eager["mul"][3].item())
     assert 0 < n_mul < 40_000
-    assert torch.equal(eager["y"][0], eager["y"][2]) and torch.equal(eager["y"][1], eager["y"][2])
+    assert torch.equal(eager["y"][0], eager["y"][2])           # DCSR and CSR run the same kernel
+    ref = eager["y"][2].cpu().numpy()                          # sorted COO of this size: its own order of additions
+    assert_close(eager["y"][1].cpu().numpy(), ref, np.abs(ref) + 1.0, np.float64, "aos coo vs csr")
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
         run_all()

@@ -71,7 +71,7 @@ def _check_mttkrp(coo, csf, Cm, Dm, what):
 
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
-@pytest.mark.parametrize("J", [1, 8, 16, 32, 33, 64, 100])
+@pytest.mark.parametrize("J", [1, 8, 16, 24, 32, 33, 64, 100, 128, 260])
 def test_mttkrp_ranks(dtype, J):
     dims = (200, 37, 53)
     coo, csf = _tensor(dims, 20_000, 400 + J, dtype)
