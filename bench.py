@@ -520,15 +520,6 @@ def measure_ceilings():
         o = torch.empty(n, dtype=tdt, device=dev)
         t = timed(lambda: spt.spt_probe_gather(idx, n, table, sdt, o))
         out[name + "_Gelem_s"] = round(n / t / 1e9, 1)
-    # factor-row gathers of MTTKRP: 32 consecutive lanes read one 128-byte row of an 80 000 x 32
-    # fp32 matrix (config 5's C), rows drawn at random
-    rows = torch.randint(0, 80_000, (n // 32,), dtype=torch.int32, device=dev, generator=g)
-    idx = (rows.repeat_interleave(32) * 32 + torch.arange(32, dtype=torch.int32, device=dev).repeat(n // 32)).int()
-    table = torch.zeros(80_000 * 32, dtype=torch.float32, device=dev)
-    o = torch.empty(n, dtype=torch.float32, device=dev)
-    t = timed(lambda: spt.spt_probe_gather(idx, n, table, spt.SPT_F32, o))
-    out["gather_rows_128B_table_10MB_Grows_s"] = round(n / 32 / t / 1e9, 2)
-    del idx, table, o, rows
     # the runtime's own device-to-device copy: the yardstick for a radix pass (read + write)
     dst = torch.empty_like(src)
     t = timed(lambda: dst.copy_(src))
