@@ -109,9 +109,11 @@ typedef enum {
  *          add up each row (best for short rows), and one that deals the entries
  *          out evenly whatever their rows (best for strongly skewed row lengths).
  *          Without the hint the mean row length nvals / rows decides (<= 32: the
- *          streamed loop); a declared bound <= 32 selects the streamed loop, a
- *          larger one the entry-balanced loop. A bound that the data violates
- *          costs time, not correctness.
+ *          streamed loop); from 2^25 stored entries on, a kernel first looks at the
+ *          entry counts of the 256-row blocks and the entry-balanced loop runs if one
+ *          block holds more than 1/1536 of all entries. A declared bound <= 32
+ *          selects the streamed loop, a larger one the entry-balanced loop. A bound
+ *          that the data violates costs time, not correctness.
  *   crd_stride  elements of crd between the coordinates of consecutive positions: 0 or 1 =
  *          contiguous (struct of arrays). A larger stride describes the array-of-structs
  *          variant of Section 5.2, where one interleaved array holds the coordinates of each
