@@ -609,6 +609,7 @@ __global__ __launch_bounds__(kBlock) void coo_atomic_spmv_kernel(
 // thread that sees the gap. No workspace, no atomics, a fixed order of additions.
 constexpr int kSmallPiece = 4 * kWave;
 constexpr int64_t kSmallCooMaxEntries = 1 << 16;  // worst case (one row holds everything): 1024 read-ahead rounds
+constexpr int64_t kSmallCooMaxRows = 1 << 20;     // worst case (all rows empty but one): one wave zeroes them, 16 384 rounds
 
 template <typename T>
 __device__ __forceinline__ void zero_rows(T* __restrict__ y, int lo, int hi) {  // rows lo .. hi - 1
@@ -962,7 +963,7 @@ static spt_status spmv_typed(Format f, const spt_tensor* A, const T* x, T* y, vo
     }
     case Format::COO2: {
       const int64_t nnz = A->nvals, N = A->level[0].N;
-      if ((A->level[0].flags & SPT_ORDERED) && nnz > 0 && nnz <= kSmallCooMaxEntries && N < INT32_MAX) {
+      if ((A->level[0].flags & SPT_ORDERED) && nnz > 0 && nnz <= kSmallCooMaxEntries && N <= kSmallCooMaxRows) {
         hipLaunchKernelGGL(coo_small_spmv_kernel<T>, dim3((unsigned)((nnz + kSmallPiece - 1) / kSmallPiece)),
                            dim3(kWave), 0, s, (int)nnz, (int)N, A->level[0].crd, A->level[1].crd, vals, x, y);
         SPT_CHECK_LAUNCH("coo_small_spmv");

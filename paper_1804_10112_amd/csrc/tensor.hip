@@ -976,7 +976,7 @@ spt_status ttm_dispatch(Format f, const spt_tensor* B, const void* C, int32_t K,
 }
 
 // c held in LDS, one resident workgroup per compute unit (ttv_wave.hip)
-bool ttv_wave_applies(int64_t nnz);
+bool ttv_wave_applies(int64_t nnz, int64_t K, int dtype);
 size_t ttv_coo_wave_workspace(int64_t nnz);
 size_t ttv_csf_wave_workspace(int64_t nnz);
 template <typename T>
@@ -988,7 +988,7 @@ spt_status ttv_csf_wave(int64_t nnz, int64_t nfib, int64_t K, const int32_t* pos
                         const T* vals, const T* c, T* out_v, void* ws, size_t ws_bytes, hipStream_t s);
 
 size_t ttv_workspace(Format f, const spt_tensor* B) {
-  if (ttv_wave_applies(B->nvals))
+  if (ttv_wave_applies(B->nvals, B->level[2].N, B->dtype))
     return f == Format::COO3 ? ttv_coo_wave_workspace(B->nvals) : ttv_csf_wave_workspace(B->nvals);
   return f == Format::COO3 ? ttv_coo_workspace(B->nvals) : seg_spmv_workspace(B->nvals);
 }
@@ -1007,7 +1007,7 @@ spt_status ttv_dispatch(Format f, const spt_tensor* B, const void* c, int32_t* o
       hipLaunchKernelGGL(set_i64_kernel, dim3(1), dim3(kWave), 0, s, out_nnz_dev, nfib);
       SPT_CHECK_LAUNCH("ttv set count");
     }
-    if (ttv_wave_applies(B->nvals)) {
+    if (ttv_wave_applies(B->nvals, B->level[2].N, B->dtype)) {
       if (B->dtype == SPT_F64)
         return ttv_csf_wave<double>(B->nvals, nfib, B->level[2].N, B->level[2].pos, B->level[2].crd,
                                     static_cast<const double*>(B->vals), static_cast<const double*>(c),
@@ -1019,7 +1019,7 @@ spt_status ttv_dispatch(Format f, const spt_tensor* B, const void* c, int32_t* o
     return csr_rows_reduce(B->dtype, B->nvals, nfib, B->level[2].pos, B->level[2].crd, B->vals, c,
                            out_vals, ws, ws_bytes, s);
   }
-  if (ttv_wave_applies(B->nvals)) {
+  if (ttv_wave_applies(B->nvals, B->level[2].N, B->dtype)) {
     const int32_t *ci = B->level[0].crd, *cj = B->level[1].crd, *ck = B->level[2].crd;
     if (B->dtype == SPT_F64)
       return ttv_coo_wave<double>(B->nvals, B->level[2].N, ci, cj, ck, static_cast<const double*>(B->vals),

@@ -400,8 +400,13 @@ static int compute_units() {
 static int64_t pieces_of(int64_t nnz) { return (nnz + kPiece - 1) / kPiece; }
 
 // Smaller tensors stay with the chunked kernels: the fixed cost of staging c on every
-// compute unit is not recovered.
-bool ttv_wave_applies(int64_t nnz) { return nnz >= (int64_t(1) << 18) && nnz + kPiece < INT32_MAX; }
+// compute unit is not recovered. So do tensors whose last dimension is so long that less
+// than a quarter of c fits the cache: their gathers go to global memory anyway, and the
+// chunked kernels keep more waves in flight for that.
+bool ttv_wave_applies(int64_t nnz, int64_t K, int dtype) {
+  const int64_t vsz = dtype == SPT_F64 ? 8 : 4;
+  return nnz >= (int64_t(1) << 18) && nnz + kPiece < INT32_MAX && K * vsz <= 4 * (int64_t)kCsfCacheBytes;
+}
 
 size_t ttv_coo_wave_workspace(int64_t nnz) {
   const int64_t np = pieces_of(nnz);

@@ -48,6 +48,8 @@ def test_csr_coo_degenerate_structures(dtype):
     v4 = np.array([1, 2, 3, 4], dtype)
     _check(wl.csr_from_sorted_coo(100000, 50, r, c4, v4), x, "csr mostly empty")
     _check(wl.coo_spec(100000, 50, r, c4, v4), x, "coo mostly empty")
+    # more than 2^20 rows: few entries still take the chunked kernel (fill + carries)
+    _check(wl.coo_spec(3_000_000, 50, np.array([3, 3, 40000, 2_999_999]), c4, v4), x, "coo, 3M rows, 4 entries")
     # row boundaries exactly on chunk boundaries
     r = np.repeat(np.arange(4), CHUNK)
     c = rng.integers(0, 50, 4 * CHUNK)

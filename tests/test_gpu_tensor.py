@@ -185,6 +185,14 @@ def test_ttv_with_the_vector_in_lds(dtype, K, tail):
     _check_ttv(coo, csf, c, f"ttv in LDS K={K} tail={tail}")
 
 
+def test_large_ttv_with_a_vector_far_beyond_lds_takes_the_chunked_kernels():
+    """c of 600 000 values: less than a quarter would fit LDS, the chunked kernels run."""
+    dims = (300, 500, 600_000)
+    coo, csf = _tensor(dims, WAVE_MIN + 30_000, 77, np.float32)
+    assert len(coo.vals) >= WAVE_MIN
+    _check_ttv(coo, csf, wl.dense_vector(dims[2], 3, np.float32, "u01"), "ttv, K = 600 000")
+
+
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 def test_ttv_in_lds_with_long_fibres_empty_fibres_and_unaligned_buffers(dtype):
     """Fibres of 1 to 3000 entries (several 256-entry pieces: chains of carries), a CSF with
