@@ -1,5 +1,5 @@
-// Device-wide prefix sum of int32 (three plain kernels, no spin waits):
-// per-tile sums -> one workgroup scans the tile sums -> per-tile scan + offset.
+// Device-wide prefix sum of int32 (two or three plain kernels, no spin waits):
+// per-tile sums -> (beyond 2048 tiles: one workgroup scans the tile sums) -> per-tile scan + offset.
 // This is the GPU form of Table 3's append_finalize (pos = running sum of the
 // per-parent counts) and of the digit offsets of every radix-sort pass.
 #pragma once
@@ -9,6 +9,7 @@ namespace spt {
 
 constexpr int kScanIPT = 16;
 constexpr int kScanTile = kScanIPT * kBlock;
+constexpr int64_t kScanSelfTiles = 2048;  // up to here a workgroup re-adds the earlier tiles' sums (8 KB)
 
 inline int64_t scan_tiles(int64_t n) { return (n + kScanTile - 1) / kScanTile; }
 inline size_t scan_workspace(int64_t n) { return align_up((size_t)(scan_tiles(n) + 1) * 4, 256); }
@@ -69,7 +70,9 @@ static __global__ __launch_bounds__(kBlock) void scan_spine_kernel(int32_t* __re
 }
 
 // out[i] = sum of in[0..i) (+ in[i] if INCLUSIVE). in may equal out.
-template <bool INCLUSIVE>
+// SELF: tile_off holds the tile sums themselves and every workgroup adds up the sums of the
+// tiles before its own (a few KB from L2), which saves the launch of the spine kernel.
+template <bool INCLUSIVE, bool SELF = false>
 __global__ __launch_bounds__(kBlock) void scan_apply_kernel(const int32_t* in, int64_t n,
                                                             const int32_t* __restrict__ tile_off,
                                                             int32_t* out) {
@@ -95,8 +98,16 @@ __global__ __launch_bounds__(kBlock) void scan_apply_kernel(const int32_t* in, i
   }
 #pragma unroll
   for (int k = 0; k < kScanIPT; ++k) s += v[k];
+  int before = 0;  // sum of everything in the tiles before this one
+  if (SELF) {
+    int part = 0;
+    for (int t = threadIdx.x; t < (int)blockIdx.x; t += kBlock) part += tile_off[t];
+    block_inclusive_sum(part, &before);
+  } else {
+    before = tile_off[blockIdx.x];
+  }
   int total;
-  int run = block_inclusive_sum(s, &total) - s + tile_off[blockIdx.x];
+  int run = block_inclusive_sum(s, &total) - s + before;
 #pragma unroll
   for (int k = 0; k < kScanIPT; ++k) {
     const int x = v[k];
@@ -118,7 +129,7 @@ __global__ __launch_bounds__(kBlock) void scan_apply_kernel(const int32_t* in, i
   }
 }
 
-// Enqueues the three kernels. tmp needs scan_workspace(n) bytes.
+// Enqueues the kernels. tmp needs scan_workspace(n) bytes.
 template <bool INCLUSIVE>
 inline spt_status device_scan_i32(const int32_t* in, int32_t* out, int64_t n, int32_t* tmp,
                                   hipStream_t s) {
@@ -126,9 +137,15 @@ inline spt_status device_scan_i32(const int32_t* in, int32_t* out, int64_t n, in
   const int64_t nt = scan_tiles(n);
   hipLaunchKernelGGL(scan_tile_sums_kernel, dim3((unsigned)nt), dim3(kBlock), 0, s, in, n, tmp);
   SPT_CHECK_LAUNCH("scan_tile_sums");
+  if (nt <= kScanSelfTiles) {  // two kernels: the apply kernel sums the earlier tiles' sums itself
+    hipLaunchKernelGGL((scan_apply_kernel<INCLUSIVE, true>), dim3((unsigned)nt), dim3(kBlock), 0, s, in, n,
+                       tmp, out);
+    SPT_CHECK_LAUNCH("scan_apply");
+    return SPT_OK;
+  }
   hipLaunchKernelGGL(scan_spine_kernel, dim3(1), dim3(kBlock), 0, s, tmp, nt);
   SPT_CHECK_LAUNCH("scan_spine");
-  hipLaunchKernelGGL(scan_apply_kernel<INCLUSIVE>, dim3((unsigned)nt), dim3(kBlock), 0, s, in, n,
+  hipLaunchKernelGGL((scan_apply_kernel<INCLUSIVE, false>), dim3((unsigned)nt), dim3(kBlock), 0, s, in, n,
                      tmp, out);
   SPT_CHECK_LAUNCH("scan_apply");
   return SPT_OK;

@@ -985,7 +985,8 @@ spt_status ttv_coo_wave(int64_t nnz, int64_t K, const int32_t* ci, const int32_t
                         void* ws, size_t ws_bytes, hipStream_t s);
 template <typename T>
 spt_status ttv_csf_wave(int64_t nnz, int64_t nfib, int64_t K, const int32_t* pos, const int32_t* ck,
-                        const T* vals, const T* c, T* out_v, void* ws, size_t ws_bytes, hipStream_t s);
+                        const T* vals, const T* c, T* out_v, int64_t* out_count, void* ws, size_t ws_bytes,
+                        hipStream_t s);
 
 size_t ttv_workspace(Format f, const spt_tensor* B) {
   if (ttv_wave_applies(B->nvals, B->level[2].N, B->dtype))
@@ -1003,18 +1004,18 @@ spt_status ttv_dispatch(Format f, const spt_tensor* B, const void* c, int32_t* o
     // The bottom level is a compressed level over the fibers: the same row
     // reduction as CSR SpMV with rows = fibers and x = c.
     const int64_t nfib = B->level[2].M;
-    if (out_nnz_dev) {
-      hipLaunchKernelGGL(set_i64_kernel, dim3(1), dim3(kWave), 0, s, out_nnz_dev, nfib);
-      SPT_CHECK_LAUNCH("ttv set count");
-    }
-    if (ttv_wave_applies(B->nvals, B->level[2].N, B->dtype)) {
+    if (ttv_wave_applies(B->nvals, B->level[2].N, B->dtype)) {  // writes the count itself
       if (B->dtype == SPT_F64)
         return ttv_csf_wave<double>(B->nvals, nfib, B->level[2].N, B->level[2].pos, B->level[2].crd,
                                     static_cast<const double*>(B->vals), static_cast<const double*>(c),
-                                    static_cast<double*>(out_vals), ws, ws_bytes, s);
+                                    static_cast<double*>(out_vals), out_nnz_dev, ws, ws_bytes, s);
       return ttv_csf_wave<float>(B->nvals, nfib, B->level[2].N, B->level[2].pos, B->level[2].crd,
                                  static_cast<const float*>(B->vals), static_cast<const float*>(c),
-                                 static_cast<float*>(out_vals), ws, ws_bytes, s);
+                                 static_cast<float*>(out_vals), out_nnz_dev, ws, ws_bytes, s);
+    }
+    if (out_nnz_dev) {
+      hipLaunchKernelGGL(set_i64_kernel, dim3(1), dim3(kWave), 0, s, out_nnz_dev, nfib);
+      SPT_CHECK_LAUNCH("ttv set count");
     }
     return csr_rows_reduce(B->dtype, B->nvals, nfib, B->level[2].pos, B->level[2].crd, B->vals, c,
                            out_vals, ws, ws_bytes, s);

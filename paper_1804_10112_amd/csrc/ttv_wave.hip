@@ -201,11 +201,6 @@ __global__ __launch_bounds__(kBlock) void ttv_piece_heads_kernel(int nnz, int np
   if (lane == kWave - 1) heads[piece] = cnt;
 }
 
-__global__ void ttv_piece_total_kernel(int npieces, const int32_t* __restrict__ heads,
-                                       const int32_t* __restrict__ off, int64_t* __restrict__ out_nnz) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) *out_nnz = (int64_t)off[npieces - 1] + heads[npieces - 1];
-}
-
 // One output entry per fibre, at index piece_off[piece] + rank of the fibre's head inside
 // the piece (append order = ascending (i, j), Section 3.4).
 template <typename T, bool VEC, bool ALL>
@@ -213,7 +208,8 @@ __global__ __launch_bounds__(kBig) void ttv_coo_wave_kernel(
     int nnz, int npieces, const int32_t* __restrict__ ci, const int32_t* __restrict__ cj,
     const int32_t* __restrict__ ck, const T* __restrict__ vals, const T* __restrict__ c, int cached,
     const int32_t* __restrict__ piece_off, int32_t* __restrict__ out_i, int32_t* __restrict__ out_j,
-    T* __restrict__ out_v, int32_t* __restrict__ carry_key, T* __restrict__ carry_val) {
+    T* __restrict__ out_v, int64_t* __restrict__ out_nnz, int32_t* __restrict__ carry_key,
+    T* __restrict__ carry_val) {
   __shared__ T s_c[kCooCacheBytes / sizeof(T)];
   stage_vector(s_c, c, cached);
   const int lane = lane_id();
@@ -271,7 +267,10 @@ __global__ __launch_bounds__(kBig) void ttv_coo_wave_kernel(
         qj = j[u][r];
       }
       const int cnt = __popc(headmask);
-      int next_idx = first[u] + wave_inclusive_sum(cnt) - cnt;
+      const int upto = first[u] + wave_inclusive_sum(cnt);
+      int next_idx = upto - cnt;
+      // the number of fibres of the result: where the last piece's last head lands, plus one
+      if (piece == npieces - 1 && lane == kWave - 1 && out_nnz) *out_nnz = upto;
       int key[kEPL];
       T p[kEPL];
 #pragma unroll
@@ -292,10 +291,13 @@ __global__ __launch_bounds__(kBig) void ttv_coo_wave_kernel(
 // ================================================================ CSF
 // first[piece] = first fibre that starts at or after the piece's first entry (piece ==
 // npieces: the number of fibres, so that the last piece also covers trailing empty fibres).
+// count (may be null) receives the number of values of the result, one per fibre.
 __global__ __launch_bounds__(kBlock) void ttv_piece_fibres_kernel(int npieces, int nfib,
                                                                   const int32_t* __restrict__ pos,
-                                                                  int32_t* __restrict__ first) {
+                                                                  int32_t* __restrict__ first,
+                                                                  int64_t* __restrict__ count) {
   const int piece = blockIdx.x * kBlock + threadIdx.x;
+  if (piece == 0 && count) *count = nfib;
   if (piece > npieces) return;
   int lo = 0, hi = nfib + 1;
   if (piece == npieces) lo = hi = nfib;
@@ -441,16 +443,12 @@ spt_status ttv_coo_wave(int64_t nnz64, int64_t K, const int32_t* ci, const int32
   SPT_CHECK_LAUNCH("ttv piece heads");
   spt_status st = device_scan_i32<false>(heads, off, np, scan_tmp, s);
   if (st != SPT_OK) return st;
-  if (out_nnz) {
-    hipLaunchKernelGGL(ttv_piece_total_kernel, dim3(1), dim3(kWave), 0, s, np, heads, off, out_nnz);
-    SPT_CHECK_LAUNCH("ttv total");
-  }
   const int cached = (int)std::min<int64_t>(K, kCooCacheBytes / sizeof(T));
   const bool all = cached == K;
   const unsigned grid = (unsigned)std::min<int64_t>(compute_units(), (np + kBigWaves - 1) / kBigWaves);
 #define SPT_TTV_COO(VEC_, ALL_)                                                                                  \
   hipLaunchKernelGGL((ttv_coo_wave_kernel<T, VEC_, ALL_>), dim3(grid), dim3(kBig), 0, s, nnz, np, ci, cj, ck, vals, \
-                     c, cached, off, out_i, out_j, out_v, ckey, cval)
+                     c, cached, off, out_i, out_j, out_v, out_nnz, ckey, cval)
   if (vec && all) SPT_TTV_COO(true, true);
   else if (vec) SPT_TTV_COO(true, false);
   else if (all) SPT_TTV_COO(false, true);
@@ -465,7 +463,8 @@ spt_status ttv_coo_wave(int64_t nnz64, int64_t K, const int32_t* ci, const int32
 
 template <typename T>
 spt_status ttv_csf_wave(int64_t nnz64, int64_t nfib, int64_t K, const int32_t* pos, const int32_t* ck,
-                        const T* vals, const T* c, T* out_v, void* ws, size_t ws_bytes, hipStream_t s) {
+                        const T* vals, const T* c, T* out_v, int64_t* out_count, void* ws, size_t ws_bytes,
+                        hipStream_t s) {
   const int nnz = (int)nnz64;
   const int np = (int)pieces_of(nnz64);
   if (nfib + 1 >= INT32_MAX) return fail(SPT_ERR_UNSUPPORTED, "ttv: more than 2^31 fibres");
@@ -477,7 +476,7 @@ spt_status ttv_csf_wave(int64_t nnz64, int64_t nfib, int64_t K, const int32_t* p
   int32_t* ckey = W.take<int32_t>(np);
   T* cval = W.take<T>(np);
   hipLaunchKernelGGL(ttv_piece_fibres_kernel, dim3((np + 1 + kBlock - 1) / kBlock), dim3(kBlock), 0, s, np, (int)nfib,
-                     pos, first);
+                     pos, first, out_count);
   SPT_CHECK_LAUNCH("ttv piece fibres");
   const bool vec = al16(ck) && al16(vals);
   const int cached = (int)std::min<int64_t>(K, kCsfCacheBytes / sizeof(T));
@@ -505,8 +504,8 @@ template spt_status ttv_coo_wave<double>(int64_t, int64_t, const int32_t*, const
                                          const double*, const double*, int32_t*, int32_t*, double*, int64_t*, void*,
                                          size_t, hipStream_t);
 template spt_status ttv_csf_wave<float>(int64_t, int64_t, int64_t, const int32_t*, const int32_t*, const float*,
-                                        const float*, float*, void*, size_t, hipStream_t);
+                                        const float*, float*, int64_t*, void*, size_t, hipStream_t);
 template spt_status ttv_csf_wave<double>(int64_t, int64_t, int64_t, const int32_t*, const int32_t*, const double*,
-                                         const double*, double*, void*, size_t, hipStream_t);
+                                         const double*, double*, int64_t*, void*, size_t, hipStream_t);
 
 }  // namespace spt

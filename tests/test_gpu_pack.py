@@ -275,3 +275,33 @@ def test_to_hashed_rows_collision_free_layout_and_full_rows():
     crd, vals, dropped = gpu_to_hashed_rows(wl.coo_spec(2, 40, rows, cols, np.arange(6.0)), 4)
     assert dropped == 2 and np.count_nonzero(crd[0] >= 0) == 4 and np.all(crd[1] == -1)
     assert set(crd[0]) <= set(cols) and all(vals[0][q] == list(cols).index(crd[0][q]) for q in range(4))
+
+
+def test_dia_offsets_of_a_matrix_with_ten_million_possible_diagonals():
+    """5M x 5M with 3000 entries on 40 diagonals near and far: the flags of all N + M - 1 possible
+    offsets are scanned by the device-wide prefix sum in its three-kernel form (more than 2048
+    tiles of 4096 values; smaller scans let every workgroup add up the earlier tiles itself)."""
+    import torch
+    import paper_1804_10112_amd as spt
+    N = M = 5_000_000
+    rng = np.random.default_rng(31)
+    offs = np.unique(np.concatenate([rng.integers(-N + 1, M, 36), [-(N - 1), M - 1, 0, 1]]))
+    o = rng.choice(offs, 3000)
+    lo, hi = np.maximum(0, -o), np.minimum(N, M - o)
+    r = (lo + rng.random(3000) * (hi - lo)).astype(np.int64)
+    r = np.minimum(r, hi - 1)
+    c = r + o
+    order = np.lexsort((c, r))
+    r, c, o = r[order], c[order], o[order]
+    keep = np.ones(len(r), bool)
+    keep[1:] = (r[1:] != r[:-1]) | (c[1:] != c[:-1])
+    r, c = r[keep], c[keep]
+    A = spt.DeviceTensor(wl.coo_spec(N, M, r, c, np.ones(len(r))))
+    cap = 64
+    out = torch.full((cap,), 12345, dtype=torch.int32, device="cuda")
+    K = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    spt.spt_coo_dia_offsets(A, out, cap, K, A.workspace(spt.SPT_OP_DIA_OFFSETS))
+    torch.cuda.synchronize()
+    expect = np.unique(c - r)
+    assert int(K.item()) == len(expect)
+    assert np.array_equal(out.cpu().numpy()[: len(expect)], expect)
