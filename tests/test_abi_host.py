@@ -73,6 +73,26 @@ def test_recognised_compositions_have_workspace_sizes():
         assert spt.spt_workspace_bytes(op, _host_desc(spec), 4) >= 256, spec.name
 
 
+def test_ttv_workspace_follows_the_kernel_choice():
+    """The query depends on the descriptor's sizes alone: below 2^18 stored entries (and for a
+    last dimension of which less than a quarter would fit LDS) the chunked kernels' carries per
+    2048 entries, from 2^18 on the carries and offsets per 256-entry piece."""
+    c5 = wl.config5(dims=(20, 16, 12), nnz=300, rank=4)
+    sizes = {}
+    for fmt in ("coo", "csf"):
+        t = _host_desc(c5[fmt])
+        for nvals in ((1 << 18) - 1, 1 << 18, 1 << 24):
+            t.nvals = nvals
+            if fmt == "csf":
+                t.level[2].M = 1000          # fibres
+            sizes[fmt, nvals] = spt.spt_workspace_bytes(B.SPT_OP_TTV, t)
+        assert sizes[fmt, 1 << 18] > 4 * sizes[fmt, (1 << 18) - 1]      # 8x the carries per entry
+        assert sizes[fmt, 1 << 24] > 32 * sizes[fmt, 1 << 18]
+        t.level[2].N = 10_000_000                                       # c far beyond LDS: chunked again
+        t.nvals = 1 << 18
+        assert spt.spt_workspace_bytes(B.SPT_OP_TTV, t) < sizes[fmt, 1 << 18]
+
+
 def _status(fn, *args):
     try:
         fn(*args)
